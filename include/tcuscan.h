@@ -1,0 +1,122 @@
+/*
+ * tcuscan -- prefix sums on MI355X (gfx950) computed as products against all-ones
+ * triangular matrices on the MFMA units.
+ *
+ * The operation is the one the paper states in Section 1 (notation paragraph) and
+ * Section 2: given a vector x of size n, return its prefix sums
+ *
+ *     inclusive:  y[i] = x[0] + ... + x[i]            (the paper's default meaning of "scan")
+ *     exclusive:  y[0] = 0,  y[i] = x[0] + ... + x[i-1]   (the inclusive result shifted by one)
+ *
+ * Algorithm 1 (MatMulScan) computes it as local scans L_s * T of s-element columns
+ * (procedure BatchMatMul), a base-s up-sweep over block totals and a down-sweep that
+ * broadcast-adds the carries (matrix B_s).  This library runs level 0 on the MFMA
+ * units, the higher levels inside a workgroup on the vector unit (as Section 2.3
+ * suggests for the B_s step), and replaces the remaining levels -- and Section 2.2's
+ * "scan the segment totals, broadcast-add them" steps for n that is not a power of
+ * s -- by a single-pass carry chain between workgroups.  The result is the same
+ * prefix sum; zero-padding of the last tile is BatchMatMul's zero-pad.
+ *
+ * Plain C ABI.  Every pointer named d_* is a DEVICE pointer owned by the caller; the
+ * library allocates nothing and frees nothing.  Calls are asynchronous: they enqueue
+ * on `stream` (a hipStream_t passed as void*) and return; outputs are valid once the
+ * stream reaches that point.  No call blocks, prints, throws or exits.
+ */
+#ifndef TCUSCAN_H
+#define TCUSCAN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TCUSCAN_OK              = 0,
+    TCUSCAN_ERR_INVALID_ARG = 1, /* null pointer with work to do, misaligned pointer, in/out overlap rule broken */
+    TCUSCAN_ERR_UNSUPPORTED = 2, /* unknown dtype, size beyond the 32-bit tile index range                        */
+    TCUSCAN_ERR_WORKSPACE   = 3, /* workspace missing or smaller than tcuscan_workspace_bytes()                   */
+    TCUSCAN_ERR_HIP         = 4  /* the HIP runtime refused the launch                                            */
+} tcuscan_status_t;
+
+/* input element type -> output (= accumulator) element type */
+typedef enum {
+    TCUSCAN_I32_I32  = 0, /* int32 in, int32 out; sums are exact modulo 2^32 (four signed-byte planes on the i8 MFMA) */
+    TCUSCAN_F16_F32  = 1, /* IEEE half in, fp32 accumulate and out (f16 MFMA)                                        */
+    TCUSCAN_I8_I32   = 2, /* int8 in, int32 out (i8 MFMA); exact modulo 2^32                                         */
+    TCUSCAN_F32_F32  = 3, /* fp32 in, fp32 out (f32 MFMA)                                                            */
+    TCUSCAN_BF16_F32 = 4  /* bfloat16 in, fp32 accumulate and out (bf16 MFMA)                                        */
+} tcuscan_dtype_t;
+
+typedef void *tcuscan_stream_t; /* a hipStream_t; NULL is the default stream */
+
+/*
+ * Bytes of device workspace a call on `rows` rows of `cols` elements needs (0 when
+ * every row fits one workgroup tile).  The workspace holds the carry chain between
+ * workgroups (Algorithm 1's up-sweep rounds t >= 3 and Section 2.2 steps 2-3): one
+ * 8-byte status word per tile plus a 256-byte header.
+ *
+ * The caller zero-fills it ONCE after allocation (hipMemset, or tcuscan_workspace_init)
+ * and may then reuse it for any number of calls whose requirement is not larger;
+ * calls rearm it themselves.  Two calls that are in flight at the same time must not
+ * share a workspace.  After 2^30 - 2 calls on one workspace zero-fill it again.
+ */
+size_t tcuscan_workspace_bytes(size_t rows, size_t cols, tcuscan_dtype_t dt);
+
+/* Enqueue a fill kernel that zeroes the workspace (usable under stream capture). */
+tcuscan_status_t tcuscan_workspace_init(void *d_ws, size_t ws_bytes, tcuscan_stream_t stream);
+
+/*
+ * y <- inclusive prefix sums of x (Algorithm 1's input/output contract: same length,
+ * may be in place).
+ *   d_in   n elements of the input type, dense.  Aligned to the element size.
+ *   d_out  n elements of the output type, dense.  Aligned to 4 bytes.  May equal d_in
+ *          when input and output elements have the same size (I32_I32, F32_F32);
+ *          any other overlap is undefined.
+ *   n      element count; n == 0 returns TCUSCAN_OK and enqueues nothing.
+ *   d_ws, ws_bytes   workspace, see tcuscan_workspace_bytes(1, n, dt); may be NULL/0
+ *          when that is 0.
+ * 16-byte aligned d_in and d_out take the 128-bit load/store path; other alignments
+ * are accepted and run an element-wise path.
+ * Floating-point results are any valid fp32 summation order (MFMA accumulation order
+ * and the carry chain's grouping are not fixed), so they may differ in the last bits
+ * from run to run; integer results are unique.
+ */
+tcuscan_status_t tcuscan_inclusive(const void *d_in, void *d_out, size_t n, tcuscan_dtype_t dt,
+                                   void *d_ws, size_t ws_bytes, tcuscan_stream_t stream);
+
+/* y <- exclusive prefix sums of x: y[0] = 0, y[i] = inclusive[i-1].  The local scans
+ * use the strictly lower triangular all-ones matrix (L_s with a zero diagonal).
+ * Arguments as tcuscan_inclusive. */
+tcuscan_status_t tcuscan_exclusive(const void *d_in, void *d_out, size_t n, tcuscan_dtype_t dt,
+                                   void *d_ws, size_t ws_bytes, tcuscan_stream_t stream);
+
+/*
+ * Row-wise scans of a dense rows x cols matrix (row stride = cols), each row
+ * independent along the last dimension (Section 2.2 step 1: Algorithm 1 on each
+ * contiguous segment in parallel).  `exclusive` != 0 selects the exclusive scan.
+ * Workspace: tcuscan_workspace_bytes(rows, cols, dt).  rows == 0 or cols == 0 is OK
+ * and enqueues nothing.
+ */
+tcuscan_status_t tcuscan_batched(const void *d_in, void *d_out, size_t rows, size_t cols,
+                                 tcuscan_dtype_t dt, int exclusive,
+                                 void *d_ws, size_t ws_bytes, tcuscan_stream_t stream);
+
+/* Elements one workgroup tile covers for this dtype (rows no longer than this need no workspace). */
+size_t tcuscan_tile_elems(tcuscan_dtype_t dt);
+
+/*
+ * Copy the workspace's sticky fault word to *h_fault (host pointer) after draining
+ * `stream`.  Non-zero means a carry-chain wait ran into its spin bound in some earlier
+ * call (results of that call are invalid); this never happens in correct operation and
+ * exists so that a protocol failure ends in an error instead of a hung GPU.
+ */
+tcuscan_status_t tcuscan_workspace_fault(const void *d_ws, tcuscan_stream_t stream, unsigned *h_fault);
+
+/* Static, human-readable name of a status code. */
+const char *tcuscan_status_string(tcuscan_status_t st);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TCUSCAN_H */

@@ -1,0 +1,128 @@
+"""ctypes binding of libtcuscan.so -- argument marshalling only.
+
+Same names as the C entry points in ``include/tcuscan.h``.  Tensors are torch CUDA tensors
+(PyTorch is used for device memory and streams, nothing else); every step of the scan runs in
+the HIP kernels.  There is no CPU fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtcuscan.so")
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
+I32_I32, F16_F32, I8_I32, F32_F32, BF16_F32 = 0, 1, 2, 3, 4
+DTYPES = {"i32": I32_I32, "f16": F16_F32, "i8": I8_I32, "f32": F32_F32, "bf16": BF16_F32}
+
+EXPORTS = ["tcuscan_workspace_bytes", "tcuscan_workspace_init", "tcuscan_inclusive", "tcuscan_exclusive",
+           "tcuscan_batched", "tcuscan_tile_elems", "tcuscan_workspace_fault", "tcuscan_status_string"]
+
+_lib = None
+
+
+class TcuscanError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {status_string(code)} (status {code})")
+
+
+def load() -> ctypes.CDLL:
+    """Load the built library.  Building is a separate step (``python -m paper_2411_17887_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} not built; run `python -m paper_2411_17887_amd.build` (hipcc, gfx950)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz, ci = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+        L.tcuscan_workspace_bytes.argtypes = [sz, sz, ci]
+        L.tcuscan_workspace_bytes.restype = sz
+        L.tcuscan_tile_elems.argtypes = [ci]
+        L.tcuscan_tile_elems.restype = sz
+        L.tcuscan_workspace_init.argtypes = [vp, sz, vp]
+        L.tcuscan_inclusive.argtypes = [vp, vp, sz, ci, vp, sz, vp]
+        L.tcuscan_exclusive.argtypes = [vp, vp, sz, ci, vp, sz, vp]
+        L.tcuscan_batched.argtypes = [vp, vp, sz, sz, ci, ci, vp, sz, vp]
+        L.tcuscan_workspace_fault.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_uint)]
+        L.tcuscan_status_string.argtypes = [ci]
+        L.tcuscan_status_string.restype = ctypes.c_char_p
+        for f in ("tcuscan_workspace_init", "tcuscan_inclusive", "tcuscan_exclusive", "tcuscan_batched",
+                  "tcuscan_workspace_fault"):
+            getattr(L, f).restype = ci
+        _lib = L
+    return _lib
+
+
+def status_string(code: int) -> str:
+    return load().tcuscan_status_string(int(code)).decode()
+
+
+def _dt(dt) -> int:
+    return DTYPES[dt] if isinstance(dt, str) else int(dt)
+
+
+def workspace_bytes(rows: int, cols: int, dt) -> int:
+    return int(load().tcuscan_workspace_bytes(rows, cols, _dt(dt)))
+
+
+def tile_elems(dt) -> int:
+    return int(load().tcuscan_tile_elems(_dt(dt)))
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return int(getattr(stream, "cuda_stream", stream))
+
+
+def _ptr(t) -> int:
+    return 0 if t is None else int(t.data_ptr())
+
+
+def _ws_args(ws):
+    return (_ptr(ws), 0 if ws is None else ws.numel() * ws.element_size())
+
+
+def new_workspace(rows: int, cols: int, dt, device="cuda"):
+    """Allocate and zero a workspace tensor (None when the shape needs none)."""
+    import torch
+    nbytes = workspace_bytes(rows, cols, dt)
+    if nbytes == 0:
+        return None
+    return torch.zeros((nbytes + 7) // 8, dtype=torch.int64, device=device)
+
+
+def workspace_init(ws, stream=None) -> None:
+    p, nb = _ws_args(ws)
+    rc = load().tcuscan_workspace_init(p, nb, _stream(stream))
+    if rc != OK:
+        raise TcuscanError(rc, "tcuscan_workspace_init")
+
+
+def inclusive(x, out, dt, ws=None, stream=None, n=None) -> None:
+    rc = load().tcuscan_inclusive(_ptr(x), _ptr(out), x.numel() if n is None else n, _dt(dt), *_ws_args(ws), _stream(stream))
+    if rc != OK:
+        raise TcuscanError(rc, "tcuscan_inclusive")
+
+
+def exclusive(x, out, dt, ws=None, stream=None, n=None) -> None:
+    rc = load().tcuscan_exclusive(_ptr(x), _ptr(out), x.numel() if n is None else n, _dt(dt), *_ws_args(ws), _stream(stream))
+    if rc != OK:
+        raise TcuscanError(rc, "tcuscan_exclusive")
+
+
+def batched(x, out, rows: int, cols: int, dt, exclusive_scan: bool = False, ws=None, stream=None) -> None:
+    rc = load().tcuscan_batched(_ptr(x), _ptr(out), rows, cols, _dt(dt), int(bool(exclusive_scan)), *_ws_args(ws),
+                                _stream(stream))
+    if rc != OK:
+        raise TcuscanError(rc, "tcuscan_batched")
+
+
+def workspace_fault(ws, stream=None) -> int:
+    v = ctypes.c_uint(0)
+    rc = load().tcuscan_workspace_fault(_ptr(ws), _stream(stream), ctypes.byref(v))
+    if rc != OK:
+        raise TcuscanError(rc, "tcuscan_workspace_fault")
+    return int(v.value)
