@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the MatMulScan hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C5] [--no-others] [--no-cpu]
+
+A step is one pass of the whole hot path (tile load, MFMA local scans, in-workgroup up-sweep,
+carry chain between workgroups, down-sweep add, store) over one batch of seeded synthetic
+input that is already resident in HBM.  Prints ONE JSON line.  `value` is G elements/s of the
+headline workload; `roofline` prices the scan kernel against the 8 TB/s HBM peak using
+algorithmic bytes (input read once + output written once); `cpu_baseline` is the sequential
+CPU oracle timed on this host in the same run; `others` holds the remaining benchmark
+configurations measured the same way.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2411_17887_amd import inputs, tcuscan  # noqa: E402
+
+PEAK_HBM_GBPS = 8000.0
+IN_BYTES = {"i32": 4, "f16": 2, "i8": 1, "f32": 4, "bf16": 2}
+DESCR = {
+    "C2": "C2: inclusive scan, n=2^24, fp16 U[0,1) -> fp32",
+    "C3": "C3: exclusive scan, n=2^28, int8 {0,1} mask -> int32",
+    "C4": "C4: inclusive scan, n=100,000,007, fp32 N(0,1) -> fp32",
+    "C5": "C5: batched row-wise inclusive scan, 4096 x 65536 (2^28 elements), bf16 U[-1,1] -> fp32",
+}
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the same
+# counters on a plain copy of known size; see profiles/.  None = not measured for that workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def device_input(x: np.ndarray, kind: str):
+    import torch
+    if kind == "bf16":
+        return torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(x).cuda()
+
+
+def launch(cfg, d_in, d_out, ws):
+    kind = cfg["kind"]
+    if cfg["call"] == "inclusive":
+        tcuscan.inclusive(d_in, d_out, kind, ws=ws)
+    elif cfg["call"] == "exclusive":
+        tcuscan.exclusive(d_in, d_out, kind, ws=ws)
+    else:
+        tcuscan.batched(d_in, d_out, cfg["rows"], cfg["cols"], kind, ws=ws)
+
+
+def measure(name: str, steps: int, warmup: int, keep_host: bool = False):
+    """Times `steps` launches of workload `name`; returns a dict of figures (and the host input)."""
+    import torch
+    cfg = inputs.CONFIGS[name]
+    kind, n = cfg["kind"], cfg["rows"] * cfg["cols"]
+    x = inputs.make_config(name)
+    out_dt = torch.int32 if kind in ("i32", "i8") else torch.float32
+    bytes_per_elem = IN_BYTES[kind] + 4
+    # rotate over enough buffer pairs that the working set exceeds the 256 MB memory-side cache
+    pairs = max(1, min(8, int(np.ceil(1.2e9 / (n * bytes_per_elem)))))
+    d_in0 = device_input(x, kind)
+    d_ins = [d_in0] + [d_in0.clone() for _ in range(pairs - 1)]
+    d_outs = [torch.empty(n, dtype=out_dt, device="cuda") for _ in range(pairs)]
+    ws = tcuscan.new_workspace(cfg["rows"], cfg["cols"], kind)
+    for i in range(warmup):
+        launch(cfg, d_ins[i % pairs], d_outs[i % pairs], ws)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()                                   # same (current) stream the kernels are launched on
+    for i in range(steps):
+        launch(cfg, d_ins[i % pairs], d_outs[i % pairs], ws)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    kern_ms = ev0.elapsed_time(ev1) / steps
+    if ws is not None and tcuscan.workspace_fault(ws) != 0:
+        raise RuntimeError("carry chain fault flag set")
+    res = {
+        "workload": DESCR.get(name, name), "n": n, "dtype": kind, "bytes_per_elem": bytes_per_elem,
+        "ms_per_step": wall_ms, "kernel_ms": kern_ms,
+        "gelems_per_s": n / (wall_ms * 1e-3) / 1e9,
+        "achieved_GBps": n * bytes_per_elem / (kern_ms * 1e-3) / 1e9,
+        "buffer_pairs": pairs,
+    }
+    res["frac_of_peak"] = res["achieved_GBps"] / PEAK_HBM_GBPS
+    last = d_outs[(steps - 1) % pairs].cpu().numpy() if keep_host else None
+    del d_ins, d_outs, d_in0
+    torch.cuda.empty_cache()
+    return res, x, last
+
+
+def copy_ceiling_gbps() -> float:
+    """A plain device-to-device copy of 1 GiB (read + write counted), as a measured ceiling."""
+    import torch
+    a = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    b = torch.empty_like(a)
+    for _ in range(3):
+        b.copy_(a)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        b.copy_(a)
+    e1.record()
+    torch.cuda.synchronize()
+    return 2 * a.numel() * 4 / (e0.elapsed_time(e1) / 10 * 1e-3) / 1e9
+
+
+def cpu_baseline(name: str, x: np.ndarray, gpu_out):
+    """The sequential oracle as it stands, one core, on the same workload; also used to check the GPU output."""
+    import oracle
+    cfg = inputs.CONFIGS[name]
+    kind, rows, cols = cfg["kind"], cfg["rows"], cfg["cols"]
+    excl = cfg["call"] == "exclusive"
+    n = rows * cols
+    is_int = kind in ("i32", "i8")
+    out = np.zeros(n, dtype=np.int32 if is_int else np.float32)      # pre-faulted
+    best = float("inf")
+    for _ in range(3):
+        t0 = time.perf_counter()
+        if is_int:
+            oracle.scan_int_into(x, kind, out, exclusive=excl, rows=rows, cols=cols)
+        else:
+            oracle.scan_to_f32(x, kind, out, exclusive=excl, rows=rows, cols=cols)
+        best = min(best, time.perf_counter() - t0)
+    parity = None
+    if gpu_out is not None:
+        if is_int:
+            nb, _ = oracle.compare_int(x, kind, gpu_out, exclusive=excl, rows=rows, cols=cols)
+            parity = {"bit_exact": nb == 0}
+        else:
+            rep = oracle.compare_float(x, kind, gpu_out, exclusive=excl, rows=rows, cols=cols)
+            parity = {"E1": rep.e1, "tol": cfg["tol"], "ok": rep.ok(cfg["tol"])}
+    return {"value": n / best / 1e9, "unit": "G elements/s", "cores": 1, "kind": "oracle",
+            "sample": f"full workload ({n} elements), best of 3 passes, {best * 1e3:.0f} ms per pass",
+            "ms": best * 1e3}, parity
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="C5", choices=["C2", "C3", "C4", "C5"])
+    ap.add_argument("--no-others", action="store_true", help="measure only the headline workload")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU by design (the scan shards with one 8-byte exchange per GPU, "
+              "which is not built); run with --gpus 1", file=sys.stderr)
+        return 2
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    tcuscan.load()
+
+    head, x, last = measure(args.workload, args.steps, args.warmup, keep_host=not args.no_cpu)
+    cpu, parity = (None, None) if args.no_cpu else cpu_baseline(args.workload, x, last)
+    del x, last
+    others = {}
+    if not args.no_others:
+        for name in ["C2", "C3", "C4", "C5"]:
+            if name == args.workload:
+                continue
+            r, _, _ = measure(name, max(10, args.steps // 2), args.warmup)
+            others[name] = {k: r[k] for k in ("workload", "kernel_ms", "gelems_per_s", "achieved_GBps", "frac_of_peak")}
+    ceiling = copy_ceiling_gbps()
+
+    line = {
+        "metric": "G elements/s (and fraction of peak HBM bandwidth in roofline.frac), inclusive scan of 2^28 elements, 1x MI355X",
+        "value": head["gelems_per_s"], "unit": "G elements/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {"bf16": "bf16->f32", "f16": "f16->f32", "i8": "i8->i32", "f32": "f32", "i32": "i32"}[head["dtype"]],
+        "data": "synthetic (seeded SplitMix64 streams, resident in HBM before timing)",
+        "config": {"workload": head["workload"], "n": head["n"], "buffer_pairs_rotated": head["buffer_pairs"]},
+        "roofline": {"bound": "hbm", "achieved": head["achieved_GBps"], "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                     "frac": head["frac_of_peak"], "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+                     "kernel": "scan_kernel", "kernel_ms": head["kernel_ms"],
+                     "algorithmic_bytes_per_elem": head["bytes_per_elem"],
+                     "frac_of_measured_copy": head["achieved_GBps"] / ceiling},
+        "cpu_baseline": cpu,
+        "parity_of_timed_output": parity,
+        "copy_ceiling_GBps": ceiling,
+        "others": others,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -41,11 +41,9 @@ constexpr int kThreads = 64 * kWaves;
 
 // Workspace header (256 bytes), followed by one 64-bit status word per tile.
 struct WsHeader {
-    uint32_t ticket;   // next tile index to hand out
-    uint32_t done;     // tiles finished in the running call
     uint32_t epoch;    // number of completed calls (mod 2^30 - 1); tags the status words
     uint32_t fault;    // sticky: a look-back wait hit its spin bound
-    uint32_t pad[60];
+    uint32_t pad[62];
 };
 static_assert(sizeof(WsHeader) == 256, "header size");
 
@@ -308,22 +306,20 @@ __global__ __launch_bounds__(kThreads) void scan_kernel(Params P)
 
     __shared__ u32x4 stage[kWaves][kStage];
     __shared__ uint32_t s_wave_total[kWaves];
-    __shared__ uint32_t s_bcast[2];
+    __shared__ uint32_t s_bcast;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 15, j = lane >> 4;         // operand order: column, quarter (also output row group q)
 
-    // ---- which tile
+    // ---- which tile.  Tiles are taken in workgroup-index order: a tile only ever waits for tiles with
+    // a smaller index, which the hardware dispatched earlier (or at the same time), so the lowest
+    // unfinished tile is always running and the chain cannot stall.  (A shared ticket counter would
+    // guarantee the same without that assumption, but one contended atomic per tile caps the whole
+    // kernel at the device's single-address atomic rate.)  Status words carry the call's tag, so
+    // words left over from earlier calls read as "not published yet" and need no clearing.
     const bool chained = P.tiles_per_row > 1;
-    uint32_t tile = blockIdx.x, tag = 0;
-    if (chained) {
-        if (threadIdx.x == 0) {
-            s_bcast[0] = atomicAdd(&P.ws->ticket, 1u);
-            s_bcast[1] = __hip_atomic_load(&P.ws->epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
-        }
-        __syncthreads();
-        tile = s_bcast[0]; tag = s_bcast[1];
-    }
+    const uint32_t tile = blockIdx.x;
+    const uint32_t tag = chained ? __hip_atomic_load(&P.ws->epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u : 0u;
     const uint64_t row = tile / P.tiles_per_row;
     const uint32_t tr = tile - (uint32_t)row * P.tiles_per_row;
     const uint64_t row_base = row * P.cols;                          // first element of the row
@@ -420,10 +416,16 @@ __global__ __launch_bounds__(kThreads) void scan_kernel(Params P)
                     __hip_atomic_store(row_status + tr, status_word(tag, kStatePrefix, acc_bits(acc_add(prefix, wg_total))),
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-            if (lane == 0) s_bcast[0] = acc_bits(prefix);
+            if (lane == 0) {
+                s_bcast = acc_bits(prefix);
+                // Single row: once the last tile has resolved its look-back every tile of this call has
+                // read the epoch, so it can be advanced here.  Several rows: a trailing kernel does it.
+                if (P.rows == 1 && tr == P.tiles_per_row - 1)
+                    __hip_atomic_store(&P.ws->epoch, tag % kEpochMod, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
         __syncthreads();
-        prefix = acc_from_bits<A>(s_bcast[0]);
+        prefix = acc_from_bits<A>(s_bcast);
     }
 
     // ---- a5: down-sweep = add the carry of (row prefix, wavefront, tile, column) to the local scans
@@ -456,15 +458,12 @@ __global__ __launch_bounds__(kThreads) void scan_kernel(Params P)
         }
     }
 
-    // ---- rearm the workspace for the next call: the last tile to finish resets the counters
-    if (chained && threadIdx.x == 0) {
-        const uint32_t finished = atomicAdd(&P.ws->done, 1u);
-        if (finished == P.num_tiles - 1) {
-            __hip_atomic_store(&P.ws->ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&P.ws->done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&P.ws->epoch, tag % kEpochMod, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
+}
+
+// Advances the workspace epoch after a multi-row call (stream-ordered behind the scan kernel).
+__global__ void advance_epoch_kernel(WsHeader *ws)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) ws->epoch = (ws->epoch + 1u) % kEpochMod;
 }
 
 __global__ void fill_zero_kernel(uint32_t *p, size_t words)
@@ -483,10 +482,18 @@ size_t in_size(int dt) { return dt == TCUSCAN_I8_I32 ? 1 : (dt == TCUSCAN_F16_F3
 
 template <int DT> hipError_t launch_dt(const Params &P, bool excl, hipStream_t s)
 {
-    dim3 grid(P.num_tiles), block(kThreads);
-    if (excl) hipLaunchKernelGGL((scan_kernel<DT, kEPW, true>),  grid, block, 0, s, P);
-    else      hipLaunchKernelGGL((scan_kernel<DT, kEPW, false>), grid, block, 0, s, P);
-    return hipGetLastError();
+    // hipLaunchKernel reports this launch's own status (hipGetLastError could return a stale,
+    // unrelated code left behind by another library's polling calls).
+    Params p = P;
+    void *args[] = {&p};
+    const void *fn = excl ? (const void *)scan_kernel<DT, kEPW, true> : (const void *)scan_kernel<DT, kEPW, false>;
+    hipError_t e = hipLaunchKernel(fn, dim3(P.num_tiles), dim3(kThreads), args, 0, s);
+    if (e == hipSuccess && P.ws && P.rows > 1) {
+        WsHeader *ws = P.ws;
+        void *a2[] = {&ws};
+        e = hipLaunchKernel((const void *)advance_epoch_kernel, dim3(1), dim3(64), a2, 0, s);
+    }
+    return e;
 }
 
 tcuscan_status_t run(const void *d_in, void *d_out, size_t rows, size_t cols, int dt, int exclusive,
@@ -536,10 +543,12 @@ tcuscan_status_t tcuscan_workspace_init(void *d_ws, size_t ws_bytes, tcuscan_str
 {
     if (ws_bytes == 0) return TCUSCAN_OK;
     if (!d_ws || ((uintptr_t)d_ws % 8) != 0 || (ws_bytes % 4) != 0) return TCUSCAN_ERR_INVALID_ARG;
-    const size_t words = ws_bytes / 4;
-    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
-                       (uint32_t *)d_ws, words);
-    return hipGetLastError() == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
+    size_t words = ws_bytes / 4;
+    uint32_t *p = (uint32_t *)d_ws;
+    void *args[] = {&p, &words};
+    hipError_t e = hipLaunchKernel((const void *)fill_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256),
+                                   args, 0, (hipStream_t)stream);
+    return e == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
 }
 
 tcuscan_status_t tcuscan_inclusive(const void *d_in, void *d_out, size_t n, tcuscan_dtype_t dt,

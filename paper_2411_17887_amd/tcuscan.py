@@ -34,6 +34,10 @@ def load() -> ctypes.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise FileNotFoundError(f"{LIB_PATH} not built; run `python -m paper_2411_17887_amd.build` (hipcc, gfx950)")
+        # PyTorch ships its own HIP runtime; it must be the one already mapped when this library's
+        # dependency on libamdhip64 is resolved, or the process ends up with two runtimes that do not
+        # know each other's streams and allocations.
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, sz, ci = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
         L.tcuscan_workspace_bytes.argtypes = [sz, sz, ci]

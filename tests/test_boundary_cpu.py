@@ -1,0 +1,101 @@
+"""Host-side checks of the C-ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments with status codes before anything is enqueued."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2411_17887_amd import tcuscan
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "tcuscan.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tcuscan_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = tcuscan.load()
+    names = declared_symbols()
+    assert set(names) == set(tcuscan.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_status_strings():
+    assert tcuscan.status_string(tcuscan.OK) == "ok"
+    seen = {tcuscan.status_string(c) for c in range(5)}
+    assert len(seen) == 5 and "unknown status" not in seen
+    assert tcuscan.status_string(99) == "unknown status"
+
+
+def test_workspace_sizing():
+    for kind in tcuscan.DTYPES:
+        tile = tcuscan.tile_elems(kind)
+        assert tile >= 4096 and tile % 4096 == 0
+        assert tcuscan.workspace_bytes(1, tile, kind) == 0            # one tile per row: no carry chain
+        assert tcuscan.workspace_bytes(1000, tile, kind) == 0
+        assert tcuscan.workspace_bytes(1, tile + 1, kind) == 256 + 8 * 2
+        assert tcuscan.workspace_bytes(3, 5 * tile - 1, kind) == 256 + 8 * 15
+        assert tcuscan.workspace_bytes(0, 100, kind) == 0 and tcuscan.workspace_bytes(4, 0, kind) == 0
+    assert tcuscan.workspace_bytes(1, 1 << 20, 9) == 0 and tcuscan.tile_elems(9) == 0
+
+
+FAKE = 0x10000      # a non-null, 16-byte aligned address that is never dereferenced on these paths
+
+
+def call(fn, *a):
+    return getattr(tcuscan.load(), fn)(*a)
+
+
+def test_empty_inputs_are_ok_and_touch_nothing():
+    assert call("tcuscan_inclusive", 0, 0, 0, tcuscan.F16_F32, 0, 0, 0) == tcuscan.OK
+    assert call("tcuscan_exclusive", 0, 0, 0, tcuscan.I8_I32, 0, 0, 0) == tcuscan.OK
+    assert call("tcuscan_batched", 0, 0, 0, 128, tcuscan.F32_F32, 0, 0, 0, 0) == tcuscan.OK
+    assert call("tcuscan_batched", 0, 0, 128, 0, tcuscan.F32_F32, 1, 0, 0, 0) == tcuscan.OK
+    assert call("tcuscan_workspace_init", 0, 0, 0) == tcuscan.OK
+
+
+def test_bad_arguments_are_rejected_before_any_launch():
+    tile = tcuscan.tile_elems("f32")
+    # null pointers with work to do
+    assert call("tcuscan_inclusive", 0, FAKE, 10, tcuscan.F32_F32, 0, 0, 0) == tcuscan.ERR_INVALID_ARG
+    assert call("tcuscan_inclusive", FAKE, 0, 10, tcuscan.F32_F32, 0, 0, 0) == tcuscan.ERR_INVALID_ARG
+    # unknown dtype
+    assert call("tcuscan_inclusive", FAKE, FAKE, 10, 5, 0, 0, 0) == tcuscan.ERR_UNSUPPORTED
+    assert call("tcuscan_exclusive", FAKE, FAKE, 10, -1, 0, 0, 0) == tcuscan.ERR_UNSUPPORTED
+    # pointers not aligned to their element size
+    assert call("tcuscan_inclusive", FAKE + 2, FAKE + 64, 10, tcuscan.F32_F32, 0, 0, 0) == tcuscan.ERR_INVALID_ARG
+    assert call("tcuscan_inclusive", FAKE + 1, FAKE + 64, 10, tcuscan.F16_F32, 0, 0, 0) == tcuscan.ERR_INVALID_ARG
+    assert call("tcuscan_inclusive", FAKE, FAKE + 66, 10, tcuscan.I8_I32, 0, 0, 0) == tcuscan.ERR_INVALID_ARG
+    # in place only when element sizes match
+    assert call("tcuscan_inclusive", FAKE, FAKE, 10, tcuscan.F16_F32, 0, 0, 0) == tcuscan.ERR_INVALID_ARG
+    assert call("tcuscan_inclusive", FAKE, FAKE, 10, tcuscan.I8_I32, 0, 0, 0) == tcuscan.ERR_INVALID_ARG
+    # workspace missing / too small / misaligned when the row spans several tiles
+    n = 3 * tile
+    need = tcuscan.workspace_bytes(1, n, "f32")
+    assert need > 0
+    assert call("tcuscan_inclusive", FAKE, FAKE + (1 << 30), n, tcuscan.F32_F32, 0, 0, 0) == tcuscan.ERR_WORKSPACE
+    assert call("tcuscan_inclusive", FAKE, FAKE + (1 << 30), n, tcuscan.F32_F32, FAKE, need - 1, 0) == tcuscan.ERR_WORKSPACE
+    assert call("tcuscan_inclusive", FAKE, FAKE + (1 << 30), n, tcuscan.F32_F32, FAKE + 4, need, 0) == tcuscan.ERR_WORKSPACE
+    assert call("tcuscan_batched", FAKE, FAKE + (1 << 30), 2, n, tcuscan.F32_F32, 0, FAKE, need, 0) == tcuscan.ERR_WORKSPACE
+    # more tiles than the 31-bit tile index can name
+    assert call("tcuscan_batched", FAKE, FAKE + (1 << 30), 1 << 33, 16, tcuscan.I8_I32, 0, 0, 0, 0) == tcuscan.ERR_UNSUPPORTED
+    # workspace_init / workspace_fault argument checks
+    assert call("tcuscan_workspace_init", 0, 64, 0) == tcuscan.ERR_INVALID_ARG
+    assert call("tcuscan_workspace_init", FAKE + 4, 64, 0) == tcuscan.ERR_INVALID_ARG
+    assert call("tcuscan_workspace_fault", 0, 0, ctypes.byref(ctypes.c_uint(0))) == tcuscan.ERR_INVALID_ARG
+    assert call("tcuscan_workspace_fault", FAKE, 0, None) == tcuscan.ERR_INVALID_ARG
+
+
+def test_binding_raises_with_the_status_text():
+    with pytest.raises(tcuscan.TcuscanError) as e:
+        class T:                      # stands in for a tensor: only data_ptr / numel / element_size are marshalled
+            def data_ptr(self): return 0
+            def numel(self): return 5
+            def element_size(self): return 4
+        tcuscan.inclusive(T(), T(), "f32", stream=0)
+    assert e.value.code == tcuscan.ERR_INVALID_ARG and "invalid argument" in str(e.value)

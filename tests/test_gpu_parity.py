@@ -1,0 +1,242 @@
+"""GPU parity: the HIP path (through the C-ABI) against the CPU oracle, element by element.
+
+Bars: integers bit-exact; floats by the E1 metric (max |got - ref| / running L1 norm against the
+compensated fp64 oracle) <= 1e-3 for f16 / bf16 inputs and <= 1e-5 for f32 inputs at every size
+used here, including n = 100,000,007; integer-valued float inputs bit-exact at any size (every
+partial sum is exactly representable in fp32, so no summation order can change a bit).
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2411_17887_amd import inputs, tcuscan
+from gpu_util import run_scan, to_device
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f16": 1e-3, "bf16": 1e-3, "f32": 1e-5}
+INT_GEN = {"i32": inputs.int32_full, "i8": inputs.int8_full}
+TRI_GEN = {"f32": inputs.tri_f32, "f16": inputs.tri_f16, "bf16": inputs.tri_bf16_bits}
+RND_GEN = {"f32": inputs.f32_normal, "f16": inputs.f16_uniform01, "bf16": inputs.bf16_uniform_pm1}
+KINDS = ["i32", "f16", "i8", "f32", "bf16"]
+
+
+def check(x, kind, got, exclusive=False, rows=None, cols=None, exact_float=False, tol=None):
+    if kind in INT_GEN:
+        nb, fb = oracle.compare_int(x, kind, got, exclusive=exclusive, rows=rows, cols=cols)
+        assert nb == 0, f"{kind}: {nb} mismatches, first at {fb}"
+    elif exact_float:
+        nb, fb = oracle.compare_float_exact(x, kind, got, exclusive=exclusive, rows=rows, cols=cols)
+        assert nb == 0, f"{kind}: {nb} mismatches, first at {fb}"
+    else:
+        rep = oracle.compare_float(x, kind, got, exclusive=exclusive, rows=rows, cols=cols)
+        assert rep.ok(tol or TOL[kind]), f"{kind}: {rep}"
+        return rep
+
+
+def edge_sizes():
+    tile = tcuscan.tile_elems("f32")
+    return [1, 2, 15, 16, 17, 63, 64, 65, 255, 256, 257, 511, 512, 513, 1023, 1024, 1025, 2047, 2049, 4095, 4096, 4097,
+            tile - 1, tile, tile + 1, 2 * tile + 3, 65 * tile + 11, (1 << 20) + 7]
+
+
+@pytest.mark.parametrize("call", ["inclusive", "exclusive"])
+@pytest.mark.parametrize("kind", KINDS)
+def test_edge_sizes(kind, call):
+    ex = call == "exclusive"
+    for n in edge_sizes():
+        print("n =", n, flush=True)
+        if kind in INT_GEN:
+            x = INT_GEN[kind](n, 1000 + n)
+            check(x, kind, run_scan(x, kind, call), exclusive=ex)
+        else:
+            x = TRI_GEN[kind](n, 2000 + n)
+            check(x, kind, run_scan(x, kind, call), exclusive=ex, exact_float=True)
+            x = RND_GEN[kind](n, 3000 + n)
+            check(x, kind, run_scan(x, kind, call), exclusive=ex)
+
+
+def test_empty_input_enqueues_nothing():
+    import torch
+    out = torch.full((4,), 5, dtype=torch.int32, device="cuda")
+    tcuscan.inclusive(out, out, "i32", n=0)
+    tcuscan.batched(out, out, 0, 7, "i32")
+    torch.cuda.synchronize()
+    assert out.tolist() == [5, 5, 5, 5]
+
+
+# ----------------------------------------------------------------- the five configurations
+
+def test_config_C1_int32_4096():
+    x = inputs.make_config("C1")
+    got = run_scan(x, "i32", "inclusive")
+    assert np.array_equal(got, oracle.scan(x, "i32"))
+
+
+def test_config_C2_f16_2p24():
+    x = inputs.make_config("C2")
+    rep = check(x, "f16", run_scan(x, "f16", "inclusive"), tol=1e-3)
+    print("C2", rep, flush=True)
+
+
+def test_config_C3_mask_exclusive_2p28():
+    x = inputs.make_config("C3")
+    got = run_scan(x, "i8", "exclusive")
+    check(x, "i8", got, exclusive=True)
+    assert got[0] == 0 and int(got[-1]) + int(x[-1]) == int(x.astype(np.int64).sum())
+
+
+def test_config_C4_f32_normal_100000007():
+    x = inputs.make_config("C4")
+    rep = check(x, "f32", run_scan(x, "f32", "inclusive"), tol=1e-5)
+    print("C4", rep, "Einf", rep.einf, flush=True)
+
+
+def test_config_C5_batched_bf16_4096x65536():
+    c = inputs.CONFIGS["C5"]
+    x = inputs.make_config("C5")
+    got = run_scan(x, "bf16", "batched", rows=c["rows"], cols=c["cols"])
+    rep = check(x, "bf16", got, rows=c["rows"], cols=c["cols"], tol=1e-3)
+    print("C5", rep, flush=True)
+
+
+# ------------------------------------------------- structure checks at full size (bit-exact floats)
+
+@pytest.mark.parametrize("kind", ["f32", "f16", "bf16"])
+def test_integer_valued_floats_are_bit_exact_at_scale(kind):
+    n = (1 << 26) + 5
+    x = TRI_GEN[kind](n, 77)
+    check(x, kind, run_scan(x, kind, "inclusive"), exact_float=True)
+    check(x, kind, run_scan(x, kind, "exclusive"), exclusive=True, exact_float=True)
+
+
+def test_int32_full_range_wraps_modulo_2_32_at_scale():
+    n = (1 << 25) + 3
+    x = inputs.int32_full(n, 5)
+    check(x, "i32", run_scan(x, "i32", "inclusive"))
+    x = np.full(100000, 2 ** 31 - 1, dtype=np.int32)
+    check(x, "i32", run_scan(x, "i32", "exclusive"), exclusive=True)
+    x = np.full(100000, -2 ** 31, dtype=np.int32)
+    check(x, "i32", run_scan(x, "i32", "inclusive"))
+
+
+def test_int8_extremes():
+    for v in (-128, 127):
+        x = np.full(3 * 8192 + 5, v, dtype=np.int8)
+        check(x, "i8", run_scan(x, "i8", "inclusive"))
+        check(x, "i8", run_scan(x, "i8", "exclusive"), exclusive=True)
+
+
+def test_f16_subnormal_inputs_are_summed_not_flushed():
+    n = 50000
+    x = np.full(n, 1, dtype=np.uint16).view(np.float16)          # 2^-24, the smallest subnormal half
+    got = run_scan(x, "f16", "inclusive")
+    check(x, "f16", got, exact_float=True)
+
+
+# ------------------------------------------------------------------------------- batched
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("rows,cols", [(7, 333), (3, 8192), (5, 8193), (64, 20000), (33, 16385), (1000, 16), (2, 70001)])
+def test_batched_shapes(kind, rows, cols):
+    for call in ("batched", "batched_exclusive"):
+        ex = call.endswith("exclusive")
+        if kind in INT_GEN:
+            x = INT_GEN[kind](rows * cols, rows + cols)
+            check(x, kind, run_scan(x, kind, call, rows=rows, cols=cols), exclusive=ex, rows=rows, cols=cols)
+        else:
+            x = TRI_GEN[kind](rows * cols, rows + cols)
+            check(x, kind, run_scan(x, kind, call, rows=rows, cols=cols), exclusive=ex, rows=rows, cols=cols, exact_float=True)
+            x = RND_GEN[kind](rows * cols, rows * cols)
+            check(x, kind, run_scan(x, kind, call, rows=rows, cols=cols), exclusive=ex, rows=rows, cols=cols)
+
+
+def test_batched_row_equals_unbatched_scan_of_that_row():
+    rows, cols = 6, 30011
+    x = inputs.int32_small(rows * cols, 9)
+    got = run_scan(x, "i32", "batched", rows=rows, cols=cols).reshape(rows, cols)
+    for r in range(rows):
+        assert np.array_equal(got[r], run_scan(x[r * cols:(r + 1) * cols].copy(), "i32", "inclusive"))
+
+
+# ------------------------------------------------------------------ pointers and buffers
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_unaligned_pointers_take_the_elementwise_path(kind):
+    n = 3 * 8192 + 77
+    for in_off, out_off in [(1, 0), (0, 1), (3, 2), (5, 3)]:
+        if kind in INT_GEN:
+            x = INT_GEN[kind](n, in_off * 10 + out_off)
+            check(x, kind, run_scan(x, kind, "inclusive", in_offset=in_off, out_offset=out_off))
+        else:
+            x = TRI_GEN[kind](n, in_off * 10 + out_off)
+            check(x, kind, run_scan(x, kind, "exclusive", in_offset=in_off, out_offset=out_off), exclusive=True, exact_float=True)
+
+
+@pytest.mark.parametrize("kind", ["i32", "f32"])
+def test_in_place(kind):
+    n = 40 * 8192 + 123
+    x = (inputs.int32_full if kind == "i32" else inputs.tri_f32)(n, 3)
+    got = run_scan(x, kind, "inclusive", inplace=True)
+    check(x, kind, got, exact_float=(kind == "f32"))
+
+
+def test_workspace_is_reusable_across_calls_shapes_and_dtypes():
+    import torch
+    big = tcuscan.new_workspace(1, 1 << 22, "i8")
+    for rep in range(3):
+        for kind, n, call in [("i8", (1 << 22) - 5, "exclusive"), ("f16", 100000, "inclusive"), ("i32", 8193, "inclusive"),
+                              ("bf16", 1 << 21, "exclusive"), ("f32", 65536 * 3 + 1, "inclusive")]:
+            x = (INT_GEN.get(kind) or TRI_GEN[kind])(n, rep * 100 + n)
+            got = run_scan(x, kind, call, ws=big)
+            check(x, kind, got, exclusive=(call == "exclusive"), exact_float=kind not in INT_GEN)
+    x = inputs.int32_small(5 * 20000, 1)
+    check(x, "i32", run_scan(x, "i32", "batched", rows=5, cols=20000, ws=big), rows=5, cols=20000)
+    assert tcuscan.workspace_fault(big) == 0
+    torch.cuda.synchronize()
+
+
+def test_carry_chain_stress_repeated_calls_are_identical():
+    """Many tiles, many repetitions, one workspace: the look-back must give the same integers every time."""
+    import torch
+    n = 300 * 8192 + 1
+    for kind, gen in [("i8", inputs.mask_i8), ("i32", inputs.int32_full)]:
+        x = gen(n, 42)
+        ref = oracle.scan(x, kind)
+        d_in = to_device(x, kind)
+        d_ref = torch.from_numpy(ref).cuda()
+        ws = tcuscan.new_workspace(1, n, kind)
+        out = torch.empty(n, dtype=torch.int32, device="cuda")
+        for rep in range(120):
+            out.fill_(-1)
+            tcuscan.inclusive(d_in, out, kind, ws=ws)
+            assert torch.equal(out, d_ref), f"{kind}: repetition {rep} differs"
+        assert tcuscan.workspace_fault(ws) == 0
+
+
+def test_two_streams_with_their_own_workspaces():
+    import torch
+    n = 200 * 8192 + 9
+    xa, xb = inputs.mask_i8(n, 1), inputs.int8_full(n, 2)
+    da, db = to_device(xa, "i8"), to_device(xb, "i8")
+    oa, ob = torch.empty(n, dtype=torch.int32, device="cuda"), torch.empty(n, dtype=torch.int32, device="cuda")
+    wa, wb = tcuscan.new_workspace(1, n, "i8"), tcuscan.new_workspace(1, n, "i8")
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for _ in range(10):
+        tcuscan.exclusive(da, oa, "i8", ws=wa, stream=sa)
+        tcuscan.inclusive(db, ob, "i8", ws=wb, stream=sb)
+    torch.cuda.synchronize()
+    check(xa, "i8", oa.cpu().numpy(), exclusive=True)
+    check(xb, "i8", ob.cpu().numpy())
+
+
+def test_workspace_init_kernel_zeroes_the_buffer():
+    import torch
+    ws = torch.full((1000,), -1, dtype=torch.int64, device="cuda")
+    tcuscan.workspace_init(ws)
+    torch.cuda.synchronize()
+    assert int(ws.abs().sum()) == 0
+    n = 20 * 8192
+    x = inputs.mask_i8(n, 8)
+    check(x, "i8", run_scan(x, "i8", "inclusive", ws=ws))
