@@ -1,7 +1,10 @@
 // tcuscan: prefix sums as triangular-matrix products on the gfx950 MFMA units.
 //
 // One kernel does the whole scan in a single pass over HBM (read every input once,
-// write every output once).  Per workgroup tile:
+// write every output once).  Per workgroup tile the order of work is: load, reduce, publish
+// the tile total, wait for the carry, scan, store -- the registers that wait for the carry hold
+// the (narrow) inputs, not the (wide) outputs, so more elements per compute unit are in flight
+// while the carry chain's latency is being paid.
 //
 //   level 0  (Algorithm 1, up-sweep t = 0; BatchMatMul with L_s)
 //            A 1 KiB run of input is viewed column-major as 16 columns of S consecutive
@@ -10,7 +13,9 @@
 //            operand holds rows of the all-ones lower-triangular matrix (strictly lower
 //            for the exclusive scan).  Data reach the MFMA operand layout through LDS:
 //            global loads are 128-bit and fully coalesced, the LDS read-back gives lane
-//            (j, c) the j-th quarter of column c.
+//            (j, c) the j-th quarter of column c.  The tile total that is published early is
+//            the product with the all-ones matrix (every row of the result is the row of
+//            column totals) for the MFMA-native types, plain vector adds for 32-bit inputs.
 //   level 1  (up-sweep t = 1 and its down-sweep)   the 16 column totals of a tile sit in
 //            one 16-lane DPP row; a row_shr scan turns them into per-column carries.
 //   level 2  tile totals inside a wavefront, wavefront totals through LDS.
@@ -25,6 +30,10 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <atomic>
 
 #include "../../include/tcuscan.h"
 
@@ -41,15 +50,14 @@ constexpr int kThreads = 64 * kWaves;
 
 // Workspace header (256 bytes), followed by one 64-bit status word per tile.
 struct WsHeader {
-    uint32_t epoch;    // number of completed calls (mod 2^30 - 1); tags the status words
     uint32_t fault;    // sticky: a look-back wait hit its spin bound
-    uint32_t pad[62];
+    uint32_t pad[63];
 };
 static_assert(sizeof(WsHeader) == 256, "header size");
 
 constexpr uint32_t kStateAggregate = 1u;   // value = total of this tile only
 constexpr uint32_t kStatePrefix    = 2u;   // value = total of this tile and all before it in the row
-constexpr uint32_t kEpochMod       = (1u << 30) - 1u;
+constexpr uint32_t kTagMod         = (1u << 30) - 2u;   // tags run over 1 .. 2^30 - 2; 0 marks a zero-filled word
 constexpr uint32_t kSpinLimit      = 1u << 24;   // look-back polls before giving up (seconds of waiting)
 
 struct Params {
@@ -57,6 +65,7 @@ struct Params {
     void       *out;
     uint64_t    rows, cols;
     uint32_t    tiles_per_row, num_tiles;
+    uint32_t    tag;         // this call's tag for the status words
     WsHeader   *ws;          // null when tiles_per_row == 1
 };
 
@@ -80,13 +89,18 @@ template <> __device__ __forceinline__ uint32_t acc_from_bits<uint32_t>(uint32_t
 
 template <class A, int CTRL> __device__ __forceinline__ A dpp_shr(A v) { return acc_from_bits<A>(dpp0<CTRL>(acc_bits(v))); }
 
+// Sum over the 64 lanes, returned wave-uniform.  Row-local DPP shifts give every row's total in its
+// lane 15; row_bcast15 / row_bcast31 fold the four row totals into lane 63.
+constexpr int kRowBcast15 = 0x142, kRowBcast31 = 0x143;
 template <class A> __device__ __forceinline__ A wave_sum(A v)
 {
-    for (int m = 32; m >= 1; m >>= 1) {
-        uint32_t o = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(((__lane_id()) ^ m) << 2), (int)acc_bits(v));
-        v = acc_add(v, acc_from_bits<A>(o));
-    }
-    return v;
+    v = acc_add(v, dpp_shr<A, kRowShr + 1>(v));
+    v = acc_add(v, dpp_shr<A, kRowShr + 2>(v));
+    v = acc_add(v, dpp_shr<A, kRowShr + 4>(v));
+    v = acc_add(v, dpp_shr<A, kRowShr + 8>(v));
+    v = acc_add(v, acc_from_bits<A>((uint32_t)__builtin_amdgcn_update_dpp(0, (int)acc_bits(v), kRowBcast15, 0xa, 0xf, false)));
+    v = acc_add(v, acc_from_bits<A>((uint32_t)__builtin_amdgcn_update_dpp(0, (int)acc_bits(v), kRowBcast31, 0xc, 0xf, false)));
+    return acc_from_bits<A>((uint32_t)__builtin_amdgcn_readlane((int)acc_bits(v), 63));
 }
 
 template <class A> __device__ __forceinline__ A lane_value(A v, int src_lane)
@@ -110,18 +124,37 @@ template <class A> __device__ __forceinline__ A uniform_from_lane(A v, int lane)
 
 template <int DT> struct Tr;
 
+// 64-bit word whose `cnt` lowest slots of `bits_per_slot` bits hold `one` (a slot pattern repeated over
+// the whole word is passed in), the rest zero: the part of a row of the triangular operand that falls
+// into one half of a lane's granule.
+__device__ __forceinline__ uint64_t low_slots(uint64_t ones, int cnt, int slots, int bits_per_slot)
+{
+    cnt = cnt < 0 ? 0 : (cnt > slots ? slots : cnt);
+    return cnt == 0 ? 0ull : ones >> (bits_per_slot * (slots - cnt));
+}
+// number of leading K slots of lane group j that row `row` of the (strictly) lower triangular matrix covers
+__device__ __forceinline__ int covered(int row, int j, int g, bool excl) { return row - g * j + (excl ? 0 : 1); }
+
 template <> struct Tr<TCUSCAN_F16_F32> {
     using acc = float; using acc4 = f32x4;
     static constexpr int kEsz = 2, kG = 8, kBlocks = 2;
-    struct AConst { f16x8 a[kBlocks]; };
+    struct AConst { f16x8 a[kBlocks]; f16x8 ones; };
+    using red = f32x4;
+    static __device__ __forceinline__ red red_init() { return f32x4{0.f, 0.f, 0.f, 0.f}; }
+    static __device__ __forceinline__ red red_add(const AConst &A, red r, u32x4 b)
+    {   // J * T: every row of the product is the row of column totals; accumulated over the tiles
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(A.ones, bits<f16x8>(b), r, 0, 0, 0);
+    }
+    static __device__ __forceinline__ acc red_lane(red r, int lane) { return lane < 16 ? r[0] : 0.f; }
     static __device__ AConst make(int lane, bool excl)
     {
         AConst A; int m = lane & 15, j = lane >> 4;
-        for (int p = 0; p < kBlocks; ++p)
-            for (int i = 0; i < kG; ++i) {
-                int pos = kG * j + i, row = 16 * p + m;
-                A.a[p][i] = (_Float16)((excl ? pos < row : pos <= row) ? 1.0f : 0.0f);
-            }
+        A.ones = bits<f16x8>(u32x4{0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0x3C003C00u});
+        for (int p = 0; p < kBlocks; ++p) {
+            const int cnt = covered(16 * p + m, j, kG, excl);
+            const uint64_t lo = low_slots(0x3C003C003C003C00ull, cnt, 4, 16), hi = low_slots(0x3C003C003C003C00ull, cnt - 4, 4, 16);
+            A.a[p] = bits<f16x8>(u32x4{(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)});   // 1.0h
+        }
         return A;
     }
     static __device__ __forceinline__ void mma(const AConst &A, u32x4 b, int, bool, acc4 (&d)[kBlocks])
@@ -136,19 +169,22 @@ template <> struct Tr<TCUSCAN_F16_F32> {
 template <> struct Tr<TCUSCAN_BF16_F32> {
     using acc = float; using acc4 = f32x4;
     static constexpr int kEsz = 2, kG = 8, kBlocks = 2;
-    struct AConst { bf16x8 a[kBlocks]; };
+    struct AConst { bf16x8 a[kBlocks]; bf16x8 ones; };
+    using red = f32x4;
+    static __device__ __forceinline__ red red_init() { return f32x4{0.f, 0.f, 0.f, 0.f}; }
+    static __device__ __forceinline__ red red_add(const AConst &A, red r, u32x4 b)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(A.ones, bits<bf16x8>(b), r, 0, 0, 0);
+    }
+    static __device__ __forceinline__ acc red_lane(red r, int lane) { return lane < 16 ? r[0] : 0.f; }
     static __device__ AConst make(int lane, bool excl)
     {
         AConst A; int m = lane & 15, j = lane >> 4;
-        u32x4 w[kBlocks];
+        A.ones = bits<bf16x8>(u32x4{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u});
         for (int p = 0; p < kBlocks; ++p) {
-            w[p] = u32x4{0u, 0u, 0u, 0u};
-            for (int i = 0; i < kG; ++i) {
-                int pos = kG * j + i, row = 16 * p + m;
-                uint32_t one = (excl ? pos < row : pos <= row) ? 0x3F80u : 0u;     // bf16 1.0
-                w[p][i >> 1] |= one << (16 * (i & 1));
-            }
-            A.a[p] = bits<bf16x8>(w[p]);
+            const int cnt = covered(16 * p + m, j, kG, excl);
+            const uint64_t lo = low_slots(0x3F803F803F803F80ull, cnt, 4, 16), hi = low_slots(0x3F803F803F803F80ull, cnt - 4, 4, 16);
+            A.a[p] = bits<bf16x8>(u32x4{(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)});  // bf16 1.0
         }
         return A;
     }
@@ -164,17 +200,22 @@ template <> struct Tr<TCUSCAN_BF16_F32> {
 template <> struct Tr<TCUSCAN_I8_I32> {
     using acc = uint32_t; using acc4 = i32x4;
     static constexpr int kEsz = 1, kG = 16, kBlocks = 4;
-    struct AConst { i32x4 a[kBlocks]; };
+    struct AConst { i32x4 a[kBlocks]; i32x4 ones; };
+    using red = i32x4;
+    static __device__ __forceinline__ red red_init() { return i32x4{0, 0, 0, 0}; }
+    static __device__ __forceinline__ red red_add(const AConst &A, red r, u32x4 b)
+    {
+        return __builtin_amdgcn_mfma_i32_16x16x64_i8(A.ones, bits<i32x4>(b), r, 0, 0, 0);
+    }
+    static __device__ __forceinline__ acc red_lane(red r, int lane) { return lane < 16 ? (uint32_t)r[0] : 0u; }
     static __device__ AConst make(int lane, bool excl)
     {
         AConst A; int m = lane & 15, j = lane >> 4;
+        A.ones = i32x4{0x01010101, 0x01010101, 0x01010101, 0x01010101};
         for (int p = 0; p < kBlocks; ++p) {
-            A.a[p] = i32x4{0, 0, 0, 0};
-            for (int i = 0; i < kG; ++i) {
-                int pos = kG * j + i, row = 16 * p + m;
-                int one = (excl ? pos < row : pos <= row) ? 1 : 0;
-                A.a[p][i >> 2] |= one << (8 * (i & 3));
-            }
+            const int cnt = covered(16 * p + m, j, kG, excl);
+            const uint64_t lo = low_slots(0x0101010101010101ull, cnt, 8, 8), hi = low_slots(0x0101010101010101ull, cnt - 8, 8, 8);
+            A.a[p] = i32x4{(int)(uint32_t)lo, (int)(uint32_t)(lo >> 32), (int)(uint32_t)hi, (int)(uint32_t)(hi >> 32)};
         }
         return A;
     }
@@ -192,6 +233,13 @@ template <> struct Tr<TCUSCAN_F32_F32> {
     static constexpr int kEsz = 4, kG = 4, kBlocks = 1;
     // The K = 4 product p takes element p of every lane's granule: slot (j, p) <-> position 4j + p.
     struct AConst { float a[4]; };
+    using red = float;      // 32-bit inputs: the tile total is four vector adds per granule
+    static __device__ __forceinline__ red red_init() { return 0.f; }
+    static __device__ __forceinline__ red red_add(const AConst &, red r, u32x4 b)
+    {
+        return r + ((bits<float>(b[0]) + bits<float>(b[1])) + (bits<float>(b[2]) + bits<float>(b[3])));
+    }
+    static __device__ __forceinline__ acc red_lane(red r, int) { return r; }
     static __device__ AConst make(int lane, bool excl)
     {
         AConst A; int m = lane & 15, j = lane >> 4;
@@ -214,11 +262,15 @@ template <> struct Tr<TCUSCAN_I32_I32> {
     // scanned by an i8 MFMA and the planes are recombined with shifts.  The i8 MFMA is signed, so
     // byte b enters as b - 128 (bit 7 flipped) and 128 * (number of summed elements) is added back.
     struct AConst { long a; };
+    using red = uint32_t;
+    static __device__ __forceinline__ red red_init() { return 0u; }
+    static __device__ __forceinline__ red red_add(const AConst &, red r, u32x4 b) { return r + b[0] + b[1] + b[2] + b[3]; }
+    static __device__ __forceinline__ acc red_lane(red r, int) { return r; }
     static __device__ AConst make(int lane, bool excl)
     {
-        int m = lane & 15, j = lane >> 4; uint32_t lo = 0;
-        for (int i = 0; i < 4; ++i) { int pos = 4 * j + i; lo |= ((excl ? pos < m : pos <= m) ? 1u : 0u) << (8 * i); }
-        AConst A; A.a = (long)(uint64_t)lo;       // K slots 4..7 of every lane are unused (zero on both sides)
+        int m = lane & 15, j = lane >> 4;
+        const uint64_t lo = low_slots(0x01010101ull, covered(m, j, kG, excl), 4, 8);
+        AConst A; A.a = (long)lo;                 // K slots 4..7 of every lane are unused (zero on both sides)
         return A;
     }
     static __device__ __forceinline__ void mma(const AConst &A, u32x4 b, int lane, bool excl, acc4 (&d)[kBlocks])
@@ -254,40 +306,57 @@ __device__ __forceinline__ uint64_t status_word(uint32_t tag, uint32_t state, ui
 }
 
 // Exclusive prefix of tile `tr` of its row: sum of the totals of tiles 0 .. tr-1, found by walking
-// back over published status words 64 at a time.  Called by all 64 lanes of one wavefront.
+// back over published status words, kWindow = 64 * kDepth at a time.  Called by all 64 lanes of one
+// wavefront.  The walk can advance at most one window per status round trip, and tiles finish at a
+// rate of (memory bandwidth / tile bytes), so the window has to cover more tiles than finish during
+// one round trip or the chain throttles the kernel; all loads of a window are in flight together.
+constexpr int kDepth = 8;
 template <class A>
 __device__ A look_back(const uint64_t *row_status, int tr, uint32_t tag, WsHeader *ws)
 {
     const int lane = __lane_id();
     A sum = acc_from_bits<A>(0u);
-    for (int base = tr - 1; base >= 0; base -= 64) {
-        const int idx = base - lane;
-        uint32_t state = kStatePrefix, vbits = 0u;          // lanes before the row start count as "prefix 0"
-        if (idx >= 0) {
-            uint32_t spins = 0;
-            for (;;) {
-                uint64_t w = __hip_atomic_load(row_status + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                uint32_t f = (uint32_t)(w >> 32);
-                if ((f >> 2) == tag) { state = f & 3u; vbits = (uint32_t)w; break; }
-                if (++spins > kSpinLimit) {               // never in correct operation: give up instead of hanging
-                    __hip_atomic_store(&ws->fault, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    break;
-                }
-                __builtin_amdgcn_s_sleep(1);
-            }
+    for (int base = tr - 1; base >= 0; base -= 64 * kDepth) {
+        uint64_t w[kDepth];
+#pragma unroll
+        for (int u = 0; u < kDepth; ++u) {
+            const int idx = base - 64 * u - lane;
+            if (idx >= 0) w[u] = __hip_atomic_load(row_status + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        const uint64_t have_prefix = __ballot(state == kStatePrefix);   // never 0 in the last window
-        const int first = have_prefix ? __builtin_ctzll(have_prefix) : 63;
-        A v = acc_from_bits<A>(lane <= first ? vbits : 0u);
-        sum = acc_add(sum, wave_sum(v));
-        if (have_prefix) break;
+        // Take every total up to and including the nearest published prefix, skip everything behind it.
+        bool done = false;
+        A part = acc_from_bits<A>(0u);
+#pragma unroll
+        for (int u = 0; u < kDepth; ++u) {
+            const int idx = base - 64 * u - lane;
+            uint32_t state = kStatePrefix, vbits = 0u;          // lanes before the row start count as "prefix 0"
+            if (idx >= 0) {
+                uint32_t spins = 0;
+                for (;;) {
+                    uint32_t f = (uint32_t)(w[u] >> 32);
+                    if ((f >> 2) == tag) { state = f & 3u; vbits = (uint32_t)w[u]; break; }
+                    if (++spins > kSpinLimit) {               // never in correct operation: give up instead of hanging
+                        __hip_atomic_store(&ws->fault, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(1);
+                    w[u] = __hip_atomic_load(row_status + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+            const uint64_t have_prefix = __ballot(state == kStatePrefix);
+            const int first = have_prefix ? __builtin_ctzll(have_prefix) : 63;
+            if (!done && lane <= first) part = acc_add(part, acc_from_bits<A>(vbits));
+            done = done || have_prefix != 0;
+        }
+        sum = acc_add(sum, wave_sum(part));
+        if (done) break;
     }
     return sum;
 }
 
 // ----------------------------------------------------------------------------- kernel
 
-template <int DT, int EPW, bool EXCL>
+template <int DT, int NT, bool EXCL>
 __global__ __launch_bounds__(kThreads) void scan_kernel(Params P)
 {
     using T = Tr<DT>;
@@ -296,14 +365,15 @@ __global__ __launch_bounds__(kThreads) void scan_kernel(Params P)
     constexpr int kG = T::kG;                       // elements per input granule
     constexpr int kS = 4 * kG;                      // column length
     constexpr int kTileElems = 64 * kG;             // one MFMA tile = 1 KiB of input
-    constexpr int kTPW = EPW / kTileElems;          // MFMA tiles per wavefront
     constexpr int kBlocks = T::kBlocks;
-    constexpr int kOutGran = EPW / 4;               // output granules per wavefront
+    constexpr int kOutGran = kTileElems / 4;        // output granules per MFMA tile
     constexpr int kOutShift = (kS == 64) ? 4 : 3;
     constexpr int kStage = kOutGran + (kOutGran >> kOutShift) + 1;
-    static_assert(kTPW >= 1 && kTPW * kTileElems == EPW, "EPW must be a multiple of the MFMA tile");
-    constexpr uint32_t kWgElems = EPW * kWaves;
+    constexpr uint32_t kEPW = NT * kTileElems;      // elements per wavefront
+    constexpr uint32_t kWgElems = kEPW * kWaves;    // elements per workgroup tile
 
+    // One staging slot per wavefront, reused tile after tile.  A wavefront's LDS instructions execute
+    // in order, so "write tile t+1" can never overtake "read tile t"; no workgroup barrier is involved.
     __shared__ u32x4 stage[kWaves][kStage];
     __shared__ uint32_t s_wave_total[kWaves];
     __shared__ uint32_t s_bcast;
@@ -319,24 +389,22 @@ __global__ __launch_bounds__(kThreads) void scan_kernel(Params P)
     // words left over from earlier calls read as "not published yet" and need no clearing.
     const bool chained = P.tiles_per_row > 1;
     const uint32_t tile = blockIdx.x;
-    const uint32_t tag = chained ? __hip_atomic_load(&P.ws->epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u : 0u;
+    const uint32_t tag = P.tag;
     const uint64_t row = tile / P.tiles_per_row;
     const uint32_t tr = tile - (uint32_t)row * P.tiles_per_row;
     const uint64_t row_base = row * P.cols;                          // first element of the row
     const uint64_t tile_base = (uint64_t)tr * kWgElems;             // first element of the tile inside the row
-    const uint64_t wave_base = tile_base + (uint64_t)wave * EPW;    // first element of this wavefront's run
+    const uint64_t wave_base = tile_base + (uint64_t)wave * kEPW;   // first element of this wavefront's run
 
     const char *in_row  = (const char *)P.in + row_base * T::kEsz;
     char       *out_row = (char *)P.out + row_base * 4;
     const bool in_vec  = (((uintptr_t)in_row) & 15) == 0;
     const bool out_vec = (((uintptr_t)out_row) & 15) == 0;
 
-    const typename T::AConst Aop = T::make(lane, EXCL);
-
     // ---- a1: coalesced 128-bit loads, zero-filled past the end of the row (BatchMatMul's zero-pad)
-    u32x4 g[kTPW];
+    u32x4 g[NT];
 #pragma unroll
-    for (int t = 0; t < kTPW; ++t) {
+    for (int t = 0; t < NT; ++t) {
         const uint64_t e0 = wave_base + (uint64_t)t * kTileElems + (uint64_t)lane * kG;
         if (in_vec && e0 + kG <= P.cols) {
             g[t] = *(const u32x4 *)(in_row + e0 * T::kEsz);
@@ -355,37 +423,21 @@ __global__ __launch_bounds__(kThreads) void scan_kernel(Params P)
         }
     }
 
-    // ---- to operand order through LDS (wave-private region, no workgroup barrier needed)
-#pragma unroll
-    for (int t = 0; t < kTPW; ++t) stage[wave][padded<3>(64 * t + lane)] = g[t];
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    u32x4 b[kTPW];
-#pragma unroll
-    for (int t = 0; t < kTPW; ++t) b[t] = stage[wave][padded<3>(64 * t + 4 * c + j)];
+    const typename T::AConst Aop = T::make(lane, EXCL);
 
-    // ---- a2: local scans of every column on the MFMA unit;  a3: level 1 on DPP
-    A4 d[kTPW][kBlocks];
-    A colcarry[kTPW];       // exclusive prefix of the column totals inside the tile, per lane
-    A tile_off[kTPW];       // exclusive prefix of the tile totals inside the wavefront (uniform)
-    A wave_total = acc_from_bits<A>(0u);
+    // ---- to operand order through LDS, and the tile total (up-sweep of this tile in one step)
+    u32x4 b[NT];
+    typename T::red rsum = T::red_init();
 #pragma unroll
-    for (int t = 0; t < kTPW; ++t) {
-        T::mma(Aop, b[t], lane, EXCL, d[t]);
-        // column totals live in row S-1 = lanes 48..63, last register of the last block
-        A tot = acc_from_bits<A>((uint32_t)bits<u32x4>(d[t][kBlocks - 1])[3]);
-        if (EXCL) tot = acc_add(tot, T::last(b[t]));     // the strictly-lower product leaves the last element out
-        A e = dpp_shr<A, kRowShr + 1>(tot);              // shift by one column -> exclusive
-        e = acc_add(e, dpp_shr<A, kRowShr + 1>(e));
-        e = acc_add(e, dpp_shr<A, kRowShr + 2>(e));
-        e = acc_add(e, dpp_shr<A, kRowShr + 4>(e));
-        e = acc_add(e, dpp_shr<A, kRowShr + 8>(e));
-        const A ttot = uniform_from_lane(acc_add(e, tot), 63);
-        colcarry[t] = lane_value(e, 48 + c);             // row 3 -> all four rows
-        tile_off[t] = wave_total;
-        wave_total = acc_add(wave_total, ttot);
+    for (int t = 0; t < NT; ++t) {
+        stage[wave][padded<3>(lane)] = g[t];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        b[t] = stage[wave][padded<3>(4 * c + j)];
+        rsum = T::red_add(Aop, rsum, b[t]);
     }
+    const A wave_total = wave_sum(T::red_lane(rsum, lane));
 
     // ---- level 2: wavefront totals through LDS
     if (lane == 0) s_wave_total[wave] = acc_bits(wave_total);
@@ -416,54 +468,54 @@ __global__ __launch_bounds__(kThreads) void scan_kernel(Params P)
                     __hip_atomic_store(row_status + tr, status_word(tag, kStatePrefix, acc_bits(acc_add(prefix, wg_total))),
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-            if (lane == 0) {
-                s_bcast = acc_bits(prefix);
-                // Single row: once the last tile has resolved its look-back every tile of this call has
-                // read the epoch, so it can be advanced here.  Several rows: a trailing kernel does it.
-                if (P.rows == 1 && tr == P.tiles_per_row - 1)
-                    __hip_atomic_store(&P.ws->epoch, tag % kEpochMod, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
+            if (lane == 0) s_bcast = acc_bits(prefix);
         }
         __syncthreads();
         prefix = acc_from_bits<A>(s_bcast);
     }
 
-    // ---- a5: down-sweep = add the carry of (row prefix, wavefront, tile, column) to the local scans
-    const A wave_carry = acc_add(prefix, wave_off);
+    // ---- a2 + a3 + a5 + a6, tile by tile with a running carry
+    A carry = acc_add(prefix, wave_off);                 // everything before this wavefront's run
 #pragma unroll
-    for (int t = 0; t < kTPW; ++t) {
-        const A carry = acc_add(acc_add(wave_carry, tile_off[t]), colcarry[t]);
+    for (int t = 0; t < NT; ++t) {
+        // a2: local scans of the 16 columns on the MFMA unit
+        A4 d[kBlocks];
+        T::mma(Aop, b[t], lane, EXCL, d);
+        // a3: the column totals are row S-1 = lanes 48..63, last register of the last block
+        A tot = acc_from_bits<A>((uint32_t)bits<u32x4>(d[kBlocks - 1])[3]);
+        if (EXCL) tot = acc_add(tot, T::last(b[t]));     // the strictly-lower product leaves the last element out
+        A e = dpp_shr<A, kRowShr + 1>(tot);              // shift by one column -> exclusive
+        e = acc_add(e, dpp_shr<A, kRowShr + 1>(e));
+        e = acc_add(e, dpp_shr<A, kRowShr + 2>(e));
+        e = acc_add(e, dpp_shr<A, kRowShr + 4>(e));
+        e = acc_add(e, dpp_shr<A, kRowShr + 8>(e));
+        const A tile_total = uniform_from_lane(acc_add(e, tot), 63);
+        // a5: down-sweep = one add of (carry of the run so far + carry of the column) per output
+        const A cc = acc_add(carry, lane_value(e, 48 + c));      // row 3 -> all four rows
 #pragma unroll
         for (int p = 0; p < kBlocks; ++p) {
-            u32x4 v = bits<u32x4>(d[t][p]);
-            for (int r = 0; r < 4; ++r) v[r] = acc_bits(acc_add(carry, acc_from_bits<A>(v[r])));
+            u32x4 v = bits<u32x4>(d[p]);
+            for (int r = 0; r < 4; ++r) v[r] = acc_bits(acc_add(cc, acc_from_bits<A>(v[r])));
             // a6: stage in output order: rows 16p + 4q .. +3 of column c are 4 consecutive outputs
-            const int og = t * (kTileElems / 4) + (kS / 4) * c + 4 * p + j;
-            stage[wave][padded<kOutShift>(og)] = v;
+            stage[wave][padded<kOutShift>((kS / 4) * c + 4 * p + j)] = v;
         }
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
-    for (int k = 0; k < kOutGran / 64; ++k) {
-        const int og = 64 * k + lane;
-        const u32x4 v = stage[wave][padded<kOutShift>(og)];
-        const uint64_t e0 = wave_base + 4ull * og;
-        if (out_vec && e0 + 4 <= P.cols) {
-            *(u32x4 *)(out_row + e0 * 4) = v;
-        } else {
-            for (int r = 0; r < 4; ++r)
-                if (e0 + r < P.cols) ((uint32_t *)out_row)[e0 + r] = v[r];
+        for (int k = 0; k < kOutGran / 64; ++k) {
+            const int og = 64 * k + lane;
+            const u32x4 v = stage[wave][padded<kOutShift>(og)];
+            const uint64_t e0 = wave_base + (uint64_t)t * kTileElems + 4ull * og;
+            if (out_vec && e0 + 4 <= P.cols) {
+                __builtin_nontemporal_store(v, (u32x4 *)(out_row + e0 * 4));   // written once, never read back here
+            } else {
+                for (int r = 0; r < 4; ++r)
+                    if (e0 + r < P.cols) ((uint32_t *)out_row)[e0 + r] = v[r];
+            }
         }
+        carry = acc_add(carry, tile_total);
     }
-
-}
-
-// Advances the workspace epoch after a multi-row call (stream-ordered behind the scan kernel).
-__global__ void advance_epoch_kernel(WsHeader *ws)
-{
-    if (threadIdx.x == 0 && blockIdx.x == 0) ws->epoch = (ws->epoch + 1u) % kEpochMod;
 }
 
 __global__ void fill_zero_kernel(uint32_t *p, size_t words)
@@ -474,26 +526,69 @@ __global__ void fill_zero_kernel(uint32_t *p, size_t words)
 
 // ------------------------------------------------------------------------ host side
 
-constexpr int kEPW = 2048;                               // elements per wavefront
-constexpr size_t kTile = (size_t)kEPW * kWaves;          // elements per workgroup tile
+constexpr size_t kSmallTile = 8192;                      // elements per workgroup tile, small variant (all dtypes)
 
 bool valid_dtype(int dt) { return dt >= 0 && dt <= 4; }
 size_t in_size(int dt) { return dt == TCUSCAN_I8_I32 ? 1 : (dt == TCUSCAN_F16_F32 || dt == TCUSCAN_BF16_F32) ? 2 : 4; }
 
-template <int DT> hipError_t launch_dt(const Params &P, bool excl, hipStream_t s)
+// MFMA tiles per wavefront for the two tile sizes of each dtype.  The small one is 8192 elements per
+// workgroup for every dtype; the large one keeps 32 (8/16-bit inputs) or 64 (32-bit inputs) input
+// registers per lane waiting for the carry.
+template <int DT> struct Tiles;
+template <> struct Tiles<TCUSCAN_I8_I32>   { static constexpr int kSmall = 2, kLarge = 8;  };
+template <> struct Tiles<TCUSCAN_F16_F32>  { static constexpr int kSmall = 4, kLarge = 8;  };
+template <> struct Tiles<TCUSCAN_BF16_F32> { static constexpr int kSmall = 4, kLarge = 8;  };
+template <> struct Tiles<TCUSCAN_F32_F32>  { static constexpr int kSmall = 8, kLarge = 16; };
+template <> struct Tiles<TCUSCAN_I32_I32>  { static constexpr int kSmall = 8, kLarge = 16; };
+
+size_t large_tile(int dt)
+{
+    switch (dt) {
+    case TCUSCAN_I8_I32:   return (size_t)Tiles<TCUSCAN_I8_I32>::kLarge * 1024 * kWaves;
+    case TCUSCAN_F16_F32:
+    case TCUSCAN_BF16_F32: return (size_t)Tiles<TCUSCAN_F16_F32>::kLarge * 512 * kWaves;
+    default:               return (size_t)Tiles<TCUSCAN_F32_F32>::kLarge * 256 * kWaves;
+    }
+}
+
+// 0 = choose by shape, 1 = always small, 2 = always large (TCUSCAN_TILE=small|large, for measurements)
+int forced_variant()
+{
+    static const int v = [] {
+        const char *e = getenv("TCUSCAN_TILE");
+        if (!e) return 0;
+        return strcmp(e, "small") == 0 ? 1 : strcmp(e, "large") == 0 ? 2 : 0;
+    }();
+    return v;
+}
+
+bool use_large(int dt, size_t rows, size_t cols)
+{
+    const int f = forced_variant();
+    if (f) return f == 2 && cols > kSmallTile;
+    const size_t lt = large_tile(dt);
+    return cols >= 2 * lt && rows * ((cols + lt - 1) / lt) >= 512;
+}
+
+std::atomic<uint32_t> g_calls{0};
+
+template <int DT> hipError_t launch_dt(Params P, bool excl, bool large, hipStream_t s)
 {
     // hipLaunchKernel reports this launch's own status (hipGetLastError could return a stale,
     // unrelated code left behind by another library's polling calls).
-    Params p = P;
-    void *args[] = {&p};
-    const void *fn = excl ? (const void *)scan_kernel<DT, kEPW, true> : (const void *)scan_kernel<DT, kEPW, false>;
-    hipError_t e = hipLaunchKernel(fn, dim3(P.num_tiles), dim3(kThreads), args, 0, s);
-    if (e == hipSuccess && P.ws && P.rows > 1) {
-        WsHeader *ws = P.ws;
-        void *a2[] = {&ws};
-        e = hipLaunchKernel((const void *)advance_epoch_kernel, dim3(1), dim3(64), a2, 0, s);
-    }
-    return e;
+    void *args[] = {&P};
+    const void *fn;
+    if (large) fn = excl ? (const void *)scan_kernel<DT, Tiles<DT>::kLarge, true> : (const void *)scan_kernel<DT, Tiles<DT>::kLarge, false>;
+    else       fn = excl ? (const void *)scan_kernel<DT, Tiles<DT>::kSmall, true> : (const void *)scan_kernel<DT, Tiles<DT>::kSmall, false>;
+    return hipLaunchKernel(fn, dim3(P.num_tiles), dim3(kThreads), args, 0, s);
+}
+
+hipError_t launch_fill(void *d, size_t bytes, hipStream_t s)
+{
+    size_t words = bytes / 4;
+    uint32_t *p = (uint32_t *)d;
+    void *args[] = {&p, &words};
+    return hipLaunchKernel((const void *)fill_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), args, 0, s);
 }
 
 tcuscan_status_t run(const void *d_in, void *d_out, size_t rows, size_t cols, int dt, int exclusive,
@@ -504,23 +599,35 @@ tcuscan_status_t run(const void *d_in, void *d_out, size_t rows, size_t cols, in
     if (!d_in || !d_out) return TCUSCAN_ERR_INVALID_ARG;
     if (((uintptr_t)d_in % in_size(dt)) != 0 || ((uintptr_t)d_out % 4) != 0) return TCUSCAN_ERR_INVALID_ARG;
     if (d_in == d_out && in_size(dt) != 4) return TCUSCAN_ERR_INVALID_ARG;
-    const size_t tpr = (cols + kTile - 1) / kTile;
-    if (rows > 0x7FFFFFFFull / tpr) return TCUSCAN_ERR_UNSUPPORTED;     // tile index must fit 31 bits
+    if (rows > 0x7FFFFFFFull / ((cols + kSmallTile - 1) / kSmallTile)) return TCUSCAN_ERR_UNSUPPORTED;   // tile index: 31 bits
     const size_t need = tcuscan_workspace_bytes(rows, cols, (tcuscan_dtype_t)dt);
     if (need && (!d_ws || ws_bytes < need || ((uintptr_t)d_ws % 8) != 0)) return TCUSCAN_ERR_WORKSPACE;
 
+    const bool large = use_large(dt, rows, cols);
+    const size_t tile = large ? large_tile(dt) : kSmallTile;
+    const size_t tpr = (cols + tile - 1) / tile;
+    hipStream_t s = (hipStream_t)stream;
     Params P;
     P.in = d_in; P.out = d_out; P.rows = rows; P.cols = cols;
     P.tiles_per_row = (uint32_t)tpr; P.num_tiles = (uint32_t)(rows * tpr);
     P.ws = need ? (WsHeader *)d_ws : nullptr;
-    hipStream_t s = (hipStream_t)stream;
+    // Every call gets a fresh tag, so status words of earlier calls are stale by construction.  A call
+    // recorded into a graph is replayed with the SAME tag; it therefore clears its status words first
+    // (with a fill kernel, which a graph replays correctly).
+    P.tag = g_calls.fetch_add(1u, std::memory_order_relaxed) % kTagMod + 1u;
+    if (P.ws && tpr > 1) {
+        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(s, &cs) != hipSuccess) { (void)hipGetLastError(); cs = hipStreamCaptureStatusNone; }
+        if (cs == hipStreamCaptureStatusActive &&
+            launch_fill((char *)d_ws + sizeof(WsHeader), 8 * rows * tpr, s) != hipSuccess) return TCUSCAN_ERR_HIP;
+    }
     hipError_t e;
     switch (dt) {
-    case TCUSCAN_I32_I32:  e = launch_dt<TCUSCAN_I32_I32>(P, exclusive != 0, s); break;
-    case TCUSCAN_F16_F32:  e = launch_dt<TCUSCAN_F16_F32>(P, exclusive != 0, s); break;
-    case TCUSCAN_I8_I32:   e = launch_dt<TCUSCAN_I8_I32>(P, exclusive != 0, s); break;
-    case TCUSCAN_F32_F32:  e = launch_dt<TCUSCAN_F32_F32>(P, exclusive != 0, s); break;
-    default:               e = launch_dt<TCUSCAN_BF16_F32>(P, exclusive != 0, s); break;
+    case TCUSCAN_I32_I32:  e = launch_dt<TCUSCAN_I32_I32>(P, exclusive != 0, large, s); break;
+    case TCUSCAN_F16_F32:  e = launch_dt<TCUSCAN_F16_F32>(P, exclusive != 0, large, s); break;
+    case TCUSCAN_I8_I32:   e = launch_dt<TCUSCAN_I8_I32>(P, exclusive != 0, large, s); break;
+    case TCUSCAN_F32_F32:  e = launch_dt<TCUSCAN_F32_F32>(P, exclusive != 0, large, s); break;
+    default:               e = launch_dt<TCUSCAN_BF16_F32>(P, exclusive != 0, large, s); break;
     }
     return e == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
 }
@@ -529,12 +636,12 @@ tcuscan_status_t run(const void *d_in, void *d_out, size_t rows, size_t cols, in
 
 extern "C" {
 
-size_t tcuscan_tile_elems(tcuscan_dtype_t dt) { return valid_dtype((int)dt) ? kTile : 0; }
+size_t tcuscan_tile_elems(tcuscan_dtype_t dt) { return valid_dtype((int)dt) ? kSmallTile : 0; }
 
 size_t tcuscan_workspace_bytes(size_t rows, size_t cols, tcuscan_dtype_t dt)
 {
     if (!valid_dtype((int)dt) || rows == 0 || cols == 0) return 0;
-    const size_t tpr = (cols + kTile - 1) / kTile;
+    const size_t tpr = (cols + kSmallTile - 1) / kSmallTile;
     if (tpr <= 1) return 0;
     return sizeof(WsHeader) + 8 * rows * tpr;
 }
@@ -543,12 +650,7 @@ tcuscan_status_t tcuscan_workspace_init(void *d_ws, size_t ws_bytes, tcuscan_str
 {
     if (ws_bytes == 0) return TCUSCAN_OK;
     if (!d_ws || ((uintptr_t)d_ws % 8) != 0 || (ws_bytes % 4) != 0) return TCUSCAN_ERR_INVALID_ARG;
-    size_t words = ws_bytes / 4;
-    uint32_t *p = (uint32_t *)d_ws;
-    void *args[] = {&p, &words};
-    hipError_t e = hipLaunchKernel((const void *)fill_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256),
-                                   args, 0, (hipStream_t)stream);
-    return e == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
+    return launch_fill(d_ws, ws_bytes, (hipStream_t)stream) == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
 }
 
 tcuscan_status_t tcuscan_inclusive(const void *d_in, void *d_out, size_t n, tcuscan_dtype_t dt,
