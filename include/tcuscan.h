@@ -57,9 +57,12 @@ typedef void *tcuscan_stream_t; /* a hipStream_t; NULL is the default stream */
  * 8-byte status word per tile plus a 256-byte header.
  *
  * The caller zero-fills it ONCE after allocation (hipMemset, or tcuscan_workspace_init)
- * and may then reuse it for any number of calls whose requirement is not larger;
- * calls rearm it themselves.  Two calls that are in flight at the same time must not
- * share a workspace.  After 2^30 - 2 calls on one workspace zero-fill it again.
+ * and may then reuse it for any number of calls whose requirement is not larger: every
+ * call tags its status words with a fresh per-process call number, so older words read
+ * as "not published".  A call recorded by stream capture is replayed with the tag it
+ * was recorded with and therefore clears its status words first (one extra fill kernel
+ * in the graph).  Two calls that are in flight at the same time must not share a
+ * workspace.  After 2^30 - 2 library calls in one process, zero-fill workspaces again.
  */
 size_t tcuscan_workspace_bytes(size_t rows, size_t cols, tcuscan_dtype_t dt);
 
@@ -102,8 +105,20 @@ tcuscan_status_t tcuscan_batched(const void *d_in, void *d_out, size_t rows, siz
                                  tcuscan_dtype_t dt, int exclusive,
                                  void *d_ws, size_t ws_bytes, tcuscan_stream_t stream);
 
-/* Elements one workgroup tile covers for this dtype (rows no longer than this need no workspace). */
+/* Elements the small workgroup tile covers (rows no longer than this need no workspace), and the
+ * large tile that long inputs use (more elements wait in registers per compute unit while the
+ * carry chain's latency is paid).  Both are multiples of s^2 = 256: a tile is a whole number of
+ * BatchMatMul chunks. */
 size_t tcuscan_tile_elems(tcuscan_dtype_t dt);
+size_t tcuscan_large_tile_elems(tcuscan_dtype_t dt);
+
+/*
+ * Tile-size policy, process-wide: 0 = choose by shape (default: the large tile when a row spans at
+ * least two of them and the call has at least 512 tiles), 1 = always the small tile, 2 = the large
+ * tile for every row longer than a small tile.  A measurement and test knob; results do not depend
+ * on it beyond floating-point summation order.
+ */
+tcuscan_status_t tcuscan_set_tile_policy(int policy);
 
 /*
  * Copy the workspace's sticky fault word to *h_fault (host pointer) after draining

@@ -30,8 +30,6 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-#include <stdlib.h>
-#include <string.h>
 
 #include <atomic>
 
@@ -551,20 +549,12 @@ size_t large_tile(int dt)
     }
 }
 
-// 0 = choose by shape, 1 = always small, 2 = always large (TCUSCAN_TILE=small|large, for measurements)
-int forced_variant()
-{
-    static const int v = [] {
-        const char *e = getenv("TCUSCAN_TILE");
-        if (!e) return 0;
-        return strcmp(e, "small") == 0 ? 1 : strcmp(e, "large") == 0 ? 2 : 0;
-    }();
-    return v;
-}
+// 0 = choose by shape, 1 = always the small tile, 2 = the large tile whenever a row is longer than a small one
+std::atomic<int> g_tile_policy{0};
 
 bool use_large(int dt, size_t rows, size_t cols)
 {
-    const int f = forced_variant();
+    const int f = g_tile_policy.load(std::memory_order_relaxed);
     if (f) return f == 2 && cols > kSmallTile;
     const size_t lt = large_tile(dt);
     return cols >= 2 * lt && rows * ((cols + lt - 1) / lt) >= 512;
@@ -637,6 +627,15 @@ tcuscan_status_t run(const void *d_in, void *d_out, size_t rows, size_t cols, in
 extern "C" {
 
 size_t tcuscan_tile_elems(tcuscan_dtype_t dt) { return valid_dtype((int)dt) ? kSmallTile : 0; }
+
+size_t tcuscan_large_tile_elems(tcuscan_dtype_t dt) { return valid_dtype((int)dt) ? large_tile((int)dt) : 0; }
+
+tcuscan_status_t tcuscan_set_tile_policy(int policy)
+{
+    if (policy < 0 || policy > 2) return TCUSCAN_ERR_INVALID_ARG;
+    g_tile_policy.store(policy, std::memory_order_relaxed);
+    return TCUSCAN_OK;
+}
 
 size_t tcuscan_workspace_bytes(size_t rows, size_t cols, tcuscan_dtype_t dt)
 {

@@ -17,7 +17,8 @@ I32_I32, F16_F32, I8_I32, F32_F32, BF16_F32 = 0, 1, 2, 3, 4
 DTYPES = {"i32": I32_I32, "f16": F16_F32, "i8": I8_I32, "f32": F32_F32, "bf16": BF16_F32}
 
 EXPORTS = ["tcuscan_workspace_bytes", "tcuscan_workspace_init", "tcuscan_inclusive", "tcuscan_exclusive",
-           "tcuscan_batched", "tcuscan_tile_elems", "tcuscan_workspace_fault", "tcuscan_status_string"]
+           "tcuscan_batched", "tcuscan_tile_elems", "tcuscan_large_tile_elems", "tcuscan_set_tile_policy",
+           "tcuscan_workspace_fault", "tcuscan_status_string"]
 
 _lib = None
 
@@ -44,6 +45,10 @@ def load() -> ctypes.CDLL:
         L.tcuscan_workspace_bytes.restype = sz
         L.tcuscan_tile_elems.argtypes = [ci]
         L.tcuscan_tile_elems.restype = sz
+        L.tcuscan_large_tile_elems.argtypes = [ci]
+        L.tcuscan_large_tile_elems.restype = sz
+        L.tcuscan_set_tile_policy.argtypes = [ci]
+        L.tcuscan_set_tile_policy.restype = ci
         L.tcuscan_workspace_init.argtypes = [vp, sz, vp]
         L.tcuscan_inclusive.argtypes = [vp, vp, sz, ci, vp, sz, vp]
         L.tcuscan_exclusive.argtypes = [vp, vp, sz, ci, vp, sz, vp]
@@ -72,6 +77,19 @@ def workspace_bytes(rows: int, cols: int, dt) -> int:
 
 def tile_elems(dt) -> int:
     return int(load().tcuscan_tile_elems(_dt(dt)))
+
+
+def large_tile_elems(dt) -> int:
+    return int(load().tcuscan_large_tile_elems(_dt(dt)))
+
+
+TILE_AUTO, TILE_SMALL, TILE_LARGE = 0, 1, 2
+
+
+def set_tile_policy(policy: int) -> None:
+    rc = load().tcuscan_set_tile_policy(int(policy))
+    if rc != OK:
+        raise TcuscanError(rc, "tcuscan_set_tile_policy")
 
 
 def _stream(stream) -> int:

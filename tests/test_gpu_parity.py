@@ -240,3 +240,90 @@ def test_workspace_init_kernel_zeroes_the_buffer():
     n = 20 * 8192
     x = inputs.mask_i8(n, 8)
     check(x, "i8", run_scan(x, "i8", "inclusive", ws=ws))
+
+
+# ------------------------------------------------------------ both tile sizes, forced
+
+@pytest.fixture
+def tile_policy():
+    yield tcuscan.set_tile_policy
+    tcuscan.set_tile_policy(tcuscan.TILE_AUTO)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_large_tile_edges(kind, tile_policy):
+    """Sizes around multiples of the large tile, with the large tile forced, inclusive and exclusive."""
+    tile_policy(tcuscan.TILE_LARGE)
+    lt = tcuscan.large_tile_elems(kind)
+    assert lt % 8192 == 0 and lt > 8192
+    for n in [8193, lt - 1, lt, lt + 1, 2 * lt - 3, 3 * lt + lt // 2 + 5, 70 * lt + 4097]:
+        print("n =", n, flush=True)
+        for call in ("inclusive", "exclusive"):
+            ex = call == "exclusive"
+            if kind in INT_GEN:
+                x = INT_GEN[kind](n, n + 1)
+                check(x, kind, run_scan(x, kind, call), exclusive=ex)
+            else:
+                x = TRI_GEN[kind](n, n + 2)
+                check(x, kind, run_scan(x, kind, call), exclusive=ex, exact_float=True)
+                x = RND_GEN[kind](n, n + 3)
+                check(x, kind, run_scan(x, kind, call), exclusive=ex)
+
+
+@pytest.mark.parametrize("policy", [1, 2])
+@pytest.mark.parametrize("kind", KINDS)
+def test_tile_policies_give_the_same_integers(kind, policy, tile_policy):
+    tile_policy(policy)
+    rows, cols = 5, 3 * tcuscan.large_tile_elems(kind) + 777
+    if kind in INT_GEN:
+        x = INT_GEN[kind](rows * cols, policy)
+        check(x, kind, run_scan(x, kind, "batched", rows=rows, cols=cols), rows=rows, cols=cols)
+    else:
+        x = TRI_GEN[kind](rows * cols, policy)
+        check(x, kind, run_scan(x, kind, "batched_exclusive", rows=rows, cols=cols), exclusive=True, rows=rows, cols=cols,
+              exact_float=True)
+
+
+def test_auto_policy_picks_the_large_tile_only_for_long_inputs():
+    # observable through results only: both must be right; the sizes sit on either side of the switch
+    for kind in ("i8", "f32"):
+        lt = tcuscan.large_tile_elems(kind)
+        for n in (512 * lt - 1, 512 * lt + 1):
+            x = (INT_GEN.get(kind) or TRI_GEN[kind])(n, 7)
+            check(x, kind, run_scan(x, kind, "inclusive"), exact_float=kind not in INT_GEN)
+
+
+# ------------------------------------------------------------------------ graph capture
+
+def test_graph_capture_replays_match_eager():
+    """A captured call is replayed with its recorded tag; the library records a fill kernel in front of it
+    so stale status words of the previous replay cannot be mistaken for fresh ones."""
+    import torch
+    n = 100 * 8192 + 321
+    kind = "i8"
+    ws = tcuscan.new_workspace(1, n, kind)
+    d_in = torch.zeros(n, dtype=torch.int8, device="cuda")
+    d_out = torch.empty(n, dtype=torch.int32, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        tcuscan.inclusive(d_in, d_out, kind, ws=ws, stream=side)          # warm-up outside capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        tcuscan.inclusive(d_in, d_out, kind, ws=ws, stream=side)
+    eager_out = torch.empty_like(d_out)
+    for rep in range(5):
+        x = inputs.int8_full(n, 100 + rep)
+        d_in.copy_(torch.from_numpy(x).cuda())
+        d_out.fill_(-1)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        check(x, kind, d_out.cpu().numpy())
+        # eager work on the same workspace between the replays
+        tcuscan.exclusive(d_in, eager_out, kind, ws=ws)
+        torch.cuda.synchronize()
+        check(x, kind, eager_out.cpu().numpy(), exclusive=True)
+    assert tcuscan.workspace_fault(ws) == 0
