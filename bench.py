@@ -35,8 +35,8 @@ DESCR = {
     "C5": "C5: batched row-wise inclusive scan, 4096 x 65536 (2^28 elements), bf16 U[-1,1] -> fp32",
 }
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the same
-# counters on a plain copy of known size; see profiles/.  None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {}
+# counters on a plain 1 GiB device copy (fetch x2.000, write x1.000); profiles/scan_kernel_bench_default.md.
+MEASURED_TRAFFIC_BYTES = {"C5": 1614448727, "C3": 1351234539, "C4": 805598700, "C2": 101483867}
 
 
 def device_input(x: np.ndarray, kind: str):
@@ -153,6 +153,8 @@ def main() -> int:
     ap.add_argument("--workload", default="C5", choices=["C2", "C3", "C4", "C5"])
     ap.add_argument("--no-others", action="store_true", help="measure only the headline workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--copy-only", action="store_true",
+                    help="run only the plain 1 GiB device copy (calibrates the HBM byte counters of rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (the scan shards with one 8-byte exchange per GPU, "
@@ -163,6 +165,9 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     tcuscan.load()
+    if args.copy_only:
+        print(json.dumps({"copy_GBps": copy_ceiling_gbps(), "bytes_read": 1 << 30, "bytes_written": 1 << 30}))
+        return 0
 
     head, x, last = measure(args.workload, args.steps, args.warmup, keep_host=not args.no_cpu)
     cpu, parity = (None, None) if args.no_cpu else cpu_baseline(args.workload, x, last)
