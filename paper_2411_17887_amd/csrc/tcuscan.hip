@@ -32,8 +32,6 @@
 #include <stdint.h>
 
 #include <atomic>
-#include <map>
-#include <mutex>
 
 #include "../../include/tcuscan.h"
 
@@ -519,217 +517,6 @@ __global__ __launch_bounds__(kThreads) void scan_kernel(Params P)
     }
 }
 
-// ------------------------------------------------------------- persistent, pipelined kernel
-//
-// Same per-tile work as scan_kernel, different schedule.  The grid is sized so that every workgroup
-// is resident at once; workgroup w owns tiles w, w + G, w + 2G, ...  Per iteration a workgroup runs
-//
-//     reduce + publish the total of its NEXT tile, start the loads of the tile after that,
-//     then look back for its CURRENT tile, then scan + store the current tile.
-//
-// The total of a tile is therefore published one whole iteration before anyone needs it (every
-// other workgroup does the same), so a look-back finds its predecessors' words already visible, and
-// while it waits the workgroup has loads in flight.  The registers that bridge the gap hold inputs.
-
-template <int DT, int NT> struct TileCtx {
-    uint64_t wave_base;      // first element of this wavefront's run inside the row
-    uint64_t cols;
-    const char *in_row;
-    char *out_row;
-    uint64_t *row_status;
-    uint32_t tr;
-    bool in_vec, out_vec;
-};
-
-template <int DT, int NT>
-__device__ __forceinline__ TileCtx<DT, NT> tile_ctx(const Params &P, uint32_t tile, int wave)
-{
-    using T = Tr<DT>;
-    constexpr uint32_t kEPW = NT * 64 * T::kG;
-    TileCtx<DT, NT> c;
-    const uint32_t row = tile / P.tiles_per_row;
-    c.tr = tile - row * P.tiles_per_row;
-    const uint64_t row_base = (uint64_t)row * P.cols;
-    c.wave_base = (uint64_t)c.tr * (kEPW * kWaves) + (uint64_t)wave * kEPW;
-    c.cols = P.cols;
-    c.in_row = (const char *)P.in + row_base * T::kEsz;
-    c.out_row = (char *)P.out + row_base * 4;
-    c.in_vec = (((uintptr_t)c.in_row) & 15) == 0;
-    c.out_vec = (((uintptr_t)c.out_row) & 15) == 0;
-    c.row_status = P.ws ? (uint64_t *)(P.ws + 1) + (uint64_t)row * P.tiles_per_row : nullptr;
-    return c;
-}
-
-// a1: coalesced 128-bit loads, zero-filled past the end of the row (BatchMatMul's zero-pad)
-template <int DT, int NT>
-__device__ __forceinline__ void load_run(const TileCtx<DT, NT> &c, int lane, u32x4 (&g)[NT])
-{
-    using T = Tr<DT>;
-    constexpr int kG = T::kG;
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const uint64_t e0 = c.wave_base + (uint64_t)t * (64 * kG) + (uint64_t)lane * kG;
-        if (c.in_vec && e0 + kG <= c.cols) {
-            g[t] = *(const u32x4 *)(c.in_row + e0 * T::kEsz);
-        } else {
-            uint32_t w[4] = {0u, 0u, 0u, 0u};
-            for (int i = 0; i < kG; ++i) {
-                if (e0 + i < c.cols) {
-                    uint32_t v;
-                    if (T::kEsz == 4)      v = ((const uint32_t *)c.in_row)[e0 + i];
-                    else if (T::kEsz == 2) v = ((const uint16_t *)c.in_row)[e0 + i];
-                    else                   v = ((const uint8_t *)c.in_row)[e0 + i];
-                    w[(i * T::kEsz) >> 2] |= v << (8 * ((i * T::kEsz) & 3));
-                }
-            }
-            g[t] = u32x4{w[0], w[1], w[2], w[3]};
-        }
-    }
-}
-
-template <int DT, int NT, bool EXCL>
-__global__ __launch_bounds__(kThreads) void scan_kernel_persistent(Params P)
-{
-    using T = Tr<DT>;
-    using A = typename T::acc;
-    using A4 = typename T::acc4;
-    constexpr int kG = T::kG;
-    constexpr int kS = 4 * kG;
-    constexpr int kTileElems = 64 * kG;
-    constexpr int kBlocks = T::kBlocks;
-    constexpr int kOutGran = kTileElems / 4;
-    constexpr int kOutShift = (kS == 64) ? 4 : 3;
-    constexpr int kStage = kOutGran + (kOutGran >> kOutShift) + 1;
-
-    __shared__ u32x4 stage[kWaves][kStage];
-    __shared__ uint32_t s_wave_total[kWaves];
-    __shared__ uint32_t s_bcast;
-
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // wave-uniform: keeps tile bookkeeping in SGPRs
-    const int c = lane & 15, j = lane >> 4;
-    const bool chained = P.tiles_per_row > 1;
-    const uint32_t tag = P.tag;
-    const uint32_t G = gridDim.x;
-    const typename T::AConst Aop = T::make(lane, EXCL);
-
-    // Stage 1 of a tile: operand order through LDS, tile total, publish.  Leaves the operands in b and
-    // this wavefront's offset inside the tile in wave_off.
-    auto stage1 = [&](const TileCtx<DT, NT> &cx, u32x4 (&g)[NT], u32x4 (&b)[NT], A &wave_off) {
-        typename T::red rsum = T::red_init();
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            stage[wave][padded<3>(lane)] = g[t];
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            b[t] = stage[wave][padded<3>(4 * c + j)];
-            rsum = T::red_add(Aop, rsum, b[t]);
-        }
-        const A wave_total = wave_sum(T::red_lane(rsum, lane));
-        if (lane == 0) s_wave_total[wave] = acc_bits(wave_total);
-        __syncthreads();
-        A wg_total = acc_from_bits<A>(0u);
-        wave_off = acc_from_bits<A>(0u);
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            const A v = acc_from_bits<A>(s_wave_total[w]);
-            if (w < wave) wave_off = acc_add(wave_off, v);
-            wg_total = acc_add(wg_total, v);
-        }
-        if (chained && threadIdx.x == 0)      // the first tile of a row knows its inclusive prefix already
-            __hip_atomic_store(cx.row_status + cx.tr,
-                               status_word(tag, cx.tr == 0 ? kStatePrefix : kStateAggregate, acc_bits(wg_total)),
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        return wg_total;
-    };
-
-    uint32_t cur = blockIdx.x;
-    if (cur >= P.num_tiles) return;
-    TileCtx<DT, NT> cx_cur = tile_ctx<DT, NT>(P, cur, wave);
-    u32x4 g[NT], b_cur[NT], b_next[NT];
-    A woff_cur, woff_next = acc_from_bits<A>(0u), total_cur, total_next = acc_from_bits<A>(0u);
-
-    load_run<DT, NT>(cx_cur, lane, g);
-    total_cur = stage1(cx_cur, g, b_cur, woff_cur);
-    uint32_t nxt = cur + G;
-    TileCtx<DT, NT> cx_next = cx_cur;
-    if (nxt < P.num_tiles) { cx_next = tile_ctx<DT, NT>(P, nxt, wave); load_run<DT, NT>(cx_next, lane, g); }
-
-    for (;;) {
-        const bool has_next = nxt < P.num_tiles;
-        if (has_next) {
-            total_next = stage1(cx_next, g, b_next, woff_next);
-            const uint32_t nn = nxt + G;
-            if (nn < P.num_tiles) { const TileCtx<DT, NT> cx_nn = tile_ctx<DT, NT>(P, nn, wave); load_run<DT, NT>(cx_nn, lane, g); }
-        }
-
-        // ---- a4: carry of the current tile
-        A prefix = acc_from_bits<A>(0u);
-        if (chained) {
-            if (wave == 0) {
-                if (cx_cur.tr != 0) {
-                    prefix = look_back<A>(cx_cur.row_status, (int)cx_cur.tr, tag, P.ws);
-                    if (lane == 0)
-                        __hip_atomic_store(cx_cur.row_status + cx_cur.tr,
-                                           status_word(tag, kStatePrefix, acc_bits(acc_add(prefix, total_cur))),
-                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
-                if (lane == 0) s_bcast = acc_bits(prefix);
-            }
-            __syncthreads();
-            prefix = acc_from_bits<A>(s_bcast);
-        }
-
-        // ---- a2 + a3 + a5 + a6 for the current tile
-        A carry = acc_add(prefix, woff_cur);
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            A4 d[kBlocks];
-            T::mma(Aop, b_cur[t], lane, EXCL, d);
-            A tot = acc_from_bits<A>((uint32_t)bits<u32x4>(d[kBlocks - 1])[3]);
-            if (EXCL) tot = acc_add(tot, T::last(b_cur[t]));
-            A e = dpp_shr<A, kRowShr + 1>(tot);
-            e = acc_add(e, dpp_shr<A, kRowShr + 1>(e));
-            e = acc_add(e, dpp_shr<A, kRowShr + 2>(e));
-            e = acc_add(e, dpp_shr<A, kRowShr + 4>(e));
-            e = acc_add(e, dpp_shr<A, kRowShr + 8>(e));
-            const A tile_total = uniform_from_lane(acc_add(e, tot), 63);
-            const A cc = acc_add(carry, lane_value(e, 48 + c));
-#pragma unroll
-            for (int p = 0; p < kBlocks; ++p) {
-                u32x4 v = bits<u32x4>(d[p]);
-                for (int r = 0; r < 4; ++r) v[r] = acc_bits(acc_add(cc, acc_from_bits<A>(v[r])));
-                stage[wave][padded<kOutShift>((kS / 4) * c + 4 * p + j)] = v;
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-            for (int k = 0; k < kOutGran / 64; ++k) {
-                const int og = 64 * k + lane;
-                const u32x4 v = stage[wave][padded<kOutShift>(og)];
-                const uint64_t e0 = cx_cur.wave_base + (uint64_t)t * kTileElems + 4ull * og;
-                if (cx_cur.out_vec && e0 + 4 <= cx_cur.cols) {
-                    __builtin_nontemporal_store(v, (u32x4 *)(cx_cur.out_row + e0 * 4));
-                } else {
-                    for (int r = 0; r < 4; ++r)
-                        if (e0 + r < cx_cur.cols) ((uint32_t *)cx_cur.out_row)[e0 + r] = v[r];
-                }
-            }
-            carry = acc_add(carry, tile_total);
-        }
-
-        if (!has_next) break;
-        cur = nxt; nxt += G;
-        cx_cur = cx_next;
-        if (nxt < P.num_tiles) cx_next = tile_ctx<DT, NT>(P, nxt, wave);
-#pragma unroll
-        for (int t = 0; t < NT; ++t) b_cur[t] = b_next[t];
-        woff_cur = woff_next; total_cur = total_next;
-    }
-}
-
 __global__ void fill_zero_kernel(uint32_t *p, size_t words)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -744,12 +531,12 @@ bool valid_dtype(int dt) { return dt >= 0 && dt <= 4; }
 size_t in_size(int dt) { return dt == TCUSCAN_I8_I32 ? 1 : (dt == TCUSCAN_F16_F32 || dt == TCUSCAN_BF16_F32) ? 2 : 4; }
 
 // MFMA tiles per wavefront for the two tile sizes of each dtype.  The small one is 8192 elements per
-// workgroup for every dtype; the large one keeps 32 (8/16-bit inputs) or 64 (32-bit inputs) input
+// workgroup for every dtype; the large one keeps 32 (8-bit inputs) or 64 (16/32-bit inputs) input
 // registers per lane waiting for the carry.
 template <int DT> struct Tiles;
 template <> struct Tiles<TCUSCAN_I8_I32>   { static constexpr int kSmall = 2, kLarge = 8;  };
-template <> struct Tiles<TCUSCAN_F16_F32>  { static constexpr int kSmall = 4, kLarge = 8;  };
-template <> struct Tiles<TCUSCAN_BF16_F32> { static constexpr int kSmall = 4, kLarge = 8;  };
+template <> struct Tiles<TCUSCAN_F16_F32>  { static constexpr int kSmall = 4, kLarge = 16; };
+template <> struct Tiles<TCUSCAN_BF16_F32> { static constexpr int kSmall = 4, kLarge = 16; };
 template <> struct Tiles<TCUSCAN_F32_F32>  { static constexpr int kSmall = 8, kLarge = 16; };
 template <> struct Tiles<TCUSCAN_I32_I32>  { static constexpr int kSmall = 8, kLarge = 16; };
 
@@ -768,7 +555,7 @@ std::atomic<int> g_tile_policy{0};
 
 bool use_large(int dt, size_t rows, size_t cols)
 {
-    const int f = g_tile_policy.load(std::memory_order_relaxed) & 3;
+    const int f = g_tile_policy.load(std::memory_order_relaxed);
     if (f) return f == 2 && cols > kSmallTile;
     const size_t lt = large_tile(dt);
     return cols >= 2 * lt && rows * ((cols + lt - 1) / lt) >= 512;
@@ -776,37 +563,12 @@ bool use_large(int dt, size_t rows, size_t cols)
 
 std::atomic<uint32_t> g_calls{0};
 
-// Workgroups of `fn` that are resident at once on the current device (cached per kernel).
-unsigned resident_workgroups(const void *fn)
-{
-    static std::mutex mu;
-    static std::map<const void *, unsigned> cache;
-    std::lock_guard<std::mutex> lk(mu);
-    auto it = cache.find(fn);
-    if (it != cache.end()) return it->second;
-    int dev = 0, per_cu = 0, cus = 0;
-    unsigned g = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
-        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kThreads, 0) == hipSuccess && per_cu > 0 && cus > 0)
-        g = (unsigned)per_cu * (unsigned)cus;
-    cache[fn] = g;
-    return g;
-}
-
 template <int DT> hipError_t launch_dt(Params P, bool excl, bool large, hipStream_t s)
 {
     // hipLaunchKernel reports this launch's own status (hipGetLastError could return a stale,
     // unrelated code left behind by another library's polling calls).
     void *args[] = {&P};
     const void *fn;
-    if (g_tile_policy.load(std::memory_order_relaxed) & 4) {
-        if (large) fn = excl ? (const void *)scan_kernel_persistent<DT, Tiles<DT>::kLarge, true> : (const void *)scan_kernel_persistent<DT, Tiles<DT>::kLarge, false>;
-        else       fn = excl ? (const void *)scan_kernel_persistent<DT, Tiles<DT>::kSmall, true> : (const void *)scan_kernel_persistent<DT, Tiles<DT>::kSmall, false>;
-        const unsigned g = resident_workgroups(fn);
-        if (g == 0) return hipErrorUnknown;
-        return hipLaunchKernel(fn, dim3(P.num_tiles < g ? P.num_tiles : g), dim3(kThreads), args, 0, s);
-    }
     if (large) fn = excl ? (const void *)scan_kernel<DT, Tiles<DT>::kLarge, true> : (const void *)scan_kernel<DT, Tiles<DT>::kLarge, false>;
     else       fn = excl ? (const void *)scan_kernel<DT, Tiles<DT>::kSmall, true> : (const void *)scan_kernel<DT, Tiles<DT>::kSmall, false>;
     return hipLaunchKernel(fn, dim3(P.num_tiles), dim3(kThreads), args, 0, s);
@@ -871,7 +633,7 @@ size_t tcuscan_large_tile_elems(tcuscan_dtype_t dt) { return valid_dtype((int)dt
 
 tcuscan_status_t tcuscan_set_tile_policy(int policy)
 {
-    if (policy < 0 || policy > 7 || (policy & 3) == 3) return TCUSCAN_ERR_INVALID_ARG;
+    if (policy < 0 || policy > 2) return TCUSCAN_ERR_INVALID_ARG;
     g_tile_policy.store(policy, std::memory_order_relaxed);
     return TCUSCAN_OK;
 }
