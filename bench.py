@@ -98,6 +98,33 @@ def measure(name: str, steps: int, warmup: int, keep_host: bool = False):
     return res, x, last
 
 
+def measure_levels(steps: int):
+    """Algorithm 1 run literally (one launch per round, 13 rounds at n = 16^7) against the fused kernel, same input."""
+    import torch
+    n = 1 << 28
+    x = inputs.mask_i8(n, inputs.CONFIGS["C3"]["seed"])
+    d_in = torch.from_numpy(x).cuda()
+    d_out = torch.empty(n, dtype=torch.int32, device="cuda")
+    ws = tcuscan.new_workspace(1, n, "i8")
+    res = {}
+    for name, fn in (("levels", lambda: tcuscan.matmulscan_levels(d_in, d_out, "i8")),
+                     ("fused", lambda: tcuscan.inclusive(d_in, d_out, "i8", ws=ws))):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        res[name] = {"ms": ms, "gelems_per_s": n / (ms * 1e-3) / 1e9}
+    res["workload"] = "inclusive scan, n=2^28=16^7, int8 {0,1} -> int32; 'levels' = 13 launches of Algorithm 1's rounds"
+    res["fused_speedup"] = res["levels"]["ms"] / res["fused"]["ms"]
+    return res
+
+
 def copy_ceiling_gbps() -> float:
     """A plain device-to-device copy of 1 GiB (read + write counted), as a measured ceiling."""
     import torch
@@ -179,6 +206,7 @@ def main() -> int:
                 continue
             r, _, _ = measure(name, max(10, args.steps // 2), args.warmup)
             others[name] = {k: r[k] for k in ("workload", "kernel_ms", "gelems_per_s", "achieved_GBps", "frac_of_peak")}
+        others["algorithm1_round_by_round"] = measure_levels(5)
     ceiling = copy_ceiling_gbps()
 
     line = {

@@ -128,6 +128,23 @@ tcuscan_status_t tcuscan_set_tile_policy(int policy);
  */
 tcuscan_status_t tcuscan_workspace_fault(const void *d_ws, tcuscan_stream_t stream, unsigned *h_fault);
 
+/*
+ * Algorithm 1 (MatMulScan) executed literally with s = 16: one kernel launch per round, k = log_s n
+ * up-sweep rounds (gather x[s^t - 1 :: s^t], BatchMatMul with L_s, scatter) followed by k - 1
+ * down-sweep rounds (gather x[s^t - 1 :: s^(t-1)], BatchMatMul with B_s, scatter); both constant
+ * matrices run on the MFMA unit.  Inclusive scan only, and only n = 16^k (k >= 1), the lengths
+ * Algorithm 1 is defined for; other n return TCUSCAN_ERR_UNSUPPORTED.  This is the unfused
+ * reference schedule for measurements and schedule checks, not the fast path.
+ *   d_in, d_out   as tcuscan_inclusive (d_out holds accumulator-typed values after round 0)
+ *   rounds        number of rounds to execute, in Algorithm 1's order; negative = all 2k - 1.
+ *                 With fewer rounds d_out holds the paper's intermediate state (Figure 1).
+ *   d_matmuls     optional device counter (8-byte aligned, caller-zeroed): incremented by the number
+ *                 of s x s products issued (Lemma 1).  Pass NULL when timing: counting costs atomics.
+ * No workspace.  Asynchronous on `stream`.
+ */
+tcuscan_status_t tcuscan_matmulscan_levels(const void *d_in, void *d_out, size_t n, tcuscan_dtype_t dt,
+                                           int rounds, unsigned long long *d_matmuls, tcuscan_stream_t stream);
+
 /* Static, human-readable name of a status code. */
 const char *tcuscan_status_string(tcuscan_status_t st);
 

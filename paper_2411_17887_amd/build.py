@@ -6,7 +6,7 @@ import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SOURCES = [os.path.join(HERE, "csrc", "tcuscan.hip")]
+SOURCES = [os.path.join(HERE, "csrc", "tcuscan.hip"), os.path.join(HERE, "csrc", "levels.hip")]
 LIB = os.path.join(HERE, "libtcuscan.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",

@@ -18,7 +18,7 @@ DTYPES = {"i32": I32_I32, "f16": F16_F32, "i8": I8_I32, "f32": F32_F32, "bf16": 
 
 EXPORTS = ["tcuscan_workspace_bytes", "tcuscan_workspace_init", "tcuscan_inclusive", "tcuscan_exclusive",
            "tcuscan_batched", "tcuscan_tile_elems", "tcuscan_large_tile_elems", "tcuscan_set_tile_policy",
-           "tcuscan_workspace_fault", "tcuscan_status_string"]
+           "tcuscan_workspace_fault", "tcuscan_matmulscan_levels", "tcuscan_status_string"]
 
 _lib = None
 
@@ -54,10 +54,11 @@ def load() -> ctypes.CDLL:
         L.tcuscan_exclusive.argtypes = [vp, vp, sz, ci, vp, sz, vp]
         L.tcuscan_batched.argtypes = [vp, vp, sz, sz, ci, ci, vp, sz, vp]
         L.tcuscan_workspace_fault.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_uint)]
+        L.tcuscan_matmulscan_levels.argtypes = [vp, vp, sz, ci, ci, vp, vp]
         L.tcuscan_status_string.argtypes = [ci]
         L.tcuscan_status_string.restype = ctypes.c_char_p
         for f in ("tcuscan_workspace_init", "tcuscan_inclusive", "tcuscan_exclusive", "tcuscan_batched",
-                  "tcuscan_workspace_fault"):
+                  "tcuscan_workspace_fault", "tcuscan_matmulscan_levels"):
             getattr(L, f).restype = ci
         _lib = L
     return _lib
@@ -140,6 +141,14 @@ def batched(x, out, rows: int, cols: int, dt, exclusive_scan: bool = False, ws=N
                                 _stream(stream))
     if rc != OK:
         raise TcuscanError(rc, "tcuscan_batched")
+
+
+def matmulscan_levels(x, out, dt, rounds: int = -1, matmuls=None, stream=None, n=None) -> None:
+    """Algorithm 1 round by round (s = 16, n = 16^k).  `matmuls`: optional int64 device tensor of one element."""
+    rc = load().tcuscan_matmulscan_levels(_ptr(x), _ptr(out), x.numel() if n is None else n, _dt(dt), int(rounds),
+                                          _ptr(matmuls), _stream(stream))
+    if rc != OK:
+        raise TcuscanError(rc, "tcuscan_matmulscan_levels")
 
 
 def workspace_fault(ws, stream=None) -> int:

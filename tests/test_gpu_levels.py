@@ -1,0 +1,93 @@
+"""GPU parity for the round-by-round executor of Algorithm 1 (tcuscan_matmulscan_levels).
+
+Final results against the sequential oracle; intermediate states after every round against the CPU
+replay of the paper's schedule (which is itself pinned to Figure 1(a)); the number of s x s products
+against the replay's count and Lemma 1's bound (tests/golden/lemma1_counts.txt)."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import matmulscan_model as mm
+from paper_2411_17887_amd import inputs, tcuscan
+from gpu_util import to_device, out_dtype
+
+pytestmark = pytest.mark.gpu
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def run_levels(x, kind, rounds=-1, count=False, inplace=False):
+    import torch
+    d_in = to_device(x, kind)
+    d_out = d_in if inplace else torch.full((x.size + 4,), -7, dtype=out_dtype(kind), device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int64, device="cuda") if count else None
+    tcuscan.matmulscan_levels(d_in, d_out, kind, rounds=rounds, matmuls=cnt, n=x.size)
+    torch.cuda.synchronize()
+    if not inplace:
+        assert int((d_out[x.size:] != -7).sum()) == 0
+    got = d_out[: x.size].cpu().numpy().copy()
+    return (got, int(cnt.item())) if count else got
+
+
+def lemma_rows():
+    rows = []
+    with open(os.path.join(GOLD, "lemma1_counts.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                rows.append(tuple(int(t) for t in line.split()))
+    return {r[2]: r for r in rows if r[0] == 16}
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4])
+@pytest.mark.parametrize("kind", ["i32", "i8", "f32", "f16", "bf16"])
+def test_final_result_and_product_count(kind, k):
+    n = 16 ** k
+    ints = kind in ("i32", "i8")
+    gen = {"i32": inputs.int32_full, "i8": inputs.int8_full, "f32": inputs.tri_f32, "f16": inputs.tri_f16,
+           "bf16": inputs.tri_bf16_bits}[kind]
+    x = gen(n, 50 + k)
+    got, cnt = run_levels(x, kind, count=True)
+    if ints:
+        assert oracle.compare_int(x, kind, got) == (0, -1)
+    else:
+        assert oracle.compare_float_exact(x, kind, got) == (0, -1)
+    tr = mm.Trace()
+    mm.matmul_scan(np.zeros(n, dtype=np.int64), 16, tr)
+    s, kk, nn, depth, bound = lemma_rows()[n]
+    assert cnt == tr.matmuls <= bound and tr.depth == depth == 2 * k - 1
+
+
+@pytest.mark.parametrize("kind", ["i32", "f32"])
+def test_every_intermediate_state_matches_the_cpu_replay(kind):
+    n, k = 4096, 3
+    x = inputs.int32_small(n, inputs.BASE_SEED)           # the C1 input; as floats every partial sum is exact
+    tr = mm.Trace()
+    mm.matmul_scan(x.astype(np.int64), 16, tr)
+    xin = x if kind == "i32" else x.astype(np.float32)
+    for r in range(1, 2 * k):
+        got = run_levels(xin, kind, rounds=r)
+        assert np.array_equal(got.astype(np.int64), tr.states[r - 1]), f"state after round {r}"
+    assert np.array_equal(run_levels(xin, kind, rounds=0, inplace=True).astype(np.int64), x.astype(np.int64))
+
+
+def test_random_floats_within_tolerance_and_large_sizes():
+    for kind, gen, tol in [("f32", inputs.f32_normal, 1e-5), ("f16", inputs.f16_uniform01, 1e-3), ("bf16", inputs.bf16_uniform_pm1, 1e-3)]:
+        x = gen(16 ** 5, 9)
+        rep = oracle.compare_float(x, kind, run_levels(x, kind))
+        assert rep.ok(tol), rep
+    x = inputs.mask_i8(16 ** 6, 3)
+    got, cnt = run_levels(x, "i8", count=True)
+    assert oracle.compare_int(x, "i8", got) == (0, -1)
+    assert cnt == 139811 <= lemma_rows()[16 ** 6][4]
+    x = inputs.int32_full(16 ** 5, 4)
+    assert oracle.compare_int(x, "i32", run_levels(x, "i32", inplace=True)) == (0, -1)
+
+
+def test_lengths_that_are_not_powers_of_16_are_refused():
+    import torch
+    t = torch.zeros(48, dtype=torch.int32, device="cuda")
+    for n in (0, 15, 17, 48, 4095):
+        with pytest.raises(tcuscan.TcuscanError) as e:
+            tcuscan.matmulscan_levels(t, t, "i32", n=n)
+        assert e.value.code == tcuscan.ERR_UNSUPPORTED
