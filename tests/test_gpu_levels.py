@@ -84,6 +84,13 @@ def test_random_floats_within_tolerance_and_large_sizes():
     assert oracle.compare_int(x, "i32", run_levels(x, "i32", inplace=True)) == (0, -1)
 
 
+def test_full_size_2p28_result_and_lemma1_count():
+    x = inputs.mask_i8(16 ** 7, inputs.CONFIGS["C3"]["seed"])
+    got, cnt = run_levels(x, "i8", count=True)
+    assert oracle.compare_int(x, "i8", got) == (0, -1)
+    assert cnt == 2236963 <= lemma_rows()[16 ** 7][4]          # 13 rounds
+
+
 def test_lengths_that_are_not_powers_of_16_are_refused():
     import torch
     t = torch.zeros(48, dtype=torch.int32, device="cuda")
