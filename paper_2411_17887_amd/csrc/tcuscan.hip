@@ -352,33 +352,172 @@ __device__ A look_back(const uint64_t *row_status, int tr, uint32_t tag, WsHeade
     return sum;
 }
 
-// ----------------------------------------------------------------------------- kernel
+// ------------------------------------------------------------------- per-wavefront steps
+//
+// A wavefront owns a run of NT consecutive MFMA tiles (1 KiB of input each) of one row.  The three
+// steps below are shared by the long-row kernel (workgroup tiles + carry chain) and the short-row
+// kernel (one row per wavefront).
 
+template <int DT> struct Geo {
+    using T = Tr<DT>;
+    static constexpr int kG = T::kG;                       // elements per input granule
+    static constexpr int kS = 4 * kG;                      // column length
+    static constexpr int kTileElems = 64 * kG;             // one MFMA tile = 1 KiB of input
+    static constexpr int kOutGran = kTileElems / 4;        // output granules per MFMA tile
+    static constexpr int kOutShift = (kS == 64) ? 4 : 3;
+    static constexpr int kStage = kOutGran + (kOutGran >> kOutShift) + 1;   // granules of LDS per wavefront
+};
+
+struct Run {
+    const char *in_row;      // first input byte of the row
+    char *out_row;           // first output byte of the row
+    uint64_t base;           // first element of this wavefront's run inside the row
+    uint64_t cols;           // row length
+    bool in_vec, out_vec;    // row starts are 16-byte aligned
+};
+
+// a1: coalesced 128-bit loads, zero-filled past the end of the row (BatchMatMul's zero-pad)
+template <int DT, int NT>
+__device__ __forceinline__ void load_run(const Run &R, int lane, u32x4 (&g)[NT])
+{
+    using T = Tr<DT>;
+    constexpr int kG = Geo<DT>::kG;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const uint64_t e0 = R.base + (uint64_t)t * Geo<DT>::kTileElems + (uint64_t)lane * kG;
+        if (R.in_vec && e0 + kG <= R.cols) {
+            g[t] = *(const u32x4 *)(R.in_row + e0 * T::kEsz);
+        } else {
+            uint32_t w[4] = {0u, 0u, 0u, 0u};
+            for (int i = 0; i < kG; ++i) {
+                if (e0 + i < R.cols) {
+                    uint32_t v;
+                    if (T::kEsz == 4)      v = ((const uint32_t *)R.in_row)[e0 + i];
+                    else if (T::kEsz == 2) v = ((const uint16_t *)R.in_row)[e0 + i];
+                    else                   v = ((const uint8_t *)R.in_row)[e0 + i];
+                    w[(i * T::kEsz) >> 2] |= v << (8 * ((i * T::kEsz) & 3));
+                }
+            }
+            g[t] = u32x4{w[0], w[1], w[2], w[3]};
+        }
+    }
+}
+
+// Load order -> operand order through this wavefront's LDS slot (lane (j, c) receives granule 4c + j),
+// and, if REDUCE, the total of the run: J * T accumulated over the tiles (plain adds for 32-bit inputs).
+// One slot is reused tile after tile: a wavefront's LDS instructions execute in order, so "write tile
+// t+1" can never overtake "read tile t", and no workgroup barrier is involved.
+template <int DT, int NT, bool REDUCE>
+__device__ __forceinline__ typename Tr<DT>::acc to_operands(u32x4 *slot, int lane, const typename Tr<DT>::AConst &Aop,
+                                                            const u32x4 (&g)[NT], u32x4 (&b)[NT])
+{
+    using T = Tr<DT>;
+    const int c = lane & 15, j = lane >> 4;
+    typename T::red rsum = T::red_init();
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        slot[padded<3>(lane)] = g[t];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        b[t] = slot[padded<3>(4 * c + j)];
+        if (REDUCE) rsum = T::red_add(Aop, rsum, b[t]);
+    }
+    if (!REDUCE) return acc_from_bits<typename T::acc>(0u);
+    return wave_sum(T::red_lane(rsum, lane));
+}
+
+// a2 + a3 + a5 + a6 for the run, tile by tile with a running carry (`carry` = everything before the run).
 template <int DT, int NT, bool EXCL>
-__global__ __launch_bounds__(kThreads) void scan_kernel(Params P)
+__device__ __forceinline__ void scan_and_store(u32x4 *slot, int lane, const typename Tr<DT>::AConst &Aop, const Run &R,
+                                               const u32x4 (&b)[NT], typename Tr<DT>::acc carry)
 {
     using T = Tr<DT>;
     using A = typename T::acc;
     using A4 = typename T::acc4;
-    constexpr int kG = T::kG;                       // elements per input granule
-    constexpr int kS = 4 * kG;                      // column length
-    constexpr int kTileElems = 64 * kG;             // one MFMA tile = 1 KiB of input
+    using Ge = Geo<DT>;
     constexpr int kBlocks = T::kBlocks;
-    constexpr int kOutGran = kTileElems / 4;        // output granules per MFMA tile
-    constexpr int kOutShift = (kS == 64) ? 4 : 3;
-    constexpr int kStage = kOutGran + (kOutGran >> kOutShift) + 1;
-    constexpr uint32_t kEPW = NT * kTileElems;      // elements per wavefront
-    constexpr uint32_t kWgElems = kEPW * kWaves;    // elements per workgroup tile
+    const int c = lane & 15, j = lane >> 4;         // operand order: column, quarter (also output row group q)
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        // a2: local scans of the 16 columns on the MFMA unit
+        A4 d[kBlocks];
+        T::mma(Aop, b[t], lane, EXCL, d);
+        // a3: the column totals are row S-1 = lanes 48..63, last register of the last block
+        A tot = acc_from_bits<A>((uint32_t)bits<u32x4>(d[kBlocks - 1])[3]);
+        if (EXCL) tot = acc_add(tot, T::last(b[t]));     // the strictly-lower product leaves the last element out
+        A e = dpp_shr<A, kRowShr + 1>(tot);              // shift by one column -> exclusive
+        e = acc_add(e, dpp_shr<A, kRowShr + 1>(e));
+        e = acc_add(e, dpp_shr<A, kRowShr + 2>(e));
+        e = acc_add(e, dpp_shr<A, kRowShr + 4>(e));
+        e = acc_add(e, dpp_shr<A, kRowShr + 8>(e));
+        const A tile_total = uniform_from_lane(acc_add(e, tot), 63);
+        // a5: down-sweep = one add of (carry of the run so far + carry of the column) per output
+        const A cc = acc_add(carry, lane_value(e, 48 + c));      // row 3 -> all four rows
+#pragma unroll
+        for (int p = 0; p < kBlocks; ++p) {
+            u32x4 v = bits<u32x4>(d[p]);
+            for (int r = 0; r < 4; ++r) v[r] = acc_bits(acc_add(cc, acc_from_bits<A>(v[r])));
+            // a6: stage in output order: rows 16p + 4q .. +3 of column c are 4 consecutive outputs
+            slot[padded<Ge::kOutShift>((Ge::kS / 4) * c + 4 * p + j)] = v;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int k = 0; k < Ge::kOutGran / 64; ++k) {
+            const int og = 64 * k + lane;
+            const u32x4 v = slot[padded<Ge::kOutShift>(og)];
+            const uint64_t e0 = R.base + (uint64_t)t * Ge::kTileElems + 4ull * og;
+            if (R.out_vec && e0 + 4 <= R.cols) {
+                __builtin_nontemporal_store(v, (u32x4 *)(R.out_row + e0 * 4));   // written once, never read back here
+            } else {
+                for (int r = 0; r < 4; ++r)
+                    if (e0 + r < R.cols) ((uint32_t *)R.out_row)[e0 + r] = v[r];
+            }
+        }
+        carry = acc_add(carry, tile_total);
+    }
+}
 
-    // One staging slot per wavefront, reused tile after tile.  A wavefront's LDS instructions execute
-    // in order, so "write tile t+1" can never overtake "read tile t"; no workgroup barrier is involved.
-    __shared__ u32x4 stage[kWaves][kStage];
+template <int DT>
+__device__ __forceinline__ Run make_run(const Params &P, uint64_t row, uint64_t base)
+{
+    Run R;
+    const uint64_t row_base = row * P.cols;
+    R.in_row = (const char *)P.in + row_base * Tr<DT>::kEsz;
+    R.out_row = (char *)P.out + row_base * 4;
+    R.base = base;
+    R.cols = P.cols;
+    R.in_vec = (((uintptr_t)R.in_row) & 15) == 0;
+    R.out_vec = (((uintptr_t)R.out_row) & 15) == 0;
+    return R;
+}
+
+// ----------------------------------------------------------------------- long-row kernel
+
+// Waves per SIMD the register allocator is asked to make room for (more resident tiles hide more of the
+// carry chain's latency); values found by measurement, none of them makes the allocator spill.
+template <int DT, int NT> struct MinWaves { static constexpr int value = 1; };
+template <> struct MinWaves<TCUSCAN_I8_I32, 8>    { static constexpr int value = 5; };
+template <> struct MinWaves<TCUSCAN_F16_F32, 16>  { static constexpr int value = 4; };
+template <> struct MinWaves<TCUSCAN_BF16_F32, 16> { static constexpr int value = 4; };
+
+template <int DT, int NT, bool EXCL>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(MinWaves<DT, NT>::value)))
+void scan_kernel(Params P)
+{
+    using T = Tr<DT>;
+    using A = typename T::acc;
+    constexpr uint32_t kEPW = NT * Geo<DT>::kTileElems;   // elements per wavefront
+    constexpr uint32_t kWgElems = kEPW * kWaves;          // elements per workgroup tile
+
+    __shared__ u32x4 stage[kWaves][Geo<DT>::kStage];
     __shared__ uint32_t s_wave_total[kWaves];
     __shared__ uint32_t s_bcast;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // wave-uniform: keeps tile bookkeeping in SGPRs
-    const int c = lane & 15, j = lane >> 4;         // operand order: column, quarter (also output row group q)
 
     // ---- which tile.  Tiles are taken in workgroup-index order: a tile only ever waits for tiles with
     // a smaller index, which the hardware dispatched earlier (or at the same time), so the lowest
@@ -391,52 +530,14 @@ __global__ __launch_bounds__(kThreads) void scan_kernel(Params P)
     const uint32_t tag = P.tag;
     const uint64_t row = tile / P.tiles_per_row;
     const uint32_t tr = tile - (uint32_t)row * P.tiles_per_row;
-    const uint64_t row_base = row * P.cols;                          // first element of the row
-    const uint64_t tile_base = (uint64_t)tr * kWgElems;             // first element of the tile inside the row
-    const uint64_t wave_base = tile_base + (uint64_t)wave * kEPW;   // first element of this wavefront's run
+    const Run R = make_run<DT>(P, row, (uint64_t)tr * kWgElems + (uint64_t)wave * kEPW);
 
-    const char *in_row  = (const char *)P.in + row_base * T::kEsz;
-    char       *out_row = (char *)P.out + row_base * 4;
-    const bool in_vec  = (((uintptr_t)in_row) & 15) == 0;
-    const bool out_vec = (((uintptr_t)out_row) & 15) == 0;
-
-    // ---- a1: coalesced 128-bit loads, zero-filled past the end of the row (BatchMatMul's zero-pad)
-    u32x4 g[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const uint64_t e0 = wave_base + (uint64_t)t * kTileElems + (uint64_t)lane * kG;
-        if (in_vec && e0 + kG <= P.cols) {
-            g[t] = *(const u32x4 *)(in_row + e0 * T::kEsz);
-        } else {
-            uint32_t w[4] = {0u, 0u, 0u, 0u};
-            for (int i = 0; i < kG; ++i) {
-                if (e0 + i < P.cols) {
-                    uint32_t v;
-                    if (T::kEsz == 4)      v = ((const uint32_t *)in_row)[e0 + i];
-                    else if (T::kEsz == 2) v = ((const uint16_t *)in_row)[e0 + i];
-                    else                   v = ((const uint8_t *)in_row)[e0 + i];
-                    w[(i * T::kEsz) >> 2] |= v << (8 * ((i * T::kEsz) & 3));
-                }
-            }
-            g[t] = u32x4{w[0], w[1], w[2], w[3]};
-        }
-    }
-
+    u32x4 g[NT], b[NT];
+    load_run<DT, NT>(R, lane, g);
     const typename T::AConst Aop = T::make(lane, EXCL);
 
-    // ---- to operand order through LDS, and the tile total (up-sweep of this tile in one step)
-    u32x4 b[NT];
-    typename T::red rsum = T::red_init();
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        stage[wave][padded<3>(lane)] = g[t];
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        b[t] = stage[wave][padded<3>(4 * c + j)];
-        rsum = T::red_add(Aop, rsum, b[t]);
-    }
-    const A wave_total = wave_sum(T::red_lane(rsum, lane));
+    // ---- operand order, and the total of the run (the up-sweep of this tile in one step)
+    const A wave_total = to_operands<DT, NT, true>(stage[wave], lane, Aop, g, b);
 
     // ---- level 2: wavefront totals through LDS
     if (lane == 0) s_wave_total[wave] = acc_bits(wave_total);
@@ -473,48 +574,33 @@ __global__ __launch_bounds__(kThreads) void scan_kernel(Params P)
         prefix = acc_from_bits<A>(s_bcast);
     }
 
-    // ---- a2 + a3 + a5 + a6, tile by tile with a running carry
-    A carry = acc_add(prefix, wave_off);                 // everything before this wavefront's run
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        // a2: local scans of the 16 columns on the MFMA unit
-        A4 d[kBlocks];
-        T::mma(Aop, b[t], lane, EXCL, d);
-        // a3: the column totals are row S-1 = lanes 48..63, last register of the last block
-        A tot = acc_from_bits<A>((uint32_t)bits<u32x4>(d[kBlocks - 1])[3]);
-        if (EXCL) tot = acc_add(tot, T::last(b[t]));     // the strictly-lower product leaves the last element out
-        A e = dpp_shr<A, kRowShr + 1>(tot);              // shift by one column -> exclusive
-        e = acc_add(e, dpp_shr<A, kRowShr + 1>(e));
-        e = acc_add(e, dpp_shr<A, kRowShr + 2>(e));
-        e = acc_add(e, dpp_shr<A, kRowShr + 4>(e));
-        e = acc_add(e, dpp_shr<A, kRowShr + 8>(e));
-        const A tile_total = uniform_from_lane(acc_add(e, tot), 63);
-        // a5: down-sweep = one add of (carry of the run so far + carry of the column) per output
-        const A cc = acc_add(carry, lane_value(e, 48 + c));      // row 3 -> all four rows
-#pragma unroll
-        for (int p = 0; p < kBlocks; ++p) {
-            u32x4 v = bits<u32x4>(d[p]);
-            for (int r = 0; r < 4; ++r) v[r] = acc_bits(acc_add(cc, acc_from_bits<A>(v[r])));
-            // a6: stage in output order: rows 16p + 4q .. +3 of column c are 4 consecutive outputs
-            stage[wave][padded<kOutShift>((kS / 4) * c + 4 * p + j)] = v;
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-        for (int k = 0; k < kOutGran / 64; ++k) {
-            const int og = 64 * k + lane;
-            const u32x4 v = stage[wave][padded<kOutShift>(og)];
-            const uint64_t e0 = wave_base + (uint64_t)t * kTileElems + 4ull * og;
-            if (out_vec && e0 + 4 <= P.cols) {
-                __builtin_nontemporal_store(v, (u32x4 *)(out_row + e0 * 4));   // written once, never read back here
-            } else {
-                for (int r = 0; r < 4; ++r)
-                    if (e0 + r < P.cols) ((uint32_t *)out_row)[e0 + r] = v[r];
-            }
-        }
-        carry = acc_add(carry, tile_total);
-    }
+    // ---- local scans, down-sweep add and store, with everything before this wavefront's run as carry
+    scan_and_store<DT, NT, EXCL>(stage[wave], lane, Aop, R, b, acc_add(prefix, wave_off));
+}
+
+// ---------------------------------------------------------------------- short-row kernel
+//
+// Rows no longer than one wavefront's run (NT tiles): every wavefront scans rows of its own -- no
+// totals to exchange, no carry chain, no barrier.  Many short independent rows are the shape of
+// the histogram prefix sums in gradient-boosted-tree split finding, one of the paper's two
+// motivating applications.
+
+template <int DT, int NT, bool EXCL>
+__global__ __launch_bounds__(kThreads) void scan_rows_kernel(Params P)
+{
+    using T = Tr<DT>;
+    using A = typename T::acc;
+    __shared__ u32x4 stage[kWaves][Geo<DT>::kStage];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const uint64_t row = (uint64_t)blockIdx.x * kWaves + wave;
+    if (row >= P.rows) return;
+    const Run R = make_run<DT>(P, row, 0);
+    u32x4 g[NT], b[NT];
+    load_run<DT, NT>(R, lane, g);
+    const typename T::AConst Aop = T::make(lane, EXCL);
+    to_operands<DT, NT, false>(stage[wave], lane, Aop, g, b);
+    scan_and_store<DT, NT, EXCL>(stage[wave], lane, Aop, R, b, acc_from_bits<A>(0u));
 }
 
 __global__ void fill_zero_kernel(uint32_t *p, size_t words)
@@ -526,6 +612,8 @@ __global__ void fill_zero_kernel(uint32_t *p, size_t words)
 // ------------------------------------------------------------------------ host side
 
 constexpr size_t kSmallTile = 8192;                      // elements per workgroup tile, small variant (all dtypes)
+constexpr size_t kShortRowMax = 2048;                    // rows up to this length can be scanned one per wavefront
+constexpr size_t kShortRowMinRows = 8;                   // ... when there are enough of them to fill wavefronts
 
 bool valid_dtype(int dt) { return dt >= 0 && dt <= 4; }
 size_t in_size(int dt) { return dt == TCUSCAN_I8_I32 ? 1 : (dt == TCUSCAN_F16_F32 || dt == TCUSCAN_BF16_F32) ? 2 : 4; }
@@ -563,8 +651,26 @@ bool use_large(int dt, size_t rows, size_t cols)
 
 std::atomic<uint32_t> g_calls{0};
 
+// Short rows: the smallest run length (1, 2, 4 or 8 MFMA tiles per wavefront) that holds a row.
+template <int DT, int NT> hipError_t launch_rows_nt(Params P, bool excl, hipStream_t s)
+{
+    void *args[] = {&P};
+    const void *fn = excl ? (const void *)scan_rows_kernel<DT, NT, true> : (const void *)scan_rows_kernel<DT, NT, false>;
+    return hipLaunchKernel(fn, dim3((unsigned)((P.rows + kWaves - 1) / kWaves)), dim3(kThreads), args, 0, s);
+}
+
+template <int DT> hipError_t launch_rows(Params P, bool excl, hipStream_t s)
+{
+    const size_t tiles = (P.cols + Geo<DT>::kTileElems - 1) / Geo<DT>::kTileElems;
+    if (tiles <= 1) return launch_rows_nt<DT, 1>(P, excl, s);
+    if (tiles <= 2) return launch_rows_nt<DT, 2>(P, excl, s);
+    if (tiles <= 4) return launch_rows_nt<DT, 4>(P, excl, s);
+    return launch_rows_nt<DT, 8>(P, excl, s);
+}
+
 template <int DT> hipError_t launch_dt(Params P, bool excl, bool large, hipStream_t s)
 {
+    if (P.rows >= kShortRowMinRows && P.cols <= kShortRowMax) return launch_rows<DT>(P, excl, s);
     // hipLaunchKernel reports this launch's own status (hipGetLastError could return a stale,
     // unrelated code left behind by another library's polling calls).
     void *args[] = {&P};

@@ -151,6 +151,24 @@ def test_batched_shapes(kind, rows, cols):
             check(x, kind, run_scan(x, kind, call, rows=rows, cols=cols), exclusive=ex, rows=rows, cols=cols)
 
 
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("rows,cols", [(4096, 256), (1000, 1024), (513, 2048), (77, 2047), (9, 1), (100, 300), (8, 2048),
+                                       (4099, 64), (33, 513), (65537, 16)])
+def test_short_rows_one_per_wavefront(kind, rows, cols):
+    """Many short rows (histogram-like shapes): each wavefront scans whole rows; includes row lengths that
+    leave rows unaligned, a ragged last workgroup and exclusive scans."""
+    for call in ("batched", "batched_exclusive"):
+        ex = call.endswith("exclusive")
+        if kind in INT_GEN:
+            x = INT_GEN[kind](rows * cols, rows + 3 * cols)
+            check(x, kind, run_scan(x, kind, call, rows=rows, cols=cols), exclusive=ex, rows=rows, cols=cols)
+        else:
+            x = TRI_GEN[kind](rows * cols, rows + 3 * cols)
+            check(x, kind, run_scan(x, kind, call, rows=rows, cols=cols), exclusive=ex, rows=rows, cols=cols, exact_float=True)
+            x = RND_GEN[kind](rows * cols, rows * cols + 1)
+            check(x, kind, run_scan(x, kind, call, rows=rows, cols=cols), exclusive=ex, rows=rows, cols=cols)
+
+
 def test_batched_row_equals_unbatched_scan_of_that_row():
     rows, cols = 6, 30011
     x = inputs.int32_small(rows * cols, 9)
