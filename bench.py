@@ -125,6 +125,52 @@ def measure_levels(steps: int):
     return res
 
 
+def measure_apps(steps: int):
+    """Stream compaction on the C3 mask (n = 2^28) and the 32-pass split radix sort (n = 2^26 random 32-bit keys)."""
+    import torch
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    n = 1 << 28
+    mask = torch.from_numpy(inputs.mask_i8(n, inputs.CONFIGS["C3"]["seed"])).cuda()
+    vals = torch.arange(n, dtype=torch.int32, device="cuda")
+    out = torch.empty(n, dtype=torch.int32, device="cuda")
+    pos = torch.empty(n, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ws = tcuscan.new_workspace(1, n, "i8")
+    ms = timed(lambda: tcuscan.compact_u32(vals, mask, out, pos, count=cnt, ws=ws), steps)
+    kept = int(cnt.item())
+    # scan: n + 4n; pack: mask n + positions 4n + values 4n read, 4 * kept written
+    nbytes = 5 * n + 9 * n + 4 * kept
+    res = {"compaction": {"workload": "n=2^28 int8 {0,1} mask, 32-bit values", "ms": ms, "gelems_per_s": n / (ms * 1e-3) / 1e9,
+                          "kept": kept, "algorithmic_GBps": nbytes / (ms * 1e-3) / 1e9}}
+    del vals, out, pos, mask
+    torch.cuda.empty_cache()
+    m = 1 << 26
+    keys0 = torch.from_numpy(inputs.int32_full(m, 12345)).cuda()
+    keys = torch.empty_like(keys0)
+    tmp, flags, p2 = torch.empty_like(keys0), torch.empty(m, dtype=torch.int8, device="cuda"), torch.empty_like(keys0)
+    ws2 = tcuscan.new_workspace(1, m, "i8")
+
+    def sort_once():
+        keys.copy_(keys0)
+        tcuscan.split_radix_sort_u32(keys, tmp, flags, p2, bits=32, ws=ws2)
+    ms2 = timed(sort_once, max(2, steps // 2))
+    ok = bool((keys[1:].view(torch.int32).to(torch.int64) & 0xFFFFFFFF >= keys[:-1].view(torch.int32).to(torch.int64) & 0xFFFFFFFF).all().item())
+    res["split_radix_sort"] = {"workload": "n=2^26 random 32-bit keys, 32 split passes (one mask scan each), includes one 256 MiB copy per run",
+                               "ms": ms2, "mkeys_per_s": m / (ms2 * 1e-3) / 1e6, "sorted": ok}
+    return res
+
+
 def copy_ceiling_gbps() -> float:
     """A plain device-to-device copy of 1 GiB (read + write counted), as a measured ceiling."""
     import torch
@@ -207,6 +253,7 @@ def main() -> int:
             r, _, _ = measure(name, max(10, args.steps // 2), args.warmup)
             others[name] = {k: r[k] for k in ("workload", "kernel_ms", "gelems_per_s", "achieved_GBps", "frac_of_peak")}
         others["algorithm1_round_by_round"] = measure_levels(5)
+        others.update(measure_apps(5))
     ceiling = copy_ceiling_gbps()
 
     line = {

@@ -145,6 +145,35 @@ tcuscan_status_t tcuscan_workspace_fault(const void *d_ws, tcuscan_stream_t stre
 tcuscan_status_t tcuscan_matmulscan_levels(const void *d_in, void *d_out, size_t n, tcuscan_dtype_t dt,
                                            int rounds, unsigned long long *d_matmuls, tcuscan_stream_t stream);
 
+/*
+ * Applications the paper's introduction gives as its motivation, built on the exclusive scan of a 0/1
+ * int8 mask (the I8_I32 MFMA path).  The caller provides every scratch buffer; workspace as for
+ * tcuscan_exclusive(.., n, TCUSCAN_I8_I32, ..).  n < 2^32.  Asynchronous on `stream`.
+ *
+ * Stream compaction: d_out receives, in order, the 32-bit d_values[i] whose d_mask[i] (int8) is non-zero
+ * (mask entries must be 0 or 1).
+ *   d_positions  scratch, n int32: on return the exclusive scan of the mask (the destination indices)
+ *   d_count      optional device word: number of kept elements
+ */
+tcuscan_status_t tcuscan_compact_u32(const void *d_values, const void *d_mask, void *d_out, size_t n,
+                                     void *d_positions, unsigned *d_count,
+                                     void *d_ws, size_t ws_bytes, tcuscan_stream_t stream);
+
+/*
+ * Radix sort by Blelloch's reduction to prefix sums: `bits` stable split passes, least significant bit
+ * first; pass b scans the mask "bit b is 0" and sends the zeros to the front and the ones behind them,
+ * both in their old order.  Sorts the n unsigned 32-bit d_keys in place by their low `bits` bits (32 for a
+ * full sort); d_vals, if not NULL, are n 32-bit payloads permuted along with the keys (so the sort is
+ * observably stable).
+ *   d_keys_tmp, d_vals_tmp   scratch, n words each (d_vals_tmp only with d_vals); keys buffers 16-byte aligned
+ *   d_flags                  scratch, n bytes, 16-byte aligned
+ *   d_positions              scratch, n int32
+ * One scan per bit: this answers "can the matrix unit sort?", it is not a tuned sort.
+ */
+tcuscan_status_t tcuscan_split_radix_sort_u32(void *d_keys, void *d_vals, size_t n, int bits,
+                                              void *d_keys_tmp, void *d_vals_tmp, void *d_flags, void *d_positions,
+                                              void *d_ws, size_t ws_bytes, tcuscan_stream_t stream);
+
 /* Static, human-readable name of a status code. */
 const char *tcuscan_status_string(tcuscan_status_t st);
 

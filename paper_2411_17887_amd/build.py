@@ -6,7 +6,8 @@ import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SOURCES = [os.path.join(HERE, "csrc", "tcuscan.hip"), os.path.join(HERE, "csrc", "levels.hip")]
+SOURCES = [os.path.join(HERE, "csrc", "tcuscan.hip"), os.path.join(HERE, "csrc", "levels.hip"),
+           os.path.join(HERE, "csrc", "apps.hip")]
 LIB = os.path.join(HERE, "libtcuscan.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",

@@ -18,7 +18,8 @@ DTYPES = {"i32": I32_I32, "f16": F16_F32, "i8": I8_I32, "f32": F32_F32, "bf16": 
 
 EXPORTS = ["tcuscan_workspace_bytes", "tcuscan_workspace_init", "tcuscan_inclusive", "tcuscan_exclusive",
            "tcuscan_batched", "tcuscan_tile_elems", "tcuscan_large_tile_elems", "tcuscan_set_tile_policy",
-           "tcuscan_workspace_fault", "tcuscan_matmulscan_levels", "tcuscan_status_string"]
+           "tcuscan_workspace_fault", "tcuscan_matmulscan_levels", "tcuscan_compact_u32",
+           "tcuscan_split_radix_sort_u32", "tcuscan_status_string"]
 
 _lib = None
 
@@ -55,10 +56,13 @@ def load() -> ctypes.CDLL:
         L.tcuscan_batched.argtypes = [vp, vp, sz, sz, ci, ci, vp, sz, vp]
         L.tcuscan_workspace_fault.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_uint)]
         L.tcuscan_matmulscan_levels.argtypes = [vp, vp, sz, ci, ci, vp, vp]
+        L.tcuscan_compact_u32.argtypes = [vp, vp, vp, sz, vp, vp, vp, sz, vp]
+        L.tcuscan_split_radix_sort_u32.argtypes = [vp, vp, sz, ci, vp, vp, vp, vp, vp, sz, vp]
         L.tcuscan_status_string.argtypes = [ci]
         L.tcuscan_status_string.restype = ctypes.c_char_p
         for f in ("tcuscan_workspace_init", "tcuscan_inclusive", "tcuscan_exclusive", "tcuscan_batched",
-                  "tcuscan_workspace_fault", "tcuscan_matmulscan_levels"):
+                  "tcuscan_workspace_fault", "tcuscan_matmulscan_levels", "tcuscan_compact_u32",
+                  "tcuscan_split_radix_sort_u32"):
             getattr(L, f).restype = ci
         _lib = L
     return _lib
@@ -149,6 +153,22 @@ def matmulscan_levels(x, out, dt, rounds: int = -1, matmuls=None, stream=None, n
                                           _ptr(matmuls), _stream(stream))
     if rc != OK:
         raise TcuscanError(rc, "tcuscan_matmulscan_levels")
+
+
+def compact_u32(values, mask, out, positions, count=None, ws=None, stream=None) -> None:
+    """out <- values[mask != 0] in order; positions (int32, n) is scratch; count: optional 1-element int32 tensor."""
+    rc = load().tcuscan_compact_u32(_ptr(values), _ptr(mask), _ptr(out), values.numel(), _ptr(positions), _ptr(count),
+                                    *_ws_args(ws), _stream(stream))
+    if rc != OK:
+        raise TcuscanError(rc, "tcuscan_compact_u32")
+
+
+def split_radix_sort_u32(keys, keys_tmp, flags, positions, vals=None, vals_tmp=None, bits: int = 32, ws=None, stream=None) -> None:
+    """Stable LSD radix sort of 32-bit keys (and optional payloads) by `bits` split passes, one mask scan each."""
+    rc = load().tcuscan_split_radix_sort_u32(_ptr(keys), _ptr(vals), keys.numel(), int(bits), _ptr(keys_tmp), _ptr(vals_tmp),
+                                             _ptr(flags), _ptr(positions), *_ws_args(ws), _stream(stream))
+    if rc != OK:
+        raise TcuscanError(rc, "tcuscan_split_radix_sort_u32")
 
 
 def workspace_fault(ws, stream=None) -> int:
