@@ -54,7 +54,7 @@ typedef void *tcuscan_stream_t; /* a hipStream_t; NULL is the default stream */
  * Bytes of device workspace a call on `rows` rows of `cols` elements needs (0 when
  * every row fits one workgroup tile).  The workspace holds the carry chain between
  * workgroups (Algorithm 1's up-sweep rounds t >= 3 and Section 2.2 steps 2-3): one
- * 8-byte status word per tile plus a 256-byte header.
+ * 8-byte status word per tile, kept in a 64-byte slot of its own, plus a 256-byte header.
  *
  * The caller zero-fills it ONCE after allocation (hipMemset, or tcuscan_workspace_init)
  * and may then reuse it for any number of calls whose requirement is not larger: every

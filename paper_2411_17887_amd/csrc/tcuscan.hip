@@ -46,7 +46,11 @@ typedef unsigned int u32x4  __attribute__((ext_vector_type(4)));   // one 16-byt
 constexpr int kWaves   = 4;           // wavefronts per workgroup
 constexpr int kThreads = 64 * kWaves;
 
-// Workspace header (256 bytes), followed by one 64-bit status word per tile.
+// Workspace header (256 bytes), followed by one 64-bit status word per tile, each word alone in a
+// 64-byte slot: thousands of tiles poll the words of the few hundred tiles in front of them, and with
+// the words packed 8 to a line that traffic lands on a handful of memory channels (measured: 5-9 %
+// of the whole kernel's run time).
+constexpr size_t kStatusStride = 8;    // in 64-bit words
 struct WsHeader {
     uint32_t fault;    // sticky: a look-back wait hit its spin bound
     uint32_t pad[63];
@@ -304,11 +308,12 @@ __device__ __forceinline__ uint64_t status_word(uint32_t tag, uint32_t state, ui
 }
 
 // Exclusive prefix of tile `tr` of its row: sum of the totals of tiles 0 .. tr-1, found by walking
-// back over published status words, kWindow = 64 * kDepth at a time.  Called by all 64 lanes of one
-// wavefront.  The walk can advance at most one window per status round trip, and tiles finish at a
-// rate of (memory bandwidth / tile bytes), so the window has to cover more tiles than finish during
-// one round trip or the chain throttles the kernel; all loads of a window are in flight together.
-constexpr int kDepth = 8;
+// back over published status words, 64 * kDepth at a time.  Called by all 64 lanes of one
+// wavefront.  All loads of a window are in flight together.  The window size is a measured compromise:
+// a status round trip under full memory load costs microseconds, so a wider window saves round trips,
+// but every extra word polled is uncached traffic that competes with the data (512 words per poll cost
+// 5 % of the run time against 128, and 1024 and more cost 50 %).
+constexpr int kDepth = 2;
 template <class A>
 __device__ A look_back(const uint64_t *row_status, int tr, uint32_t tag, WsHeader *ws)
 {
@@ -319,7 +324,7 @@ __device__ A look_back(const uint64_t *row_status, int tr, uint32_t tag, WsHeade
 #pragma unroll
         for (int u = 0; u < kDepth; ++u) {
             const int idx = base - 64 * u - lane;
-            if (idx >= 0) w[u] = __hip_atomic_load(row_status + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (idx >= 0) w[u] = __hip_atomic_load(row_status + (size_t)idx * kStatusStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         // Take every total up to and including the nearest published prefix, skip everything behind it.
         bool done = false;
@@ -338,7 +343,7 @@ __device__ A look_back(const uint64_t *row_status, int tr, uint32_t tag, WsHeade
                         break;
                     }
                     __builtin_amdgcn_s_sleep(1);
-                    w[u] = __hip_atomic_load(row_status + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    w[u] = __hip_atomic_load(row_status + (size_t)idx * kStatusStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
             const uint64_t have_prefix = __ballot(state == kStatePrefix);
@@ -553,7 +558,7 @@ void scan_kernel(Params P)
     // ---- a4: carry chain between workgroup tiles of the same row
     A prefix = acc_from_bits<A>(0u);
     if (chained) {
-        uint64_t *row_status = (uint64_t *)(P.ws + 1) + row * P.tiles_per_row;
+        uint64_t *row_status = (uint64_t *)(P.ws + 1) + row * P.tiles_per_row * kStatusStride;
         if (wave == 0) {
             if (tr == 0) {
                 if (lane == 0)
@@ -561,11 +566,11 @@ void scan_kernel(Params P)
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             } else {
                 if (lane == 0)
-                    __hip_atomic_store(row_status + tr, status_word(tag, kStateAggregate, acc_bits(wg_total)),
+                    __hip_atomic_store(row_status + (size_t)tr * kStatusStride, status_word(tag, kStateAggregate, acc_bits(wg_total)),
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 prefix = look_back<A>(row_status, (int)tr, tag, P.ws);
                 if (lane == 0)
-                    __hip_atomic_store(row_status + tr, status_word(tag, kStatePrefix, acc_bits(acc_add(prefix, wg_total))),
+                    __hip_atomic_store(row_status + (size_t)tr * kStatusStride, status_word(tag, kStatePrefix, acc_bits(acc_add(prefix, wg_total))),
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             if (lane == 0) s_bcast = acc_bits(prefix);
@@ -716,7 +721,7 @@ tcuscan_status_t run(const void *d_in, void *d_out, size_t rows, size_t cols, in
         hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
         if (hipStreamIsCapturing(s, &cs) != hipSuccess) { (void)hipGetLastError(); cs = hipStreamCaptureStatusNone; }
         if (cs == hipStreamCaptureStatusActive &&
-            launch_fill((char *)d_ws + sizeof(WsHeader), 8 * rows * tpr, s) != hipSuccess) return TCUSCAN_ERR_HIP;
+            launch_fill((char *)d_ws + sizeof(WsHeader), 8 * kStatusStride * rows * tpr, s) != hipSuccess) return TCUSCAN_ERR_HIP;
     }
     hipError_t e;
     switch (dt) {
@@ -749,7 +754,7 @@ size_t tcuscan_workspace_bytes(size_t rows, size_t cols, tcuscan_dtype_t dt)
     if (!valid_dtype((int)dt) || rows == 0 || cols == 0) return 0;
     const size_t tpr = (cols + kSmallTile - 1) / kSmallTile;
     if (tpr <= 1) return 0;
-    return sizeof(WsHeader) + 8 * rows * tpr;
+    return sizeof(WsHeader) + 8 * kStatusStride * rows * tpr;
 }
 
 tcuscan_status_t tcuscan_workspace_init(void *d_ws, size_t ws_bytes, tcuscan_stream_t stream)

@@ -38,8 +38,8 @@ def test_workspace_sizing():
         assert tile >= 4096 and tile % 4096 == 0
         assert tcuscan.workspace_bytes(1, tile, kind) == 0            # one tile per row: no carry chain
         assert tcuscan.workspace_bytes(1000, tile, kind) == 0
-        assert tcuscan.workspace_bytes(1, tile + 1, kind) == 256 + 8 * 2
-        assert tcuscan.workspace_bytes(3, 5 * tile - 1, kind) == 256 + 8 * 15
+        assert tcuscan.workspace_bytes(1, tile + 1, kind) == 256 + 64 * 2
+        assert tcuscan.workspace_bytes(3, 5 * tile - 1, kind) == 256 + 64 * 15
         assert tcuscan.workspace_bytes(0, 100, kind) == 0 and tcuscan.workspace_bytes(4, 0, kind) == 0
     assert tcuscan.workspace_bytes(1, 1 << 20, 9) == 0 and tcuscan.tile_elems(9) == 0
 
