@@ -106,16 +106,18 @@ tcuscan_status_t tcuscan_batched(const void *d_in, void *d_out, size_t rows, siz
                                  void *d_ws, size_t ws_bytes, tcuscan_stream_t stream);
 
 /* Elements the small workgroup tile covers (rows no longer than this need no workspace), and the
- * large tile that long inputs use (more elements wait in registers per compute unit while the
- * carry chain's latency is paid).  Both are multiples of s^2 = 256: a tile is a whole number of
- * BatchMatMul chunks. */
+ * large and huge tiles that long inputs use (more elements wait in registers per compute unit while
+ * the carry chain's latency is paid, and fewer status words are published and polled per byte).  All
+ * are multiples of s^2 = 256: a tile is a whole number of BatchMatMul chunks. */
 size_t tcuscan_tile_elems(tcuscan_dtype_t dt);
 size_t tcuscan_large_tile_elems(tcuscan_dtype_t dt);
+size_t tcuscan_huge_tile_elems(tcuscan_dtype_t dt);
 
 /*
- * Tile-size policy, process-wide: 0 = choose by shape (default: the large tile when a row spans at
- * least two of them and the call has at least 512 tiles), 1 = always the small tile, 2 = the large
- * tile for every row longer than a small tile.  A measurement and test knob; results do not depend
+ * Tile-size policy, process-wide: 0 = choose by shape (default: the huge tile when a row spans at
+ * least four of them and the call has at least 256 tiles, else the large tile when a row spans at
+ * least two of them and the call has at least 512 tiles, else the small one), 1 = always the small
+ * tile, 2 / 3 = the large / huge tile for every row longer than a small tile.  A measurement and test knob; results do not depend
  * on it beyond floating-point summation order.
  */
 tcuscan_status_t tcuscan_set_tile_policy(int policy);

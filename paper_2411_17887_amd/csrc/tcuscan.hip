@@ -623,35 +623,42 @@ constexpr size_t kShortRowMinRows = 8;                   // ... when there are e
 bool valid_dtype(int dt) { return dt >= 0 && dt <= 4; }
 size_t in_size(int dt) { return dt == TCUSCAN_I8_I32 ? 1 : (dt == TCUSCAN_F16_F32 || dt == TCUSCAN_BF16_F32) ? 2 : 4; }
 
-// MFMA tiles per wavefront for the two tile sizes of each dtype.  The small one is 8192 elements per
-// workgroup for every dtype; the large one keeps 32 (8-bit inputs) or 64 (16/32-bit inputs) input
-// registers per lane waiting for the carry.
+// MFMA tiles per wavefront for the three tile sizes of each dtype.  Small is 8192 elements per workgroup
+// for every dtype; large and huge keep 32 .. 128 input registers per lane waiting for the carry (the
+// longer the carry chain, the more a big tile pays: fewer status words to publish and poll per byte).
 template <int DT> struct Tiles;
-template <> struct Tiles<TCUSCAN_I8_I32>   { static constexpr int kSmall = 2, kLarge = 8;  };
-template <> struct Tiles<TCUSCAN_F16_F32>  { static constexpr int kSmall = 4, kLarge = 16; };
-template <> struct Tiles<TCUSCAN_BF16_F32> { static constexpr int kSmall = 4, kLarge = 16; };
-template <> struct Tiles<TCUSCAN_F32_F32>  { static constexpr int kSmall = 8, kLarge = 16; };
-template <> struct Tiles<TCUSCAN_I32_I32>  { static constexpr int kSmall = 8, kLarge = 16; };
+template <> struct Tiles<TCUSCAN_I8_I32>   { static constexpr int kSmall = 2, kLarge = 8,  kHuge = 16; };
+template <> struct Tiles<TCUSCAN_F16_F32>  { static constexpr int kSmall = 4, kLarge = 16, kHuge = 32; };
+template <> struct Tiles<TCUSCAN_BF16_F32> { static constexpr int kSmall = 4, kLarge = 16, kHuge = 32; };
+template <> struct Tiles<TCUSCAN_F32_F32>  { static constexpr int kSmall = 8, kLarge = 16, kHuge = 16; };
+template <> struct Tiles<TCUSCAN_I32_I32>  { static constexpr int kSmall = 8, kLarge = 16, kHuge = 16; };
 
-size_t large_tile(int dt)
+enum TileSize { kTileSmall = 0, kTileLarge = 1, kTileHuge = 2 };
+
+size_t tile_elems(int dt, int size)
 {
+    if (size == kTileSmall) return kSmallTile;
+    const bool huge = size == kTileHuge;
     switch (dt) {
-    case TCUSCAN_I8_I32:   return (size_t)Tiles<TCUSCAN_I8_I32>::kLarge * 1024 * kWaves;
+    case TCUSCAN_I8_I32:   return (size_t)(huge ? Tiles<TCUSCAN_I8_I32>::kHuge : Tiles<TCUSCAN_I8_I32>::kLarge) * 1024 * kWaves;
     case TCUSCAN_F16_F32:
-    case TCUSCAN_BF16_F32: return (size_t)Tiles<TCUSCAN_F16_F32>::kLarge * 512 * kWaves;
-    default:               return (size_t)Tiles<TCUSCAN_F32_F32>::kLarge * 256 * kWaves;
+    case TCUSCAN_BF16_F32: return (size_t)(huge ? Tiles<TCUSCAN_F16_F32>::kHuge : Tiles<TCUSCAN_F16_F32>::kLarge) * 512 * kWaves;
+    default:               return (size_t)(huge ? Tiles<TCUSCAN_F32_F32>::kHuge : Tiles<TCUSCAN_F32_F32>::kLarge) * 256 * kWaves;
     }
 }
 
-// 0 = choose by shape, 1 = always the small tile, 2 = the large tile whenever a row is longer than a small one
+// 0 = choose by shape, 1 = always the small tile, 2 / 3 = the large / huge tile whenever a row is longer
+// than a small one
 std::atomic<int> g_tile_policy{0};
 
-bool use_large(int dt, size_t rows, size_t cols)
+int choose_tile(int dt, size_t rows, size_t cols)
 {
     const int f = g_tile_policy.load(std::memory_order_relaxed);
-    if (f) return f == 2 && cols > kSmallTile;
-    const size_t lt = large_tile(dt);
-    return cols >= 2 * lt && rows * ((cols + lt - 1) / lt) >= 512;
+    if (f) return (f == 1 || cols <= kSmallTile) ? kTileSmall : (f == 2 ? kTileLarge : kTileHuge);
+    const size_t ht = tile_elems(dt, kTileHuge), lt = tile_elems(dt, kTileLarge);
+    if (cols >= 4 * ht && rows * ((cols + ht - 1) / ht) >= 256) return kTileHuge;
+    if (cols >= 2 * lt && rows * ((cols + lt - 1) / lt) >= 512) return kTileLarge;
+    return kTileSmall;
 }
 
 std::atomic<uint32_t> g_calls{0};
@@ -673,15 +680,16 @@ template <int DT> hipError_t launch_rows(Params P, bool excl, hipStream_t s)
     return launch_rows_nt<DT, 8>(P, excl, s);
 }
 
-template <int DT> hipError_t launch_dt(Params P, bool excl, bool large, hipStream_t s)
+template <int DT> hipError_t launch_dt(Params P, bool excl, int size, hipStream_t s)
 {
     if (P.rows >= kShortRowMinRows && P.cols <= kShortRowMax) return launch_rows<DT>(P, excl, s);
     // hipLaunchKernel reports this launch's own status (hipGetLastError could return a stale,
     // unrelated code left behind by another library's polling calls).
     void *args[] = {&P};
     const void *fn;
-    if (large) fn = excl ? (const void *)scan_kernel<DT, Tiles<DT>::kLarge, true> : (const void *)scan_kernel<DT, Tiles<DT>::kLarge, false>;
-    else       fn = excl ? (const void *)scan_kernel<DT, Tiles<DT>::kSmall, true> : (const void *)scan_kernel<DT, Tiles<DT>::kSmall, false>;
+    if (size == kTileHuge)       fn = excl ? (const void *)scan_kernel<DT, Tiles<DT>::kHuge, true>  : (const void *)scan_kernel<DT, Tiles<DT>::kHuge, false>;
+    else if (size == kTileLarge) fn = excl ? (const void *)scan_kernel<DT, Tiles<DT>::kLarge, true> : (const void *)scan_kernel<DT, Tiles<DT>::kLarge, false>;
+    else                         fn = excl ? (const void *)scan_kernel<DT, Tiles<DT>::kSmall, true> : (const void *)scan_kernel<DT, Tiles<DT>::kSmall, false>;
     return hipLaunchKernel(fn, dim3(P.num_tiles), dim3(kThreads), args, 0, s);
 }
 
@@ -705,8 +713,8 @@ tcuscan_status_t run(const void *d_in, void *d_out, size_t rows, size_t cols, in
     const size_t need = tcuscan_workspace_bytes(rows, cols, (tcuscan_dtype_t)dt);
     if (need && (!d_ws || ws_bytes < need || ((uintptr_t)d_ws % 8) != 0)) return TCUSCAN_ERR_WORKSPACE;
 
-    const bool large = use_large(dt, rows, cols);
-    const size_t tile = large ? large_tile(dt) : kSmallTile;
+    const int size = choose_tile(dt, rows, cols);
+    const size_t tile = tile_elems(dt, size);
     const size_t tpr = (cols + tile - 1) / tile;
     hipStream_t s = (hipStream_t)stream;
     Params P;
@@ -725,11 +733,11 @@ tcuscan_status_t run(const void *d_in, void *d_out, size_t rows, size_t cols, in
     }
     hipError_t e;
     switch (dt) {
-    case TCUSCAN_I32_I32:  e = launch_dt<TCUSCAN_I32_I32>(P, exclusive != 0, large, s); break;
-    case TCUSCAN_F16_F32:  e = launch_dt<TCUSCAN_F16_F32>(P, exclusive != 0, large, s); break;
-    case TCUSCAN_I8_I32:   e = launch_dt<TCUSCAN_I8_I32>(P, exclusive != 0, large, s); break;
-    case TCUSCAN_F32_F32:  e = launch_dt<TCUSCAN_F32_F32>(P, exclusive != 0, large, s); break;
-    default:               e = launch_dt<TCUSCAN_BF16_F32>(P, exclusive != 0, large, s); break;
+    case TCUSCAN_I32_I32:  e = launch_dt<TCUSCAN_I32_I32>(P, exclusive != 0, size, s); break;
+    case TCUSCAN_F16_F32:  e = launch_dt<TCUSCAN_F16_F32>(P, exclusive != 0, size, s); break;
+    case TCUSCAN_I8_I32:   e = launch_dt<TCUSCAN_I8_I32>(P, exclusive != 0, size, s); break;
+    case TCUSCAN_F32_F32:  e = launch_dt<TCUSCAN_F32_F32>(P, exclusive != 0, size, s); break;
+    default:               e = launch_dt<TCUSCAN_BF16_F32>(P, exclusive != 0, size, s); break;
     }
     return e == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
 }
@@ -740,11 +748,13 @@ extern "C" {
 
 size_t tcuscan_tile_elems(tcuscan_dtype_t dt) { return valid_dtype((int)dt) ? kSmallTile : 0; }
 
-size_t tcuscan_large_tile_elems(tcuscan_dtype_t dt) { return valid_dtype((int)dt) ? large_tile((int)dt) : 0; }
+size_t tcuscan_large_tile_elems(tcuscan_dtype_t dt) { return valid_dtype((int)dt) ? tile_elems((int)dt, kTileLarge) : 0; }
+
+size_t tcuscan_huge_tile_elems(tcuscan_dtype_t dt) { return valid_dtype((int)dt) ? tile_elems((int)dt, kTileHuge) : 0; }
 
 tcuscan_status_t tcuscan_set_tile_policy(int policy)
 {
-    if (policy < 0 || policy > 2) return TCUSCAN_ERR_INVALID_ARG;
+    if (policy < 0 || policy > 3) return TCUSCAN_ERR_INVALID_ARG;
     g_tile_policy.store(policy, std::memory_order_relaxed);
     return TCUSCAN_OK;
 }

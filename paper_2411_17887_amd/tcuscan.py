@@ -17,7 +17,8 @@ I32_I32, F16_F32, I8_I32, F32_F32, BF16_F32 = 0, 1, 2, 3, 4
 DTYPES = {"i32": I32_I32, "f16": F16_F32, "i8": I8_I32, "f32": F32_F32, "bf16": BF16_F32}
 
 EXPORTS = ["tcuscan_workspace_bytes", "tcuscan_workspace_init", "tcuscan_inclusive", "tcuscan_exclusive",
-           "tcuscan_batched", "tcuscan_tile_elems", "tcuscan_large_tile_elems", "tcuscan_set_tile_policy",
+           "tcuscan_batched", "tcuscan_tile_elems", "tcuscan_large_tile_elems", "tcuscan_huge_tile_elems",
+           "tcuscan_set_tile_policy",
            "tcuscan_workspace_fault", "tcuscan_matmulscan_levels", "tcuscan_compact_u32",
            "tcuscan_split_radix_sort_u32", "tcuscan_status_string"]
 
@@ -48,6 +49,8 @@ def load() -> ctypes.CDLL:
         L.tcuscan_tile_elems.restype = sz
         L.tcuscan_large_tile_elems.argtypes = [ci]
         L.tcuscan_large_tile_elems.restype = sz
+        L.tcuscan_huge_tile_elems.argtypes = [ci]
+        L.tcuscan_huge_tile_elems.restype = sz
         L.tcuscan_set_tile_policy.argtypes = [ci]
         L.tcuscan_set_tile_policy.restype = ci
         L.tcuscan_workspace_init.argtypes = [vp, sz, vp]
@@ -88,7 +91,11 @@ def large_tile_elems(dt) -> int:
     return int(load().tcuscan_large_tile_elems(_dt(dt)))
 
 
-TILE_AUTO, TILE_SMALL, TILE_LARGE = 0, 1, 2
+def huge_tile_elems(dt) -> int:
+    return int(load().tcuscan_huge_tile_elems(_dt(dt)))
+
+
+TILE_AUTO, TILE_SMALL, TILE_LARGE, TILE_HUGE = 0, 1, 2, 3
 
 
 def set_tile_policy(policy: int) -> None:

@@ -268,11 +268,12 @@ def tile_policy():
     tcuscan.set_tile_policy(tcuscan.TILE_AUTO)
 
 
+@pytest.mark.parametrize("size", ["large", "huge"])
 @pytest.mark.parametrize("kind", KINDS)
-def test_large_tile_edges(kind, tile_policy):
-    """Sizes around multiples of the large tile, with the large tile forced, inclusive and exclusive."""
-    tile_policy(tcuscan.TILE_LARGE)
-    lt = tcuscan.large_tile_elems(kind)
+def test_large_tile_edges(kind, size, tile_policy):
+    """Sizes around multiples of the large / huge tile, with that tile forced, inclusive and exclusive."""
+    tile_policy(tcuscan.TILE_LARGE if size == "large" else tcuscan.TILE_HUGE)
+    lt = tcuscan.large_tile_elems(kind) if size == "large" else tcuscan.huge_tile_elems(kind)
     assert lt % 8192 == 0 and lt > 8192
     for n in [8193, lt - 1, lt, lt + 1, 2 * lt - 3, 3 * lt + lt // 2 + 5, 70 * lt + 4097]:
         print("n =", n, flush=True)
@@ -288,11 +289,11 @@ def test_large_tile_edges(kind, tile_policy):
                 check(x, kind, run_scan(x, kind, call), exclusive=ex)
 
 
-@pytest.mark.parametrize("policy", [1, 2])
+@pytest.mark.parametrize("policy", [1, 2, 3])
 @pytest.mark.parametrize("kind", KINDS)
 def test_tile_policies_give_the_same_integers(kind, policy, tile_policy):
     tile_policy(policy)
-    rows, cols = 5, 3 * tcuscan.large_tile_elems(kind) + 777
+    rows, cols = 5, 3 * tcuscan.huge_tile_elems(kind) + 777
     if kind in INT_GEN:
         x = INT_GEN[kind](rows * cols, policy)
         check(x, kind, run_scan(x, kind, "batched", rows=rows, cols=cols), rows=rows, cols=cols)
@@ -304,9 +305,9 @@ def test_tile_policies_give_the_same_integers(kind, policy, tile_policy):
 
 def test_auto_policy_picks_the_large_tile_only_for_long_inputs():
     # observable through results only: both must be right; the sizes sit on either side of the switch
-    for kind in ("i8", "f32"):
-        lt = tcuscan.large_tile_elems(kind)
-        for n in (512 * lt - 1, 512 * lt + 1):
+    for kind in ("i8", "f32", "bf16"):
+        lt, ht = tcuscan.large_tile_elems(kind), tcuscan.huge_tile_elems(kind)
+        for n in (512 * lt - 1, 512 * lt + 1, 256 * ht - 1, 256 * ht + 1):
             x = (INT_GEN.get(kind) or TRI_GEN[kind])(n, 7)
             check(x, kind, run_scan(x, kind, "inclusive"), exact_float=kind not in INT_GEN)
 
