@@ -346,3 +346,32 @@ def test_graph_capture_replays_match_eager():
         torch.cuda.synchronize()
         check(x, kind, eager_out.cpu().numpy(), exclusive=True)
     assert tcuscan.workspace_fault(ws) == 0
+
+
+# ------------------------------------------------------------------ seeded random shapes
+
+def test_random_shapes_dtypes_and_offsets(tile_policy):
+    """300 seeded random calls: dtype, inclusive / exclusive, rows x cols (log-uniform), tile policy, pointer offsets."""
+    rng = np.random.default_rng(20241127)
+    for case in range(300):
+        kind = KINDS[int(rng.integers(0, 5))]
+        ex = bool(rng.integers(0, 2))
+        total = int(2 ** rng.uniform(0, 21))
+        rows = int(2 ** rng.uniform(0, np.log2(total) + 1e-9)) if rng.integers(0, 3) else 1
+        rows = max(1, min(rows, total))
+        cols = max(1, total // rows)
+        pol = int(rng.integers(0, 4))
+        in_off = int(rng.integers(0, 4)) if rng.integers(0, 4) == 0 else 0
+        out_off = int(rng.integers(0, 4)) if rng.integers(0, 4) == 0 else 0
+        tile_policy(pol)
+        call = ("batched_exclusive" if ex else "batched") if rows > 1 else ("exclusive" if ex else "inclusive")
+        print(f"case {case}: {kind} {call} {rows}x{cols} policy {pol} offsets {in_off},{out_off}", flush=True)
+        n = rows * cols
+        if kind in INT_GEN:
+            x = INT_GEN[kind](n, case)
+            got = run_scan(x, kind, call, rows=rows, cols=cols, in_offset=in_off, out_offset=out_off)
+            check(x, kind, got, exclusive=ex, rows=rows, cols=cols)
+        else:
+            x = TRI_GEN[kind](n, case)
+            got = run_scan(x, kind, call, rows=rows, cols=cols, in_offset=in_off, out_offset=out_off)
+            check(x, kind, got, exclusive=ex, rows=rows, cols=cols, exact_float=True)
