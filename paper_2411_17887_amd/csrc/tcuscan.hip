@@ -655,10 +655,22 @@ int choose_tile(int dt, size_t rows, size_t cols)
 {
     const int f = g_tile_policy.load(std::memory_order_relaxed);
     if (f) return (f == 1 || cols <= kSmallTile) ? kTileSmall : (f == 2 ? kTileLarge : kTileHuge);
-    const size_t ht = tile_elems(dt, kTileHuge), lt = tile_elems(dt, kTileLarge);
-    if (cols >= 4 * ht && rows * ((cols + ht - 1) / ht) >= 256) return kTileHuge;
-    if (cols >= 2 * lt && rows * ((cols + lt - 1) / lt) >= 512) return kTileLarge;
-    return kTileSmall;
+    // Measured on MI355X (2^27 .. 2^28 elements split into rows of 2^14 .. 2^24): short carry chains run best
+    // on small tiles (loads and stores alternate at a finer grain), long ones on big tiles (fewer status
+    // words per byte); the crossover depends on the input width.  Big tiles need enough tiles to fill the chip.
+    const size_t esz = in_size(dt);
+    const size_t to_large = esz == 2 ? ((size_t)1 << 18) + 1 : esz == 1 ? 32768 : 16384;
+    const size_t to_huge  = ((size_t)1 << 22) + 1;
+    int want = cols >= to_huge ? kTileHuge : cols >= to_large ? kTileLarge : kTileSmall;
+    if (want == kTileHuge) {
+        const size_t ht = tile_elems(dt, kTileHuge);
+        if (rows * ((cols + ht - 1) / ht) < 256) want = kTileLarge;
+    }
+    if (want == kTileLarge) {
+        const size_t lt = tile_elems(dt, kTileLarge);
+        if (rows * ((cols + lt - 1) / lt) < 512) want = kTileSmall;
+    }
+    return want;
 }
 
 std::atomic<uint32_t> g_calls{0};

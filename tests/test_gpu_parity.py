@@ -169,6 +169,14 @@ def test_short_rows_one_per_wavefront(kind, rows, cols):
             check(x, kind, run_scan(x, kind, call, rows=rows, cols=cols), exclusive=ex, rows=rows, cols=cols)
 
 
+@pytest.mark.parametrize("kind", KINDS)
+def test_batched_rows_that_are_exact_multiples_of_the_tiles(kind):
+    """Row lengths that are whole numbers of small / large tiles, on either side of the policy's switch points."""
+    for rows, cols in [(3, 16384), (64, 16384), (40, 32768), (17, 65536), (5, (1 << 18)), (3, (1 << 18) + 8192), (2, 1 << 20)]:
+        x = (INT_GEN.get(kind) or TRI_GEN[kind])(rows * cols, rows)
+        check(x, kind, run_scan(x, kind, "batched", rows=rows, cols=cols), rows=rows, cols=cols, exact_float=kind not in INT_GEN)
+
+
 def test_batched_row_equals_unbatched_scan_of_that_row():
     rows, cols = 6, 30011
     x = inputs.int32_small(rows * cols, 9)
@@ -307,7 +315,7 @@ def test_auto_policy_picks_the_large_tile_only_for_long_inputs():
     # observable through results only: both must be right; the sizes sit on either side of the switch
     for kind in ("i8", "f32", "bf16"):
         lt, ht = tcuscan.large_tile_elems(kind), tcuscan.huge_tile_elems(kind)
-        for n in (512 * lt - 1, 512 * lt + 1, 256 * ht - 1, 256 * ht + 1):
+        for n in (512 * lt - 1, 512 * lt + 1, 256 * ht - 1, 256 * ht + 1, (1 << 22) - 1, (1 << 22) + 1):
             x = (INT_GEN.get(kind) or TRI_GEN[kind])(n, 7)
             check(x, kind, run_scan(x, kind, "inclusive"), exact_float=kind not in INT_GEN)
 
