@@ -36,7 +36,7 @@ DESCR = {
 }
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the same
 # counters on a plain 1 GiB device copy (fetch x2.000, write x1.000); profiles/scan_kernel_bench_default.md.
-MEASURED_TRAFFIC_BYTES = {"C5": 1612541436, "C3": 1350837535, "C4": 811854414, "C2": 101708307}
+MEASURED_TRAFFIC_BYTES = {"C5": 1627020960, "C3": 1350739081, "C4": 811956778, "C2": 101671616}
 
 
 def device_input(x: np.ndarray, kind: str):
