@@ -508,17 +508,17 @@ template <> struct MinWaves<TCUSCAN_I8_I32, 8>    { static constexpr int value =
 template <> struct MinWaves<TCUSCAN_F16_F32, 16>  { static constexpr int value = 4; };
 template <> struct MinWaves<TCUSCAN_BF16_F32, 16> { static constexpr int value = 4; };
 
-template <int DT, int NT, bool EXCL>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(MinWaves<DT, NT>::value)))
+template <int DT, int NT, bool EXCL, int W>
+__global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(MinWaves<DT, NT>::value)))
 void scan_kernel(Params P)
 {
     using T = Tr<DT>;
     using A = typename T::acc;
     constexpr uint32_t kEPW = NT * Geo<DT>::kTileElems;   // elements per wavefront
-    constexpr uint32_t kWgElems = kEPW * kWaves;          // elements per workgroup tile
+    constexpr uint32_t kWgElems = kEPW * W;               // elements per workgroup tile (W wavefronts)
 
-    __shared__ u32x4 stage[kWaves][Geo<DT>::kStage];
-    __shared__ uint32_t s_wave_total[kWaves];
+    __shared__ u32x4 stage[W][Geo<DT>::kStage];
+    __shared__ uint32_t s_wave_total[W];
     __shared__ uint32_t s_bcast;
 
     const int lane = threadIdx.x & 63;
@@ -549,7 +549,7 @@ void scan_kernel(Params P)
     __syncthreads();
     A wave_off = acc_from_bits<A>(0u), wg_total = acc_from_bits<A>(0u);
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
+    for (int w = 0; w < W; ++w) {
         const A v = acc_from_bits<A>(s_wave_total[w]);
         if (w < wave) wave_off = acc_add(wave_off, v);
         wg_total = acc_add(wg_total, v);
@@ -623,29 +623,42 @@ constexpr size_t kShortRowMinRows = 8;                   // ... when there are e
 bool valid_dtype(int dt) { return dt >= 0 && dt <= 4; }
 size_t in_size(int dt) { return dt == TCUSCAN_I8_I32 ? 1 : (dt == TCUSCAN_F16_F32 || dt == TCUSCAN_BF16_F32) ? 2 : 4; }
 
-// MFMA tiles per wavefront for the three tile sizes of each dtype.  Small is 8192 elements per workgroup
-// for every dtype; large and huge keep 32 .. 128 input registers per lane waiting for the carry (the
-// longer the carry chain, the more a big tile pays: fewer status words to publish and poll per byte).
-template <int DT> struct Tiles;
-template <> struct Tiles<TCUSCAN_I8_I32>   { static constexpr int kSmall = 2, kLarge = 8,  kHuge = 16; };
-template <> struct Tiles<TCUSCAN_F16_F32>  { static constexpr int kSmall = 4, kLarge = 16, kHuge = 32; };
-template <> struct Tiles<TCUSCAN_BF16_F32> { static constexpr int kSmall = 4, kLarge = 16, kHuge = 32; };
-template <> struct Tiles<TCUSCAN_F32_F32>  { static constexpr int kSmall = 8, kLarge = 16, kHuge = 16; };
-template <> struct Tiles<TCUSCAN_I32_I32>  { static constexpr int kSmall = 8, kLarge = 16, kHuge = 16; };
+// MFMA tiles per wavefront and wavefronts per workgroup for the three tile sizes of each dtype.  Small is
+// 8192 elements per workgroup for every dtype; large and huge keep 32 .. 128 input registers per lane
+// waiting for the carry (the longer the carry chain, the more a big tile pays: fewer status words to
+// publish and poll per byte).  For 32-bit inputs "huge" is the large tile in its 8-wavefront form (half
+// the run per wavefront), which measures 5 % faster on long chains and 5 % slower on short ones.
+template <int DT> struct Tiles;   // MFMA tiles per wavefront (k..) and wavefronts per workgroup (w..) for each tile size
+template <> struct Tiles<TCUSCAN_I8_I32>   { static constexpr int kSmall = 2, kLarge = 8,  kHuge = 16, wSmall = 4, wLarge = 4, wHuge = 4; };
+template <> struct Tiles<TCUSCAN_F16_F32>  { static constexpr int kSmall = 4, kLarge = 16, kHuge = 32, wSmall = 4, wLarge = 4, wHuge = 4; };
+template <> struct Tiles<TCUSCAN_BF16_F32> { static constexpr int kSmall = 4, kLarge = 16, kHuge = 32, wSmall = 4, wLarge = 4, wHuge = 4; };
+template <> struct Tiles<TCUSCAN_F32_F32>  { static constexpr int kSmall = 8, kLarge = 16, kHuge = 8,  wSmall = 4, wLarge = 4, wHuge = 8; };
+template <> struct Tiles<TCUSCAN_I32_I32>  { static constexpr int kSmall = 8, kLarge = 16, kHuge = 8,  wSmall = 4, wLarge = 4, wHuge = 8; };
 
 enum TileSize { kTileSmall = 0, kTileLarge = 1, kTileHuge = 2 };
 
+template <int DT> size_t tile_elems_dt(int size)
+{
+    using Ti = Tiles<DT>;
+    const size_t per_tile = Geo<DT>::kTileElems;
+    return size == kTileHuge ? per_tile * Ti::kHuge * Ti::wHuge : size == kTileLarge ? per_tile * Ti::kLarge * Ti::wLarge
+                                                                                    : per_tile * Ti::kSmall * Ti::wSmall;
+}
+
 size_t tile_elems(int dt, int size)
 {
-    if (size == kTileSmall) return kSmallTile;
-    const bool huge = size == kTileHuge;
     switch (dt) {
-    case TCUSCAN_I8_I32:   return (size_t)(huge ? Tiles<TCUSCAN_I8_I32>::kHuge : Tiles<TCUSCAN_I8_I32>::kLarge) * 1024 * kWaves;
-    case TCUSCAN_F16_F32:
-    case TCUSCAN_BF16_F32: return (size_t)(huge ? Tiles<TCUSCAN_F16_F32>::kHuge : Tiles<TCUSCAN_F16_F32>::kLarge) * 512 * kWaves;
-    default:               return (size_t)(huge ? Tiles<TCUSCAN_F32_F32>::kHuge : Tiles<TCUSCAN_F32_F32>::kLarge) * 256 * kWaves;
+    case TCUSCAN_I8_I32:   return tile_elems_dt<TCUSCAN_I8_I32>(size);
+    case TCUSCAN_F16_F32:  return tile_elems_dt<TCUSCAN_F16_F32>(size);
+    case TCUSCAN_BF16_F32: return tile_elems_dt<TCUSCAN_BF16_F32>(size);
+    case TCUSCAN_F32_F32:  return tile_elems_dt<TCUSCAN_F32_F32>(size);
+    default:               return tile_elems_dt<TCUSCAN_I32_I32>(size);
     }
 }
+static_assert(Geo<TCUSCAN_I8_I32>::kTileElems * Tiles<TCUSCAN_I8_I32>::kSmall * Tiles<TCUSCAN_I8_I32>::wSmall == kSmallTile &&
+              Geo<TCUSCAN_F16_F32>::kTileElems * Tiles<TCUSCAN_F16_F32>::kSmall * Tiles<TCUSCAN_F16_F32>::wSmall == kSmallTile &&
+              Geo<TCUSCAN_F32_F32>::kTileElems * Tiles<TCUSCAN_F32_F32>::kSmall * Tiles<TCUSCAN_F32_F32>::wSmall == kSmallTile,
+              "the small tile is the same number of elements for every dtype");
 
 // 0 = choose by shape, 1 = always the small tile, 2 / 3 = the large / huge tile whenever a row is longer
 // than a small one
@@ -699,10 +712,12 @@ template <int DT> hipError_t launch_dt(Params P, bool excl, int size, hipStream_
     // unrelated code left behind by another library's polling calls).
     void *args[] = {&P};
     const void *fn;
-    if (size == kTileHuge)       fn = excl ? (const void *)scan_kernel<DT, Tiles<DT>::kHuge, true>  : (const void *)scan_kernel<DT, Tiles<DT>::kHuge, false>;
-    else if (size == kTileLarge) fn = excl ? (const void *)scan_kernel<DT, Tiles<DT>::kLarge, true> : (const void *)scan_kernel<DT, Tiles<DT>::kLarge, false>;
-    else                         fn = excl ? (const void *)scan_kernel<DT, Tiles<DT>::kSmall, true> : (const void *)scan_kernel<DT, Tiles<DT>::kSmall, false>;
-    return hipLaunchKernel(fn, dim3(P.num_tiles), dim3(kThreads), args, 0, s);
+    using Ti = Tiles<DT>;
+    int waves;
+    if (size == kTileHuge)       { waves = Ti::wHuge;  fn = excl ? (const void *)scan_kernel<DT, Ti::kHuge, true, Ti::wHuge>   : (const void *)scan_kernel<DT, Ti::kHuge, false, Ti::wHuge>; }
+    else if (size == kTileLarge) { waves = Ti::wLarge; fn = excl ? (const void *)scan_kernel<DT, Ti::kLarge, true, Ti::wLarge> : (const void *)scan_kernel<DT, Ti::kLarge, false, Ti::wLarge>; }
+    else                         { waves = Ti::wSmall; fn = excl ? (const void *)scan_kernel<DT, Ti::kSmall, true, Ti::wSmall> : (const void *)scan_kernel<DT, Ti::kSmall, false, Ti::wSmall>; }
+    return hipLaunchKernel(fn, dim3(P.num_tiles), dim3(64 * waves), args, 0, s);
 }
 
 hipError_t launch_fill(void *d, size_t bytes, hipStream_t s)
