@@ -7,24 +7,27 @@
 // while the carry chain's latency is being paid.
 //
 //   level 0  (Algorithm 1, up-sweep t = 0; BatchMatMul with L_s)
-//            A 1 KiB run of input is viewed column-major as 16 columns of S consecutive
-//            elements (S = 16 / 32 / 64 for 4 / 2 / 1-byte inputs).  Each column is
-//            replaced by its local prefix sums by an MFMA  D = L * T  whose constant left
-//            operand holds rows of the all-ones lower-triangular matrix (strictly lower
-//            for the exclusive scan).  Data reach the MFMA operand layout through LDS:
-//            global loads are 128-bit and fully coalesced, the LDS read-back gives lane
-//            (j, c) the j-th quarter of column c.  The tile total that is published early is
-//            the product with the all-ones matrix (every row of the result is the row of
-//            column totals) for the MFMA-native types, plain vector adds for 32-bit inputs.
-//   level 1  (up-sweep t = 1 and its down-sweep)   the 16 column totals of a tile sit in
-//            one 16-lane DPP row; a row_shr scan turns them into per-column carries.
-//   level 2  tile totals inside a wavefront, wavefront totals through LDS.
-//   level 3+ (remaining up-/down-sweep rounds; Section 2.2 steps 2-4 for lengths that are
+//            A 1 KiB run of input is 64 granules of 16 bytes, s = 16 / 8 / 4 elements each for
+//            1 / 2 / 4-byte inputs, and lane l of the wavefront loads granule l (128-bit, fully
+//            coalesced).  Every granule is replaced by its local prefix sums by an MFMA
+//            D = (I_4 (x) L_s) * T : the lane's granule is its share of the B operand as it is, the
+//            constant left operand holds the rows of the all-ones lower-triangular blocks
+//            (strictly lower for the exclusive scan) -- 64 s x s products per instruction group.
+//            The tile total that is published early is the product with the all-ones matrix
+//            (every row of the result is the row of column totals) for the MFMA-native types,
+//            plain vector adds for 32-bit inputs.
+//   level 1-2 (up-sweep t = 1, 2 and their down-sweep)   the 64 granule totals of a tile -- a second
+//            product with a 0/1 matrix puts each where its carry is needed -- are scanned with DPP
+//            row shifts inside 16-lane rows; the four row totals are wave-uniform.
+//   level 3  tile totals inside a wavefront (a running carry), wavefront totals through LDS.
+//   level 4+ (remaining up-/down-sweep rounds; Section 2.2 steps 2-4 for lengths that are
 //            not powers of s)  one 64-bit status word per workgroup tile, published with
 //            relaxed agent-scope atomics and resolved by a decoupled look-back.
 //   down-sweep  (B_s: broadcast-add of a carry)  is a vector add, as the paper's
 //            discussion section recommends, fused before the store.
-//   store    results go back through LDS so that every lane writes 16 contiguous bytes.
+//   store    straight from the MFMA result registers: the rows of the triangular blocks are dealt
+//            to result rows so that each store instruction writes 1 KiB of consecutive outputs
+//            (partial lines per instruction measured 30 % slower).  No data pass through LDS.
 //
 // The C entry points at the bottom validate arguments on the host and launch this kernel.
 
@@ -94,20 +97,24 @@ template <class A, int CTRL> __device__ __forceinline__ A dpp_shr(A v) { return 
 // Sum over the 64 lanes, returned wave-uniform.  Row-local DPP shifts give every row's total in its
 // lane 15; row_bcast15 / row_bcast31 fold the four row totals into lane 63.
 constexpr int kRowBcast15 = 0x142, kRowBcast31 = 0x143;
-template <class A> __device__ __forceinline__ A wave_sum(A v)
-{
+template <class A> __device__ __forceinline__ A wave_inclusive_scan(A v)
+{   // lane l receives v[0] + ... + v[l]
     v = acc_add(v, dpp_shr<A, kRowShr + 1>(v));
     v = acc_add(v, dpp_shr<A, kRowShr + 2>(v));
     v = acc_add(v, dpp_shr<A, kRowShr + 4>(v));
     v = acc_add(v, dpp_shr<A, kRowShr + 8>(v));
     v = acc_add(v, acc_from_bits<A>((uint32_t)__builtin_amdgcn_update_dpp(0, (int)acc_bits(v), kRowBcast15, 0xa, 0xf, false)));
     v = acc_add(v, acc_from_bits<A>((uint32_t)__builtin_amdgcn_update_dpp(0, (int)acc_bits(v), kRowBcast31, 0xc, 0xf, false)));
-    return acc_from_bits<A>((uint32_t)__builtin_amdgcn_readlane((int)acc_bits(v), 63));
+    return v;
 }
-
-template <class A> __device__ __forceinline__ A lane_value(A v, int src_lane)
-{   // every lane receives v of lane src_lane (per-lane selectable source)
-    return acc_from_bits<A>((uint32_t)__builtin_amdgcn_ds_bpermute(src_lane << 2, (int)acc_bits(v)));
+template <class A> __device__ __forceinline__ A wave_sum(A v)
+{
+    return acc_from_bits<A>((uint32_t)__builtin_amdgcn_readlane((int)acc_bits(wave_inclusive_scan(v)), 63));
+}
+constexpr int kWaveShr1 = 0x138;   // DPP control: shift right by one lane across the whole wavefront
+template <class A> __device__ __forceinline__ A wave_shift_up(A v)
+{   // lane l receives v[l - 1], lane 0 receives 0
+    return dpp_shr<A, kWaveShr1>(v);
 }
 
 template <class A> __device__ __forceinline__ A uniform_from_lane(A v, int lane)
@@ -117,12 +124,23 @@ template <class A> __device__ __forceinline__ A uniform_from_lane(A v, int lane)
 
 // ------------------------------------------------------------------- dtype traits
 //
-// A tile is 64 granules of 16 bytes.  Lane (j, c) = (lane / 16, lane % 16) feeds the MFMA
-// with granule 4c + j, i.e. the j-th quarter of column c; the K slot of element i of that
-// granule pairs with the same (j, i) slot of the constant operand, so the constant is
-// built as  A[row][slot(j, i)] = [pos(j, i) <= row]  (or < for the exclusive scan) with
-// pos = position of the element inside its column.  Output block p holds rows
-// 16p .. 16p+15; lane (q, c) register r of block p is row 16p + 4q + r of column c.
+// A tile is 64 granules of 16 bytes (G elements each), and lane l = 16j + c loads granule l.  The MFMA
+// takes lane (j, c)'s granule as K slots (j, 0..G-1) of column c of its B operand, so a column holds the
+// four granules c, 16+c, 32+c, 48+c.  Level 0 (BatchMatMul with L_s, s = G) scans every granule by
+// itself: the constant A operand is block-diagonal, row (j, i) = [same j, slot i' <= i]  (< for the
+// exclusive scan) -- I_4 (x) L_G, 64 independent s x s products in one pass over the matrix unit.
+//
+// The rows are dealt to the MFMA's 16-row result blocks so that one store instruction of the wavefront
+// writes 1 KiB of consecutive outputs.  Lane (q, c) register r of block p is result row 4q + r; it is
+// made to be element 4 * sub(p, q) + r of granule (jmap(p, q), c):
+//      8-bit  (G = 16, 4 blocks)   jmap = p,            sub = q
+//     16-bit  (G =  8, 2 blocks)   jmap = 2p + q / 2,   sub = q % 2
+//     32-bit  (G =  4, 1 block)    jmap = q,            sub = 0     (every lane keeps its own granule)
+// so the four results of a lane in block p are outputs G * (16 jmap + c) + 4 sub .. +3 of the tile.
+//
+// A second constant operand ("tot") delivers the granule totals where they are needed: result row
+// 4q + r of  tot * T  is the total of granule (jmap(r, q), c), i.e. register p of lane (q, c) is the total
+// of the granule whose results the lane holds in block p.
 
 template <int DT> struct Tr;
 
@@ -134,13 +152,38 @@ __device__ __forceinline__ uint64_t low_slots(uint64_t ones, int cnt, int slots,
     cnt = cnt < 0 ? 0 : (cnt > slots ? slots : cnt);
     return cnt == 0 ? 0ull : ones >> (bits_per_slot * (slots - cnt));
 }
-// number of leading K slots of lane group j that row `row` of the (strictly) lower triangular matrix covers
-__device__ __forceinline__ int covered(int row, int j, int g, bool excl) { return row - g * j + (excl ? 0 : 1); }
+
+// Shared by the two 16-bit types: which granule row / which half a result row of block p stands for.
+struct Map16 {
+    static __device__ __forceinline__ int jmap(int p, int q) { return 2 * p + (q >> 1); }
+    static __device__ __forceinline__ int sub(int, int q) { return q & 1; }
+};
+
+// Operands of a 16-bit type as raw words; `one` is the 16-bit pattern of 1.0 repeated four times.
+struct AWords16 { u32x4 a[2]; u32x4 ones; u32x4 tot; };
+__device__ __forceinline__ AWords16 make16(int lane, bool excl, uint64_t one)
+{
+    AWords16 A; const int m = lane & 15, jj = lane >> 4;       // this lane supplies row m, K slots (jj, 0..7)
+    const uint32_t o = (uint32_t)one;
+    A.ones = u32x4{o, o, o, o};
+    for (int p = 0; p < 2; ++p) {
+        const int j = Map16::jmap(p, m >> 2), i = 4 * Map16::sub(p, m >> 2) + (m & 3);
+        const int cnt = jj == j ? i + (excl ? 0 : 1) : 0;
+        const uint64_t lo = low_slots(one, cnt, 4, 16), hi = low_slots(one, cnt - 4, 4, 16);
+        A.a[p] = u32x4{(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)};
+    }
+    const int r = m & 3;
+    const uint32_t t = (r < 2 && jj == Map16::jmap(r, m >> 2)) ? o : 0u;
+    A.tot = u32x4{t, t, t, t};
+    return A;
+}
 
 template <> struct Tr<TCUSCAN_F16_F32> {
     using acc = float; using acc4 = f32x4;
     static constexpr int kEsz = 2, kG = 8, kBlocks = 2;
-    struct AConst { f16x8 a[kBlocks]; f16x8 ones; };
+    static constexpr bool kLinear = false;
+    using Map = Map16;
+    struct AConst { f16x8 a[kBlocks]; f16x8 ones; f16x8 tot; };
     using red = f32x4;
     static __device__ __forceinline__ red red_init() { return f32x4{0.f, 0.f, 0.f, 0.f}; }
     static __device__ __forceinline__ red red_add(const AConst &A, red r, u32x4 b)
@@ -148,15 +191,14 @@ template <> struct Tr<TCUSCAN_F16_F32> {
         return __builtin_amdgcn_mfma_f32_16x16x32_f16(A.ones, bits<f16x8>(b), r, 0, 0, 0);
     }
     static __device__ __forceinline__ acc red_lane(red r, int lane) { return lane < 16 ? r[0] : 0.f; }
+    static __device__ __forceinline__ red totals(const AConst &A, u32x4 b)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(A.tot, bits<f16x8>(b), red_init(), 0, 0, 0);
+    }
     static __device__ AConst make(int lane, bool excl)
     {
-        AConst A; int m = lane & 15, j = lane >> 4;
-        A.ones = bits<f16x8>(u32x4{0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0x3C003C00u});
-        for (int p = 0; p < kBlocks; ++p) {
-            const int cnt = covered(16 * p + m, j, kG, excl);
-            const uint64_t lo = low_slots(0x3C003C003C003C00ull, cnt, 4, 16), hi = low_slots(0x3C003C003C003C00ull, cnt - 4, 4, 16);
-            A.a[p] = bits<f16x8>(u32x4{(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)});   // 1.0h
-        }
+        const AWords16 w = make16(lane, excl, 0x3C003C003C003C00ull);       // 1.0h
+        AConst A; A.a[0] = bits<f16x8>(w.a[0]); A.a[1] = bits<f16x8>(w.a[1]); A.ones = bits<f16x8>(w.ones); A.tot = bits<f16x8>(w.tot);
         return A;
     }
     static __device__ __forceinline__ void mma(const AConst &A, u32x4 b, int, bool, acc4 (&d)[kBlocks])
@@ -165,13 +207,14 @@ template <> struct Tr<TCUSCAN_F16_F32> {
         f16x8 bv = bits<f16x8>(b);
         for (int p = 0; p < kBlocks; ++p) d[p] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A.a[p], bv, z, 0, 0, 0);
     }
-    static __device__ __forceinline__ acc last(u32x4 b) { return (float)bits<f16x8>(b)[kG - 1]; }
 };
 
 template <> struct Tr<TCUSCAN_BF16_F32> {
     using acc = float; using acc4 = f32x4;
     static constexpr int kEsz = 2, kG = 8, kBlocks = 2;
-    struct AConst { bf16x8 a[kBlocks]; bf16x8 ones; };
+    static constexpr bool kLinear = false;
+    using Map = Map16;
+    struct AConst { bf16x8 a[kBlocks]; bf16x8 ones; bf16x8 tot; };
     using red = f32x4;
     static __device__ __forceinline__ red red_init() { return f32x4{0.f, 0.f, 0.f, 0.f}; }
     static __device__ __forceinline__ red red_add(const AConst &A, red r, u32x4 b)
@@ -179,15 +222,14 @@ template <> struct Tr<TCUSCAN_BF16_F32> {
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(A.ones, bits<bf16x8>(b), r, 0, 0, 0);
     }
     static __device__ __forceinline__ acc red_lane(red r, int lane) { return lane < 16 ? r[0] : 0.f; }
+    static __device__ __forceinline__ red totals(const AConst &A, u32x4 b)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(A.tot, bits<bf16x8>(b), red_init(), 0, 0, 0);
+    }
     static __device__ AConst make(int lane, bool excl)
     {
-        AConst A; int m = lane & 15, j = lane >> 4;
-        A.ones = bits<bf16x8>(u32x4{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u});
-        for (int p = 0; p < kBlocks; ++p) {
-            const int cnt = covered(16 * p + m, j, kG, excl);
-            const uint64_t lo = low_slots(0x3F803F803F803F80ull, cnt, 4, 16), hi = low_slots(0x3F803F803F803F80ull, cnt - 4, 4, 16);
-            A.a[p] = bits<bf16x8>(u32x4{(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)});  // bf16 1.0
-        }
+        const AWords16 w = make16(lane, excl, 0x3F803F803F803F80ull);       // bf16 1.0
+        AConst A; A.a[0] = bits<bf16x8>(w.a[0]); A.a[1] = bits<bf16x8>(w.a[1]); A.ones = bits<bf16x8>(w.ones); A.tot = bits<bf16x8>(w.tot);
         return A;
     }
     static __device__ __forceinline__ void mma(const AConst &A, u32x4 b, int, bool, acc4 (&d)[kBlocks])
@@ -196,13 +238,17 @@ template <> struct Tr<TCUSCAN_BF16_F32> {
         bf16x8 bv = bits<bf16x8>(b);
         for (int p = 0; p < kBlocks; ++p) d[p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A.a[p], bv, z, 0, 0, 0);
     }
-    static __device__ __forceinline__ acc last(u32x4 b) { return bits<float>(b[3] & 0xFFFF0000u); }
 };
 
 template <> struct Tr<TCUSCAN_I8_I32> {
     using acc = uint32_t; using acc4 = i32x4;
     static constexpr int kEsz = 1, kG = 16, kBlocks = 4;
-    struct AConst { i32x4 a[kBlocks]; i32x4 ones; };
+    static constexpr bool kLinear = false;
+    struct Map {
+        static __device__ __forceinline__ int jmap(int p, int) { return p; }
+        static __device__ __forceinline__ int sub(int, int q) { return q; }
+    };
+    struct AConst { i32x4 a[kBlocks]; i32x4 ones; i32x4 tot; };
     using red = i32x4;
     static __device__ __forceinline__ red red_init() { return i32x4{0, 0, 0, 0}; }
     static __device__ __forceinline__ red red_add(const AConst &A, red r, u32x4 b)
@@ -210,15 +256,21 @@ template <> struct Tr<TCUSCAN_I8_I32> {
         return __builtin_amdgcn_mfma_i32_16x16x64_i8(A.ones, bits<i32x4>(b), r, 0, 0, 0);
     }
     static __device__ __forceinline__ acc red_lane(red r, int lane) { return lane < 16 ? (uint32_t)r[0] : 0u; }
+    static __device__ __forceinline__ red totals(const AConst &A, u32x4 b)
+    {
+        return __builtin_amdgcn_mfma_i32_16x16x64_i8(A.tot, bits<i32x4>(b), red_init(), 0, 0, 0);
+    }
     static __device__ AConst make(int lane, bool excl)
     {
-        AConst A; int m = lane & 15, j = lane >> 4;
+        AConst A; const int m = lane & 15, jj = lane >> 4;     // this lane supplies row m, K slots (jj, 0..15)
         A.ones = i32x4{0x01010101, 0x01010101, 0x01010101, 0x01010101};
         for (int p = 0; p < kBlocks; ++p) {
-            const int cnt = covered(16 * p + m, j, kG, excl);
+            const int cnt = jj == p ? m + (excl ? 0 : 1) : 0;  // row m of block p is element m of granule row p
             const uint64_t lo = low_slots(0x0101010101010101ull, cnt, 8, 8), hi = low_slots(0x0101010101010101ull, cnt - 8, 8, 8);
             A.a[p] = i32x4{(int)(uint32_t)lo, (int)(uint32_t)(lo >> 32), (int)(uint32_t)hi, (int)(uint32_t)(hi >> 32)};
         }
+        const int t = jj == (m & 3) ? 0x01010101 : 0;          // row 4q + r: total of granule row r
+        A.tot = i32x4{t, t, t, t};
         return A;
     }
     static __device__ __forceinline__ void mma(const AConst &A, u32x4 b, int, bool, acc4 (&d)[kBlocks])
@@ -227,13 +279,19 @@ template <> struct Tr<TCUSCAN_I8_I32> {
         i32x4 bv = bits<i32x4>(b);
         for (int p = 0; p < kBlocks; ++p) d[p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A.a[p], bv, z, 0, 0, 0);
     }
-    static __device__ __forceinline__ acc last(u32x4 b) { return (uint32_t)(int32_t)(int8_t)(b[3] >> 24); }
 };
 
 template <> struct Tr<TCUSCAN_F32_F32> {
     using acc = float; using acc4 = f32x4;
     static constexpr int kEsz = 4, kG = 4, kBlocks = 1;
-    // The K = 4 product p takes element p of every lane's granule: slot (j, p) <-> position 4j + p.
+    // A granule is 4 elements: level 0 is s = 4, and lane (q, c) holds the four results of the granule it
+    // loaded.  The K = 4 product p takes element p of every lane's granule: slot (j, p) <-> element p of
+    // the granule of lane group j.
+    static constexpr bool kLinear = true;     // lane l keeps granule l from load to store
+    struct Map {
+        static __device__ __forceinline__ int jmap(int, int q) { return q; }
+        static __device__ __forceinline__ int sub(int, int) { return 0; }
+    };
     struct AConst { float a[4]; };
     using red = float;      // 32-bit inputs: the tile total is four vector adds per granule
     static __device__ __forceinline__ red red_init() { return 0.f; }
@@ -245,7 +303,7 @@ template <> struct Tr<TCUSCAN_F32_F32> {
     static __device__ AConst make(int lane, bool excl)
     {
         AConst A; int m = lane & 15, j = lane >> 4;
-        for (int p = 0; p < 4; ++p) { int pos = 4 * j + p; A.a[p] = (excl ? pos < m : pos <= m) ? 1.0f : 0.0f; }
+        for (int p = 0; p < 4; ++p) A.a[p] = (j == (m >> 2) && (excl ? p < (m & 3) : p <= (m & 3))) ? 1.0f : 0.0f;
         return A;
     }
     static __device__ __forceinline__ void mma(const AConst &A, u32x4 b, int, bool, acc4 (&d)[kBlocks])
@@ -254,12 +312,13 @@ template <> struct Tr<TCUSCAN_F32_F32> {
         for (int p = 0; p < 4; ++p) r = __builtin_amdgcn_mfma_f32_16x16x4f32(A.a[p], bits<float>(b[p]), r, 0, 0, 0);
         d[0] = r;
     }
-    static __device__ __forceinline__ acc last(u32x4 b) { return bits<float>(b[3]); }
 };
 
 template <> struct Tr<TCUSCAN_I32_I32> {
     using acc = uint32_t; using acc4 = i32x4;
     static constexpr int kEsz = 4, kG = 4, kBlocks = 1;
+    static constexpr bool kLinear = true;    // s = 4, as for fp32
+    using Map = Tr<TCUSCAN_F32_F32>::Map;
     // int32 has no MFMA of its own: x = sum_p 2^(8p) * byte_p(x) (mod 2^32), every byte plane is
     // scanned by an i8 MFMA and the planes are recombined with shifts.  The i8 MFMA is signed, so
     // byte b enters as b - 128 (bit 7 flipped) and 128 * (number of summed elements) is added back.
@@ -271,7 +330,7 @@ template <> struct Tr<TCUSCAN_I32_I32> {
     static __device__ AConst make(int lane, bool excl)
     {
         int m = lane & 15, j = lane >> 4;
-        const uint64_t lo = low_slots(0x01010101ull, covered(m, j, kG, excl), 4, 8);
+        const uint64_t lo = j == (m >> 2) ? low_slots(0x01010101ull, (m & 3) + (excl ? 0 : 1), 4, 8) : 0ull;
         AConst A; A.a = (long)lo;                 // K slots 4..7 of every lane are unused (zero on both sides)
         return A;
     }
@@ -285,20 +344,13 @@ template <> struct Tr<TCUSCAN_I32_I32> {
             uint32_t hi = __builtin_amdgcn_perm(x3, x2, 0x00000c0cu | ((4u + p) << 24) | ((uint32_t)p << 16));
             pl[p] = __builtin_amdgcn_mfma_i32_16x16x32_i8(A.a, (long)(uint64_t)(lo | hi), z, 0, 0, 0);
         }
-        int q = lane >> 4;
         for (int r = 0; r < 4; ++r) {
-            uint32_t cnt = (uint32_t)(4 * q + r) + (excl ? 0u : 1u);          // elements summed into row 4q + r
+            uint32_t cnt = (uint32_t)r + (excl ? 0u : 1u);                    // elements summed into row 4q + r
             uint32_t v = (uint32_t)pl[0][r] + ((uint32_t)pl[1][r] << 8) + ((uint32_t)pl[2][r] << 16) + ((uint32_t)pl[3][r] << 24);
             d[0][r] = (int)(v + cnt * 0x80808080u);                           // 128 * cnt on every byte plane
         }
     }
-    static __device__ __forceinline__ acc last(u32x4 b) { return b[3]; }
 };
-
-// LDS staging positions (in granules).  One pad granule per 2^shift granules keeps both the
-// linear (lane l <-> granule l) and the operand-order (lane (j,c) <-> granule 4c + j, or the
-// output order) access patterns spread over the banks.
-template <int SHIFT> __device__ __forceinline__ int padded(int g) { return g + (g >> SHIFT); }
 
 // ------------------------------------------------------------------------ carry chain
 
@@ -368,17 +420,13 @@ template <int DT> struct Geo {
     static constexpr int kG = T::kG;                       // elements per input granule
     static constexpr int kS = 4 * kG;                      // column length
     static constexpr int kTileElems = 64 * kG;             // one MFMA tile = 1 KiB of input
-    static constexpr int kOutGran = kTileElems / 4;        // output granules per MFMA tile
-    static constexpr int kOutShift = (kS == 64) ? 4 : 3;
-    static constexpr int kStage = kOutGran + (kOutGran >> kOutShift) + 1;   // granules of LDS per wavefront
 };
 
 struct Run {
-    const char *in_row;      // first input byte of the row
-    char *out_row;           // first output byte of the row
-    uint64_t base;           // first element of this wavefront's run inside the row
-    uint64_t cols;           // row length
-    bool in_vec, out_vec;    // row starts are 16-byte aligned
+    const char *in;          // first input byte of this wavefront's run
+    char *out;               // first output byte of the run
+    uint32_t rem;            // elements of the row from the start of the run on (saturated; 0 when the run starts past the end)
+    bool in_vec, out_vec;    // run starts are 16-byte aligned
 };
 
 // a1: coalesced 128-bit loads, zero-filled past the end of the row (BatchMatMul's zero-pad)
@@ -389,17 +437,17 @@ __device__ __forceinline__ void load_run(const Run &R, int lane, u32x4 (&g)[NT])
     constexpr int kG = Geo<DT>::kG;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        const uint64_t e0 = R.base + (uint64_t)t * Geo<DT>::kTileElems + (uint64_t)lane * kG;
-        if (R.in_vec && e0 + kG <= R.cols) {
-            g[t] = *(const u32x4 *)(R.in_row + e0 * T::kEsz);
+        const uint32_t e0 = (uint32_t)t * Geo<DT>::kTileElems + (uint32_t)lane * kG;      // element offset inside the run
+        if (R.in_vec && e0 + kG <= R.rem) {
+            g[t] = *(const u32x4 *)(R.in + e0 * T::kEsz);
         } else {
             uint32_t w[4] = {0u, 0u, 0u, 0u};
             for (int i = 0; i < kG; ++i) {
-                if (e0 + i < R.cols) {
+                if (e0 + i < R.rem) {
                     uint32_t v;
-                    if (T::kEsz == 4)      v = ((const uint32_t *)R.in_row)[e0 + i];
-                    else if (T::kEsz == 2) v = ((const uint16_t *)R.in_row)[e0 + i];
-                    else                   v = ((const uint8_t *)R.in_row)[e0 + i];
+                    if (T::kEsz == 4)      v = ((const uint32_t *)R.in)[e0 + i];
+                    else if (T::kEsz == 2) v = ((const uint16_t *)R.in)[e0 + i];
+                    else                   v = ((const uint8_t *)R.in)[e0 + i];
                     w[(i * T::kEsz) >> 2] |= v << (8 * ((i * T::kEsz) & 3));
                 }
             }
@@ -408,94 +456,109 @@ __device__ __forceinline__ void load_run(const Run &R, int lane, u32x4 (&g)[NT])
     }
 }
 
-// Load order -> operand order through this wavefront's LDS slot (lane (j, c) receives granule 4c + j),
-// and, if REDUCE, the total of the run: J * T accumulated over the tiles (plain adds for 32-bit inputs).
-// One slot is reused tile after tile: a wavefront's LDS instructions execute in order, so "write tile
-// t+1" can never overtake "read tile t", and no workgroup barrier is involved.
-template <int DT, int NT, bool REDUCE>
-__device__ __forceinline__ typename Tr<DT>::acc to_operands(u32x4 *slot, int lane, const typename Tr<DT>::AConst &Aop,
-                                                            const u32x4 (&g)[NT], u32x4 (&b)[NT])
+// Total of the run, taken from the granules as loaded: J * T accumulated over the tiles (every row of the
+// product with the all-ones matrix is the row of column totals, and the grand total does not depend on
+// which column a granule sits in), plain adds for 32-bit inputs.  No LDS traffic: the total is ready to be
+// published as soon as the loads have landed.
+template <int DT, int NT>
+__device__ __forceinline__ typename Tr<DT>::acc reduce_run(int lane, const typename Tr<DT>::AConst &Aop, const u32x4 (&g)[NT])
 {
     using T = Tr<DT>;
-    const int c = lane & 15, j = lane >> 4;
     typename T::red rsum = T::red_init();
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        slot[padded<3>(lane)] = g[t];
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        b[t] = slot[padded<3>(4 * c + j)];
-        if (REDUCE) rsum = T::red_add(Aop, rsum, b[t]);
-    }
-    if (!REDUCE) return acc_from_bits<typename T::acc>(0u);
+    for (int t = 0; t < NT; ++t) rsum = T::red_add(Aop, rsum, g[t]);
     return wave_sum(T::red_lane(rsum, lane));
 }
 
+// Exclusive scan inside each 16-lane row (lane (q, c) receives v(q, 0) + ... + v(q, c-1)).
+template <class A> __device__ __forceinline__ A row_exclusive_scan(A v)
+{
+    A e = dpp_shr<A, kRowShr + 1>(v);
+    e = acc_add(e, dpp_shr<A, kRowShr + 1>(e));
+    e = acc_add(e, dpp_shr<A, kRowShr + 2>(e));
+    e = acc_add(e, dpp_shr<A, kRowShr + 4>(e));
+    e = acc_add(e, dpp_shr<A, kRowShr + 8>(e));
+    return e;
+}
+
 // a2 + a3 + a5 + a6 for the run, tile by tile with a running carry (`carry` = everything before the run).
+// Nothing passes through LDS: lane l feeds the MFMA with the granule it loaded, and results are stored
+// straight from the MFMA's result registers, 1 KiB of consecutive outputs per store instruction.
 template <int DT, int NT, bool EXCL>
-__device__ __forceinline__ void scan_and_store(u32x4 *slot, int lane, const typename Tr<DT>::AConst &Aop, const Run &R,
-                                               const u32x4 (&b)[NT], typename Tr<DT>::acc carry)
+__device__ __forceinline__ void scan_and_store(int lane, const typename Tr<DT>::AConst &Aop, const Run &R,
+                                               const u32x4 (&g)[NT], typename Tr<DT>::acc carry)
 {
     using T = Tr<DT>;
     using A = typename T::acc;
     using A4 = typename T::acc4;
     using Ge = Geo<DT>;
     constexpr int kBlocks = T::kBlocks;
-    const int c = lane & 15, j = lane >> 4;         // operand order: column, quarter (also output row group q)
+    const int c = lane & 15, q = lane >> 4;         // result layout: column, row group
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        // a2: local scans of the 16 columns on the MFMA unit
+        // a2: level 0, the local scans of the 64 granules on the MFMA unit
         A4 d[kBlocks];
-        T::mma(Aop, b[t], lane, EXCL, d);
-        // a3: the column totals are row S-1 = lanes 48..63, last register of the last block
-        A tot = acc_from_bits<A>((uint32_t)bits<u32x4>(d[kBlocks - 1])[3]);
-        if (EXCL) tot = acc_add(tot, T::last(b[t]));     // the strictly-lower product leaves the last element out
-        A e = dpp_shr<A, kRowShr + 1>(tot);              // shift by one column -> exclusive
-        e = acc_add(e, dpp_shr<A, kRowShr + 1>(e));
-        e = acc_add(e, dpp_shr<A, kRowShr + 2>(e));
-        e = acc_add(e, dpp_shr<A, kRowShr + 4>(e));
-        e = acc_add(e, dpp_shr<A, kRowShr + 8>(e));
-        const A tile_total = uniform_from_lane(acc_add(e, tot), 63);
-        // a5: down-sweep = one add of (carry of the run so far + carry of the column) per output
-        const A cc = acc_add(carry, lane_value(e, 48 + c));      // row 3 -> all four rows
+        T::mma(Aop, g[t], lane, EXCL, d);
+        // a3 (up-sweep rounds t = 1, 2 and their down-sweep, on the vector unit): e[p] = everything in the run
+        // before the granule whose results this lane holds in block p
+        A e[kBlocks];
+        if constexpr (T::kLinear) {
+            // the lane's own granule: its total is the last row of its block; scan the 64 totals in lane order
+            A tot = acc_from_bits<A>((uint32_t)bits<u32x4>(d[0])[3]);
+            if (EXCL) tot = acc_add(tot, acc_from_bits<A>(g[t][3]));   // the strictly-lower product leaves the last element out
+            const A inc = wave_inclusive_scan(tot);
+            e[0] = acc_add(carry, wave_shift_up(inc));
+            carry = acc_add(carry, uniform_from_lane(inc, 63));
+        } else {
+            // granule totals from the matrix unit (register p: granule (jmap(p, q), c)), scanned over c inside
+            // each 16-lane row; the totals of the four granule rows j are wave-uniform and are added in order
+            const u32x4 tt = bits<u32x4>(T::totals(Aop, g[t]));
+#pragma unroll
+            for (int p = 0; p < kBlocks; ++p) {
+                const A tot = acc_from_bits<A>(tt[p]);
+                const A ex = row_exclusive_scan(tot);
+                const A inc = acc_add(ex, tot);
+                if constexpr (T::kG == 16) {                 // block p <-> granule row p, the same in every lane row
+                    e[p] = acc_add(carry, ex);
+                    carry = acc_add(carry, uniform_from_lane(inc, 15));
+                } else {                                     // block p <-> granule rows 2p (lane rows 0, 1) and 2p + 1 (lane rows 2, 3)
+                    const A lo = uniform_from_lane(inc, 15), hi = uniform_from_lane(inc, 47);
+                    const A mid = acc_add(carry, lo);
+                    e[p] = acc_add(q >= 2 ? mid : carry, ex);
+                    carry = acc_add(mid, hi);
+                }
+            }
+        }
+        // a5: down-sweep = one add per output;  a6: store
 #pragma unroll
         for (int p = 0; p < kBlocks; ++p) {
             u32x4 v = bits<u32x4>(d[p]);
-            for (int r = 0; r < 4; ++r) v[r] = acc_bits(acc_add(cc, acc_from_bits<A>(v[r])));
-            // a6: stage in output order: rows 16p + 4q .. +3 of column c are 4 consecutive outputs
-            slot[padded<Ge::kOutShift>((Ge::kS / 4) * c + 4 * p + j)] = v;
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-        for (int k = 0; k < Ge::kOutGran / 64; ++k) {
-            const int og = 64 * k + lane;
-            const u32x4 v = slot[padded<Ge::kOutShift>(og)];
-            const uint64_t e0 = R.base + (uint64_t)t * Ge::kTileElems + 4ull * og;
-            if (R.out_vec && e0 + 4 <= R.cols) {
-                __builtin_nontemporal_store(v, (u32x4 *)(R.out_row + e0 * 4));   // written once, never read back here
+            for (int r = 0; r < 4; ++r) v[r] = acc_bits(acc_add(e[p], acc_from_bits<A>(v[r])));
+            const uint32_t e0 = (uint32_t)t * Ge::kTileElems
+                              + (uint32_t)(Ge::kG * (16 * T::Map::jmap(p, q) + c) + 4 * T::Map::sub(p, q));
+            if (R.out_vec && e0 + 4 <= R.rem) {
+                __builtin_nontemporal_store(v, (u32x4 *)(R.out + e0 * 4));   // written once, never read back here
             } else {
                 for (int r = 0; r < 4; ++r)
-                    if (e0 + r < R.cols) ((uint32_t *)R.out_row)[e0 + r] = v[r];
+                    if (e0 + r < R.rem) ((uint32_t *)R.out)[e0 + r] = v[r];
             }
         }
-        carry = acc_add(carry, tile_total);
     }
 }
 
 template <int DT>
 __device__ __forceinline__ Run make_run(const Params &P, uint64_t row, uint64_t base)
 {
+    // `base` (first element of the run inside the row) is a multiple of an MFMA tile, so run starts are
+    // 16-byte aligned exactly when the row start is.  Offsets inside a run fit 32 bits.
     Run R;
-    const uint64_t row_base = row * P.cols;
-    R.in_row = (const char *)P.in + row_base * Tr<DT>::kEsz;
-    R.out_row = (char *)P.out + row_base * 4;
-    R.base = base;
-    R.cols = P.cols;
-    R.in_vec = (((uintptr_t)R.in_row) & 15) == 0;
-    R.out_vec = (((uintptr_t)R.out_row) & 15) == 0;
+    const uint64_t first = row * P.cols + base;
+    R.in = (const char *)P.in + first * Tr<DT>::kEsz;
+    R.out = (char *)P.out + first * 4;
+    const uint64_t left = base < P.cols ? P.cols - base : 0;
+    R.rem = left < 0x40000000ull ? (uint32_t)left : 0x40000000u;
+    R.in_vec = (((uintptr_t)R.in) & 15) == 0;
+    R.out_vec = (((uintptr_t)R.out) & 15) == 0;
     return R;
 }
 
@@ -517,7 +580,6 @@ void scan_kernel(Params P)
     constexpr uint32_t kEPW = NT * Geo<DT>::kTileElems;   // elements per wavefront
     constexpr uint32_t kWgElems = kEPW * W;               // elements per workgroup tile (W wavefronts)
 
-    __shared__ u32x4 stage[W][Geo<DT>::kStage];
     __shared__ uint32_t s_wave_total[W];
     __shared__ uint32_t s_bcast;
 
@@ -537,12 +599,12 @@ void scan_kernel(Params P)
     const uint32_t tr = tile - (uint32_t)row * P.tiles_per_row;
     const Run R = make_run<DT>(P, row, (uint64_t)tr * kWgElems + (uint64_t)wave * kEPW);
 
-    u32x4 g[NT], b[NT];
+    u32x4 g[NT];
     load_run<DT, NT>(R, lane, g);
     const typename T::AConst Aop = T::make(lane, EXCL);
 
-    // ---- operand order, and the total of the run (the up-sweep of this tile in one step)
-    const A wave_total = to_operands<DT, NT, true>(stage[wave], lane, Aop, g, b);
+    // ---- the total of the run (the up-sweep of this tile in one step)
+    const A wave_total = reduce_run<DT, NT>(lane, Aop, g);
 
     // ---- level 2: wavefront totals through LDS
     if (lane == 0) s_wave_total[wave] = acc_bits(wave_total);
@@ -580,7 +642,7 @@ void scan_kernel(Params P)
     }
 
     // ---- local scans, down-sweep add and store, with everything before this wavefront's run as carry
-    scan_and_store<DT, NT, EXCL>(stage[wave], lane, Aop, R, b, acc_add(prefix, wave_off));
+    scan_and_store<DT, NT, EXCL>(lane, Aop, R, g, acc_add(prefix, wave_off));
 }
 
 // ---------------------------------------------------------------------- short-row kernel
@@ -595,17 +657,15 @@ __global__ __launch_bounds__(kThreads) void scan_rows_kernel(Params P)
 {
     using T = Tr<DT>;
     using A = typename T::acc;
-    __shared__ u32x4 stage[kWaves][Geo<DT>::kStage];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const uint64_t row = (uint64_t)blockIdx.x * kWaves + wave;
     if (row >= P.rows) return;
     const Run R = make_run<DT>(P, row, 0);
-    u32x4 g[NT], b[NT];
+    u32x4 g[NT];
     load_run<DT, NT>(R, lane, g);
     const typename T::AConst Aop = T::make(lane, EXCL);
-    to_operands<DT, NT, false>(stage[wave], lane, Aop, g, b);
-    scan_and_store<DT, NT, EXCL>(stage[wave], lane, Aop, R, b, acc_from_bits<A>(0u));
+    scan_and_store<DT, NT, EXCL>(lane, Aop, R, g, acc_from_bits<A>(0u));
 }
 
 __global__ void fill_zero_kernel(uint32_t *p, size_t words)
@@ -626,14 +686,14 @@ size_t in_size(int dt) { return dt == TCUSCAN_I8_I32 ? 1 : (dt == TCUSCAN_F16_F3
 // MFMA tiles per wavefront and wavefronts per workgroup for the three tile sizes of each dtype.  Small is
 // 8192 elements per workgroup for every dtype; large and huge keep 32 .. 128 input registers per lane
 // waiting for the carry (the longer the carry chain, the more a big tile pays: fewer status words to
-// publish and poll per byte).  For 32-bit inputs "huge" is the large tile in its 8-wavefront form (half
-// the run per wavefront), which measures 5 % faster on long chains and 5 % slower on short ones.
+// publish and poll per byte).  For 32-bit inputs the one big tile is 8 wavefronts of 8 MFMA tiles: the same
+// 16384 elements as 4 wavefronts of 16, at half the registers per wavefront.
 template <int DT> struct Tiles;   // MFMA tiles per wavefront (k..) and wavefronts per workgroup (w..) for each tile size
 template <> struct Tiles<TCUSCAN_I8_I32>   { static constexpr int kSmall = 2, kLarge = 8,  kHuge = 16, wSmall = 4, wLarge = 4, wHuge = 4; };
 template <> struct Tiles<TCUSCAN_F16_F32>  { static constexpr int kSmall = 4, kLarge = 16, kHuge = 32, wSmall = 4, wLarge = 4, wHuge = 4; };
 template <> struct Tiles<TCUSCAN_BF16_F32> { static constexpr int kSmall = 4, kLarge = 16, kHuge = 32, wSmall = 4, wLarge = 4, wHuge = 4; };
-template <> struct Tiles<TCUSCAN_F32_F32>  { static constexpr int kSmall = 8, kLarge = 16, kHuge = 8,  wSmall = 4, wLarge = 4, wHuge = 8; };
-template <> struct Tiles<TCUSCAN_I32_I32>  { static constexpr int kSmall = 8, kLarge = 16, kHuge = 8,  wSmall = 4, wLarge = 4, wHuge = 8; };
+template <> struct Tiles<TCUSCAN_F32_F32>  { static constexpr int kSmall = 8, kLarge = 8,  kHuge = 8,  wSmall = 4, wLarge = 8, wHuge = 8; };
+template <> struct Tiles<TCUSCAN_I32_I32>  { static constexpr int kSmall = 8, kLarge = 8,  kHuge = 8,  wSmall = 4, wLarge = 8, wHuge = 8; };
 
 enum TileSize { kTileSmall = 0, kTileLarge = 1, kTileHuge = 2 };
 
@@ -672,7 +732,7 @@ int choose_tile(int dt, size_t rows, size_t cols)
     // on small tiles (loads and stores alternate at a finer grain), long ones on big tiles (fewer status
     // words per byte); the crossover depends on the input width.  Big tiles need enough tiles to fill the chip.
     const size_t esz = in_size(dt);
-    const size_t to_large = esz == 2 ? ((size_t)1 << 18) + 1 : esz == 1 ? 32768 : 16384;
+    const size_t to_large = esz == 2 ? ((size_t)1 << 18) + 1 : esz == 1 ? 32768 : 65537;
     const size_t to_huge  = ((size_t)1 << 22) + 1;
     int want = cols >= to_huge ? kTileHuge : cols >= to_large ? kTileLarge : kTileSmall;
     if (want == kTileHuge) {
