@@ -115,10 +115,10 @@ size_t tcuscan_huge_tile_elems(tcuscan_dtype_t dt);
 
 /*
  * Tile-size policy, process-wide: 0 = choose by shape (default: small tiles for short rows, large
- * ones from 2^14 .. 2^18 elements per row on depending on the input width, huge ones beyond 2^22, and
- * only when the call then still has 512 / 256 tiles to fill the chip), 1 = always the small tile,
- * 2 / 3 = the large / huge tile for every row longer than a small tile.  A measurement and test knob; results do not depend
- * on it beyond floating-point summation order.
+ * ones from 2^13 .. 2^18 elements per row on depending on the input width, huge ones beyond
+ * 2^22 .. 2^23, and only when the call then still has 512 / 256 tiles to fill the chip), 1 = always the
+ * small tile, 2 / 3 = the large / huge tile for every row longer than a small tile.  A measurement and
+ * test knob; results do not depend on it beyond floating-point summation order.
  */
 tcuscan_status_t tcuscan_set_tile_policy(int policy);
 

@@ -732,8 +732,8 @@ int choose_tile(int dt, size_t rows, size_t cols)
     // on small tiles (loads and stores alternate at a finer grain), long ones on big tiles (fewer status
     // words per byte); the crossover depends on the input width.  Big tiles need enough tiles to fill the chip.
     const size_t esz = in_size(dt);
-    const size_t to_large = esz == 2 ? ((size_t)1 << 18) + 1 : esz == 1 ? 32768 : 65537;
-    const size_t to_huge  = ((size_t)1 << 22) + 1;
+    const size_t to_large = esz == 2 ? ((size_t)1 << 18) + 1 : esz == 1 ? kSmallTile + 1 : ((size_t)1 << 17) + 1;
+    const size_t to_huge  = esz == 2 ? ((size_t)1 << 23) + 1 : ((size_t)1 << 22) + 1;
     int want = cols >= to_huge ? kTileHuge : cols >= to_large ? kTileLarge : kTileSmall;
     if (want == kTileHuge) {
         const size_t ht = tile_elems(dt, kTileHuge);
