@@ -122,6 +122,24 @@ def measure_levels(steps: int):
         res[name] = {"ms": ms, "gelems_per_s": n / (ms * 1e-3) / 1e9}
     res["workload"] = "inclusive scan, n=2^28=16^7, int8 {0,1} -> int32; 'levels' = 13 launches of Algorithm 1's rounds"
     res["fused_speedup"] = res["levels"]["ms"] / res["fused"]["ms"]
+    # The fan-in against depth trade-off (Lemma 1: 2 log_s n - 1 rounds): the same executor with s = 4, 16, 32 on the
+    # one length all three divide (2^20 = 4^10 = 16^5 = 32^4, where the launches dominate) and on their largest
+    # power below 2^28 + 1 (where the strided gathers dominate).
+    radices = []
+    for s, k in ((4, 10), (16, 5), (32, 4), (4, 14), (16, 7), (32, 5)):
+        m = s ** k
+        for _ in range(2):
+            tcuscan.matmulscan_levels(d_in, d_out, "i8", n=m, s=s)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            tcuscan.matmulscan_levels(d_in, d_out, "i8", n=m, s=s)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        radices.append({"s": s, "n": m, "rounds": 2 * k - 1, "ms": ms, "gelems_per_s": m / (ms * 1e-3) / 1e9})
+    res["radices"] = radices
     return res
 
 

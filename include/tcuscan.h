@@ -148,6 +148,16 @@ tcuscan_status_t tcuscan_matmulscan_levels(const void *d_in, void *d_out, size_t
                                            int rounds, unsigned long long *d_matmuls, tcuscan_stream_t stream);
 
 /*
+ * The same executor for the other radices the matrix unit has a native shape for: s = 4 (sixteen 4 x 4
+ * blocks per MFMA instruction), s = 16 (as above) and s = 32 (32 x 32 MFMA); n = s^k.  Algorithm 1 is
+ * stated for any s >= 2; Lemma 1 gives its depth 2 log_s n - 1 and its product count, and the paper's
+ * comparison table (Section 3) is the fan-in against depth trade-off this call lets one measure.
+ * Other s return TCUSCAN_ERR_UNSUPPORTED.  Arguments as tcuscan_matmulscan_levels.
+ */
+tcuscan_status_t tcuscan_matmulscan_levels_radix(const void *d_in, void *d_out, size_t n, tcuscan_dtype_t dt, int s,
+                                                 int rounds, unsigned long long *d_matmuls, tcuscan_stream_t stream);
+
+/*
  * Applications the paper's introduction gives as its motivation, built on the exclusive scan of a 0/1
  * int8 mask (the I8_I32 MFMA path).  The caller provides every scratch buffer; workspace as for
  * tcuscan_exclusive(.., n, TCUSCAN_I8_I32, ..).  n < 2^32.  Asynchronous on `stream`.

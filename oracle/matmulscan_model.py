@@ -116,6 +116,21 @@ def matmul_scan(x: np.ndarray, s: int, trace: Trace | None = None) -> np.ndarray
     return x
 
 
+def gathered_lengths(n: int, s: int):
+    """Lengths of the subvectors Algorithm 1 gathers, round by round, for n = s^k: the up-sweep round t
+    takes x[s^t - 1 :: s^t], the down-sweep round t takes x[s^t - 1 :: s^(t-1)]."""
+    k = _exact_log(n, s)
+    ups = [(n - s ** t) // s ** t + 1 for t in range(k)]
+    downs = [(n - s ** t) // s ** (t - 1) + 1 for t in range(k - 1, 0, -1)]
+    return ups + downs
+
+
+def product_count(n: int, s: int) -> int:
+    """Number of s x s products Algorithm 1 issues for n = s^k: BatchMatMul pads every gathered vector
+    to a multiple of s^2 and multiplies chunk by chunk (the quantity Lemma 1 bounds)."""
+    return sum(-(-m // (s * s)) for m in gathered_lengths(n, s))
+
+
 def _recurse(z: np.ndarray, s: int, Ls, Bs, trace) -> np.ndarray:
     """Algorithm 2, Recurse.  Precondition: every aligned run of s entries of z already holds
     its local prefix sums.  Postcondition: z holds the prefix sums of the whole vector."""

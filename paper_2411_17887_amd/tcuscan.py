@@ -19,7 +19,7 @@ DTYPES = {"i32": I32_I32, "f16": F16_F32, "i8": I8_I32, "f32": F32_F32, "bf16": 
 EXPORTS = ["tcuscan_workspace_bytes", "tcuscan_workspace_init", "tcuscan_inclusive", "tcuscan_exclusive",
            "tcuscan_batched", "tcuscan_tile_elems", "tcuscan_large_tile_elems", "tcuscan_huge_tile_elems",
            "tcuscan_set_tile_policy",
-           "tcuscan_workspace_fault", "tcuscan_matmulscan_levels", "tcuscan_compact_u32",
+           "tcuscan_workspace_fault", "tcuscan_matmulscan_levels", "tcuscan_matmulscan_levels_radix", "tcuscan_compact_u32",
            "tcuscan_split_radix_sort_u32", "tcuscan_status_string"]
 
 _lib = None
@@ -59,13 +59,14 @@ def load() -> ctypes.CDLL:
         L.tcuscan_batched.argtypes = [vp, vp, sz, sz, ci, ci, vp, sz, vp]
         L.tcuscan_workspace_fault.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_uint)]
         L.tcuscan_matmulscan_levels.argtypes = [vp, vp, sz, ci, ci, vp, vp]
+        L.tcuscan_matmulscan_levels_radix.argtypes = [vp, vp, sz, ci, ci, ci, vp, vp]
         L.tcuscan_compact_u32.argtypes = [vp, vp, vp, sz, vp, vp, vp, sz, vp]
         L.tcuscan_split_radix_sort_u32.argtypes = [vp, vp, sz, ci, vp, vp, vp, vp, vp, sz, vp]
         L.tcuscan_status_string.argtypes = [ci]
         L.tcuscan_status_string.restype = ctypes.c_char_p
         for f in ("tcuscan_workspace_init", "tcuscan_inclusive", "tcuscan_exclusive", "tcuscan_batched",
-                  "tcuscan_workspace_fault", "tcuscan_matmulscan_levels", "tcuscan_compact_u32",
-                  "tcuscan_split_radix_sort_u32"):
+                  "tcuscan_workspace_fault", "tcuscan_matmulscan_levels", "tcuscan_matmulscan_levels_radix",
+                  "tcuscan_compact_u32", "tcuscan_split_radix_sort_u32"):
             getattr(L, f).restype = ci
         _lib = L
     return _lib
@@ -154,10 +155,15 @@ def batched(x, out, rows: int, cols: int, dt, exclusive_scan: bool = False, ws=N
         raise TcuscanError(rc, "tcuscan_batched")
 
 
-def matmulscan_levels(x, out, dt, rounds: int = -1, matmuls=None, stream=None, n=None) -> None:
-    """Algorithm 1 round by round (s = 16, n = 16^k).  `matmuls`: optional int64 device tensor of one element."""
-    rc = load().tcuscan_matmulscan_levels(_ptr(x), _ptr(out), x.numel() if n is None else n, _dt(dt), int(rounds),
-                                          _ptr(matmuls), _stream(stream))
+def matmulscan_levels(x, out, dt, rounds: int = -1, matmuls=None, stream=None, n=None, s: int = 16) -> None:
+    """Algorithm 1 round by round (n = s^k; s = 16 by default, 4 and 32 as well).  `matmuls`: optional int64
+    device tensor of one element."""
+    n = x.numel() if n is None else n
+    if s == 16:
+        rc = load().tcuscan_matmulscan_levels(_ptr(x), _ptr(out), n, _dt(dt), int(rounds), _ptr(matmuls), _stream(stream))
+    else:
+        rc = load().tcuscan_matmulscan_levels_radix(_ptr(x), _ptr(out), n, _dt(dt), int(s), int(rounds), _ptr(matmuls),
+                                                    _stream(stream))
     if rc != OK:
         raise TcuscanError(rc, "tcuscan_matmulscan_levels")
 

@@ -7,7 +7,8 @@ import os
 
 rows = ["# Paper, Lemma 1: depth = 2k - 1, products <= ceil(2n / (s(s-1))) + 2k - 2  for n = s^k.",
         "# columns: s k n depth bound"]
-for s, k in [(2, 4), (4, 2), (4, 5), (16, 1), (16, 2), (16, 3), (16, 4), (16, 6), (16, 7)]:
+for s, k in [(2, 4), (4, 1), (4, 2), (4, 3), (4, 5), (4, 6), (4, 14), (16, 1), (16, 2), (16, 3), (16, 4), (16, 6), (16, 7),
+             (32, 1), (32, 2), (32, 3), (32, 5)]:
     n = s ** k
     bound = -(-2 * n // (s * (s - 1))) + 2 * k - 2
     rows.append(f"{s} {k} {n} {2 * k - 1} {bound}")

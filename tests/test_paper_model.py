@@ -116,7 +116,7 @@ def closed_form_matmuls(n, s, k):
 def test_product_counts_at_benchmark_sizes():
     """Counts at sizes too large to replay are taken from the gathered-vector lengths; the formula is first
     validated against the replay at sizes that can be run, then compared with the lemma's bound."""
-    for s, k in [(2, 4), (4, 5), (16, 2), (16, 3), (16, 4)]:
+    for s, k in [(2, 4), (4, 5), (4, 6), (16, 2), (16, 3), (16, 4), (32, 2), (32, 3)]:
         n = s ** k
         tr = mm.Trace()
         mm.matmul_scan(np.ones(n, dtype=np.int64), s, tr)
@@ -125,7 +125,11 @@ def test_product_counts_at_benchmark_sizes():
         lens = [(n - s ** t) // s ** t + 1 for t in range(k)] + [(n - s ** t) // s ** (t - 1) + 1 for t in range(k - 1, 0, -1)]
         assert tr.gathered_len_per_round == lens and len(ks) == tr.depth
     for s, k, n, depth, bound in lemma_rows():
-        assert closed_form_matmuls(n, s, k) <= bound
+        assert closed_form_matmuls(n, s, k) == mm.product_count(n, s) <= bound
+        assert len(mm.gathered_lengths(n, s)) == depth
+    # the counts the GPU tests expect at full size
+    assert mm.product_count(16 ** 7, 16) == 2236963 and mm.product_count(4 ** 14, 4) == 44739243
+    assert mm.product_count(32 ** 5, 32) == 67651
 
 
 @pytest.mark.parametrize("s,k", [(2, 5), (3, 4), (4, 3), (16, 2), (16, 3)])
