@@ -105,6 +105,21 @@ tcuscan_status_t tcuscan_batched(const void *d_in, void *d_out, size_t rows, siz
                                  tcuscan_dtype_t dt, int exclusive,
                                  void *d_ws, size_t ws_bytes, tcuscan_stream_t stream);
 
+/*
+ * The general form: row-wise scans with option flags.
+ *   TCUSCAN_EXCLUSIVE  exclusive instead of inclusive
+ *   TCUSCAN_REVERSE    every row is scanned from its end: y[i] = x[i] + ... + x[cols-1] (inclusive) or
+ *                      x[i+1] + ... + x[cols-1] (exclusive) -- the suffix sums, i.e. the scan of the reversed
+ *                      row, reversed.  In Algorithm 1's terms the local products use the upper triangular
+ *                      all-ones matrix (the transpose of L_s) and the carries travel from the last block to
+ *                      the first.
+ * Unknown flag bits return TCUSCAN_ERR_INVALID_ARG.  Everything else as tcuscan_batched.
+ */
+#define TCUSCAN_EXCLUSIVE 1u
+#define TCUSCAN_REVERSE   2u
+tcuscan_status_t tcuscan_scan(const void *d_in, void *d_out, size_t rows, size_t cols, tcuscan_dtype_t dt, unsigned flags,
+                              void *d_ws, size_t ws_bytes, tcuscan_stream_t stream);
+
 /* Elements the small workgroup tile covers (rows no longer than this need no workspace), and the
  * large and huge tiles that long inputs use (more elements wait in registers per compute unit while
  * the carry chain's latency is paid, and fewer status words are published and polled per byte).  All

@@ -194,6 +194,42 @@ def compare_float_exact(x: np.ndarray, kind, got: np.ndarray, exclusive: bool = 
     return int(nb.value), int(fb.value)
 
 
+# ---- reverse scans (suffix sums): by definition the scan of the reversed row, reversed.  Nothing new is
+# computed here: rows are flipped on the way in and on the way out of the functions above.
+
+def _flip_rows(a: np.ndarray, rows: int, cols: int) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a).reshape(rows, cols)[:, ::-1])
+
+
+def scan_reverse(x: np.ndarray, kind, exclusive: bool = False, rows=None, cols=None, with_l1: bool = False):
+    """Suffix sums: y[i] = x[i] + ... + x[cols-1] (inclusive) or x[i+1] + ... + x[cols-1] (exclusive), per row."""
+    k = _kind(kind)
+    xx, rows, cols = _prep(x, k, rows, cols)
+    r = scan(_flip_rows(xx, rows, cols), k, exclusive, rows, cols, with_l1)
+    if with_l1:
+        return _flip_rows(r[0], rows, cols).reshape(xx.shape), _flip_rows(r[1], rows, cols).reshape(xx.shape)
+    return _flip_rows(r, rows, cols).reshape(xx.shape)
+
+
+def compare_float_reverse(x, kind, got, exclusive: bool = False, rows=None, cols=None) -> FloatReport:
+    k = _kind(kind)
+    xx, rows, cols = _prep(x, k, rows, cols)
+    return compare_float(_flip_rows(xx, rows, cols), k, _flip_rows(got, rows, cols), exclusive, rows, cols)
+
+
+def compare_int_reverse(x, kind, got, exclusive: bool = False, rows=None, cols=None):
+    """(mismatches, first mismatching index in the flipped order or -1)."""
+    k = _kind(kind)
+    xx, rows, cols = _prep(x, k, rows, cols)
+    return compare_int(_flip_rows(xx, rows, cols), k, _flip_rows(got, rows, cols), exclusive, rows, cols)
+
+
+def compare_float_exact_reverse(x, kind, got, exclusive: bool = False, rows=None, cols=None):
+    k = _kind(kind)
+    xx, rows, cols = _prep(x, k, rows, cols)
+    return compare_float_exact(_flip_rows(xx, rows, cols), k, _flip_rows(got, rows, cols), exclusive, rows, cols)
+
+
 def half_to_double(bits: int) -> float:
     return float(lib().oracle_half_to_double(int(bits)))
 

@@ -71,6 +71,7 @@ struct Params {
     uint64_t    rows, cols;
     uint32_t    tiles_per_row, num_tiles;
     uint32_t    tag;         // this call's tag for the status words
+    uint32_t    reverse;     // non-zero: suffix sums (every row is scanned from its end)
     WsHeader   *ws;          // null when tiles_per_row == 1
 };
 
@@ -152,6 +153,27 @@ __device__ __forceinline__ uint64_t low_slots(uint64_t ones, int cnt, int slots,
     cnt = cnt < 0 ? 0 : (cnt > slots ? slots : cnt);
     return cnt == 0 ? 0ull : ones >> (bits_per_slot * (slots - cnt));
 }
+// the same with the `cnt` highest slots (rows of the upper triangular blocks of a reverse scan)
+__device__ __forceinline__ uint64_t high_slots(uint64_t ones, int cnt, int slots, int bits_per_slot)
+{
+    cnt = cnt < 0 ? 0 : (cnt > slots ? slots : cnt);
+    return cnt == 0 ? 0ull : (ones << (bits_per_slot * (slots - cnt))) & (slots * bits_per_slot == 64 ? ~0ull : ((1ull << (slots * bits_per_slot)) - 1));
+}
+// Row i of a G x G triangular block as two words of G/2 slots each: slots 0 .. i (forward) or i .. G-1 (reverse);
+// the strict forms leave slot i out.
+__device__ __forceinline__ void tri_row(uint64_t ones, int i, int G, int bits_per_slot, bool excl, bool rev, bool present,
+                                        uint64_t &lo, uint64_t &hi)
+{
+    const int half = G / 2;
+    if (!present) { lo = hi = 0; return; }
+    if (!rev) {
+        const int cnt = i + (excl ? 0 : 1);
+        lo = low_slots(ones, cnt, half, bits_per_slot); hi = low_slots(ones, cnt - half, half, bits_per_slot);
+    } else {
+        const int cnt = G - i - (excl ? 1 : 0);
+        hi = high_slots(ones, cnt, half, bits_per_slot); lo = high_slots(ones, cnt - half, half, bits_per_slot);
+    }
+}
 
 // Shared by the two 16-bit types: which granule row / which half a result row of block p stands for.
 struct Map16 {
@@ -161,15 +183,15 @@ struct Map16 {
 
 // Operands of a 16-bit type as raw words; `one` is the 16-bit pattern of 1.0 repeated four times.
 struct AWords16 { u32x4 a[2]; u32x4 ones; u32x4 tot; };
-__device__ __forceinline__ AWords16 make16(int lane, bool excl, uint64_t one)
+__device__ __forceinline__ AWords16 make16(int lane, bool excl, bool rev, uint64_t one)
 {
     AWords16 A; const int m = lane & 15, jj = lane >> 4;       // this lane supplies row m, K slots (jj, 0..7)
     const uint32_t o = (uint32_t)one;
     A.ones = u32x4{o, o, o, o};
     for (int p = 0; p < 2; ++p) {
         const int j = Map16::jmap(p, m >> 2), i = 4 * Map16::sub(p, m >> 2) + (m & 3);
-        const int cnt = jj == j ? i + (excl ? 0 : 1) : 0;
-        const uint64_t lo = low_slots(one, cnt, 4, 16), hi = low_slots(one, cnt - 4, 4, 16);
+        uint64_t lo, hi;
+        tri_row(one, i, 8, 16, excl, rev, jj == j, lo, hi);
         A.a[p] = u32x4{(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)};
     }
     const int r = m & 3;
@@ -195,13 +217,13 @@ template <> struct Tr<TCUSCAN_F16_F32> {
     {
         return __builtin_amdgcn_mfma_f32_16x16x32_f16(A.tot, bits<f16x8>(b), red_init(), 0, 0, 0);
     }
-    static __device__ AConst make(int lane, bool excl)
+    static __device__ AConst make(int lane, bool excl, bool rev)
     {
-        const AWords16 w = make16(lane, excl, 0x3C003C003C003C00ull);       // 1.0h
+        const AWords16 w = make16(lane, excl, rev, 0x3C003C003C003C00ull);       // 1.0h
         AConst A; A.a[0] = bits<f16x8>(w.a[0]); A.a[1] = bits<f16x8>(w.a[1]); A.ones = bits<f16x8>(w.ones); A.tot = bits<f16x8>(w.tot);
         return A;
     }
-    static __device__ __forceinline__ void mma(const AConst &A, u32x4 b, int, bool, acc4 (&d)[kBlocks])
+    static __device__ __forceinline__ void mma(const AConst &A, u32x4 b, int, bool, bool, acc4 (&d)[kBlocks])
     {
         const f32x4 z = {0.f, 0.f, 0.f, 0.f};
         f16x8 bv = bits<f16x8>(b);
@@ -226,13 +248,13 @@ template <> struct Tr<TCUSCAN_BF16_F32> {
     {
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(A.tot, bits<bf16x8>(b), red_init(), 0, 0, 0);
     }
-    static __device__ AConst make(int lane, bool excl)
+    static __device__ AConst make(int lane, bool excl, bool rev)
     {
-        const AWords16 w = make16(lane, excl, 0x3F803F803F803F80ull);       // bf16 1.0
+        const AWords16 w = make16(lane, excl, rev, 0x3F803F803F803F80ull);       // bf16 1.0
         AConst A; A.a[0] = bits<bf16x8>(w.a[0]); A.a[1] = bits<bf16x8>(w.a[1]); A.ones = bits<bf16x8>(w.ones); A.tot = bits<bf16x8>(w.tot);
         return A;
     }
-    static __device__ __forceinline__ void mma(const AConst &A, u32x4 b, int, bool, acc4 (&d)[kBlocks])
+    static __device__ __forceinline__ void mma(const AConst &A, u32x4 b, int, bool, bool, acc4 (&d)[kBlocks])
     {
         const f32x4 z = {0.f, 0.f, 0.f, 0.f};
         bf16x8 bv = bits<bf16x8>(b);
@@ -260,20 +282,20 @@ template <> struct Tr<TCUSCAN_I8_I32> {
     {
         return __builtin_amdgcn_mfma_i32_16x16x64_i8(A.tot, bits<i32x4>(b), red_init(), 0, 0, 0);
     }
-    static __device__ AConst make(int lane, bool excl)
+    static __device__ AConst make(int lane, bool excl, bool rev)
     {
         AConst A; const int m = lane & 15, jj = lane >> 4;     // this lane supplies row m, K slots (jj, 0..15)
         A.ones = i32x4{0x01010101, 0x01010101, 0x01010101, 0x01010101};
         for (int p = 0; p < kBlocks; ++p) {
-            const int cnt = jj == p ? m + (excl ? 0 : 1) : 0;  // row m of block p is element m of granule row p
-            const uint64_t lo = low_slots(0x0101010101010101ull, cnt, 8, 8), hi = low_slots(0x0101010101010101ull, cnt - 8, 8, 8);
+            uint64_t lo, hi;                                   // row m of block p is element m of granule row p
+            tri_row(0x0101010101010101ull, m, 16, 8, excl, rev, jj == p, lo, hi);
             A.a[p] = i32x4{(int)(uint32_t)lo, (int)(uint32_t)(lo >> 32), (int)(uint32_t)hi, (int)(uint32_t)(hi >> 32)};
         }
         const int t = jj == (m & 3) ? 0x01010101 : 0;          // row 4q + r: total of granule row r
         A.tot = i32x4{t, t, t, t};
         return A;
     }
-    static __device__ __forceinline__ void mma(const AConst &A, u32x4 b, int, bool, acc4 (&d)[kBlocks])
+    static __device__ __forceinline__ void mma(const AConst &A, u32x4 b, int, bool, bool, acc4 (&d)[kBlocks])
     {
         const i32x4 z = {0, 0, 0, 0};
         i32x4 bv = bits<i32x4>(b);
@@ -300,13 +322,16 @@ template <> struct Tr<TCUSCAN_F32_F32> {
         return r + ((bits<float>(b[0]) + bits<float>(b[1])) + (bits<float>(b[2]) + bits<float>(b[3])));
     }
     static __device__ __forceinline__ acc red_lane(red r, int) { return r; }
-    static __device__ AConst make(int lane, bool excl)
+    static __device__ AConst make(int lane, bool excl, bool rev)
     {
         AConst A; int m = lane & 15, j = lane >> 4;
-        for (int p = 0; p < 4; ++p) A.a[p] = (j == (m >> 2) && (excl ? p < (m & 3) : p <= (m & 3))) ? 1.0f : 0.0f;
+        for (int p = 0; p < 4; ++p) {
+            const bool in = rev ? (excl ? p > (m & 3) : p >= (m & 3)) : (excl ? p < (m & 3) : p <= (m & 3));
+            A.a[p] = (j == (m >> 2) && in) ? 1.0f : 0.0f;
+        }
         return A;
     }
-    static __device__ __forceinline__ void mma(const AConst &A, u32x4 b, int, bool, acc4 (&d)[kBlocks])
+    static __device__ __forceinline__ void mma(const AConst &A, u32x4 b, int, bool, bool, acc4 (&d)[kBlocks])
     {
         f32x4 r = {0.f, 0.f, 0.f, 0.f};
         for (int p = 0; p < 4; ++p) r = __builtin_amdgcn_mfma_f32_16x16x4f32(A.a[p], bits<float>(b[p]), r, 0, 0, 0);
@@ -327,14 +352,16 @@ template <> struct Tr<TCUSCAN_I32_I32> {
     static __device__ __forceinline__ red red_init() { return 0u; }
     static __device__ __forceinline__ red red_add(const AConst &, red r, u32x4 b) { return r + b[0] + b[1] + b[2] + b[3]; }
     static __device__ __forceinline__ acc red_lane(red r, int) { return r; }
-    static __device__ AConst make(int lane, bool excl)
+    static __device__ AConst make(int lane, bool excl, bool rev)
     {
         int m = lane & 15, j = lane >> 4;
-        const uint64_t lo = j == (m >> 2) ? low_slots(0x01010101ull, (m & 3) + (excl ? 0 : 1), 4, 8) : 0ull;
+        uint64_t lo = 0;
+        if (j == (m >> 2))
+            lo = rev ? high_slots(0x01010101ull, 4 - (m & 3) - (excl ? 1 : 0), 4, 8) : low_slots(0x01010101ull, (m & 3) + (excl ? 0 : 1), 4, 8);
         AConst A; A.a = (long)lo;                 // K slots 4..7 of every lane are unused (zero on both sides)
         return A;
     }
-    static __device__ __forceinline__ void mma(const AConst &A, u32x4 b, int lane, bool excl, acc4 (&d)[kBlocks])
+    static __device__ __forceinline__ void mma(const AConst &A, u32x4 b, int lane, bool excl, bool rev, acc4 (&d)[kBlocks])
     {
         const i32x4 z = {0, 0, 0, 0};
         uint32_t x0 = b[0] ^ 0x80808080u, x1 = b[1] ^ 0x80808080u, x2 = b[2] ^ 0x80808080u, x3 = b[3] ^ 0x80808080u;
@@ -345,7 +372,7 @@ template <> struct Tr<TCUSCAN_I32_I32> {
             pl[p] = __builtin_amdgcn_mfma_i32_16x16x32_i8(A.a, (long)(uint64_t)(lo | hi), z, 0, 0, 0);
         }
         for (int r = 0; r < 4; ++r) {
-            uint32_t cnt = (uint32_t)r + (excl ? 0u : 1u);                    // elements summed into row 4q + r
+            uint32_t cnt = (uint32_t)(rev ? 3 - r : r) + (excl ? 0u : 1u);    // elements summed into row 4q + r
             uint32_t v = (uint32_t)pl[0][r] + ((uint32_t)pl[1][r] << 8) + ((uint32_t)pl[2][r] << 16) + ((uint32_t)pl[3][r] << 24);
             d[0][r] = (int)(v + cnt * 0x80808080u);                           // 128 * cnt on every byte plane
         }
@@ -429,15 +456,27 @@ struct Run {
     bool in_vec, out_vec;    // run starts are 16-byte aligned
 };
 
+// Element offset, inside the run, of granule slot `l` (0 .. 63) of MFMA tile `t` in processing order.  A reverse
+// scan mirrors the granules -- tile 0, slot 0 is the last granule of the run -- and leaves the elements inside a
+// granule where they are (the triangular blocks are upper triangular instead); a load or store instruction still
+// covers 1 KiB of consecutive memory, and everything that scans "the slots before this one" then scans the
+// elements after it.  (Written as tile part + lane part so that the tile part folds into the instruction's
+// immediate offset.)
+template <int DT, int NT, bool REV> __device__ __forceinline__ uint32_t slot_offset(int t, int l)
+{
+    constexpr int kG = Tr<DT>::kG;
+    return REV ? (uint32_t)(NT - 1 - t) * (64 * kG) + (uint32_t)((63 - l) * kG) : (uint32_t)t * (64 * kG) + (uint32_t)(l * kG);
+}
+
 // a1: coalesced 128-bit loads, zero-filled past the end of the row (BatchMatMul's zero-pad)
-template <int DT, int NT>
+template <int DT, int NT, bool REV>
 __device__ __forceinline__ void load_run(const Run &R, int lane, u32x4 (&g)[NT])
 {
     using T = Tr<DT>;
     constexpr int kG = Geo<DT>::kG;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        const uint32_t e0 = (uint32_t)t * Geo<DT>::kTileElems + (uint32_t)lane * kG;      // element offset inside the run
+        const uint32_t e0 = slot_offset<DT, NT, REV>(t, lane);                            // element offset inside the run
         if (R.in_vec && e0 + kG <= R.rem) {
             g[t] = *(const u32x4 *)(R.in + e0 * T::kEsz);
         } else {
@@ -484,7 +523,7 @@ template <class A> __device__ __forceinline__ A row_exclusive_scan(A v)
 // a2 + a3 + a5 + a6 for the run, tile by tile with a running carry (`carry` = everything before the run).
 // Nothing passes through LDS: lane l feeds the MFMA with the granule it loaded, and results are stored
 // straight from the MFMA's result registers, 1 KiB of consecutive outputs per store instruction.
-template <int DT, int NT, bool EXCL>
+template <int DT, int NT, bool EXCL, bool REV>
 __device__ __forceinline__ void scan_and_store(int lane, const typename Tr<DT>::AConst &Aop, const Run &R,
                                                const u32x4 (&g)[NT], typename Tr<DT>::acc carry)
 {
@@ -498,14 +537,15 @@ __device__ __forceinline__ void scan_and_store(int lane, const typename Tr<DT>::
     for (int t = 0; t < NT; ++t) {
         // a2: level 0, the local scans of the 64 granules on the MFMA unit
         A4 d[kBlocks];
-        T::mma(Aop, g[t], lane, EXCL, d);
+        T::mma(Aop, g[t], lane, EXCL, REV, d);
         // a3 (up-sweep rounds t = 1, 2 and their down-sweep, on the vector unit): e[p] = everything in the run
         // before the granule whose results this lane holds in block p
         A e[kBlocks];
         if constexpr (T::kLinear) {
             // the lane's own granule: its total is the last row of its block; scan the 64 totals in lane order
-            A tot = acc_from_bits<A>((uint32_t)bits<u32x4>(d[0])[3]);
-            if (EXCL) tot = acc_add(tot, acc_from_bits<A>(g[t][3]));   // the strictly-lower product leaves the last element out
+            constexpr int edge = REV ? 0 : 3;                           // the row of the block that sums the whole granule
+            A tot = acc_from_bits<A>((uint32_t)bits<u32x4>(d[0])[edge]);
+            if (EXCL) tot = acc_add(tot, acc_from_bits<A>(g[t][edge]));  // the strict product leaves that row's own element out
             const A inc = wave_inclusive_scan(tot);
             e[0] = acc_add(carry, wave_shift_up(inc));
             carry = acc_add(carry, uniform_from_lane(inc, 63));
@@ -534,8 +574,7 @@ __device__ __forceinline__ void scan_and_store(int lane, const typename Tr<DT>::
         for (int p = 0; p < kBlocks; ++p) {
             u32x4 v = bits<u32x4>(d[p]);
             for (int r = 0; r < 4; ++r) v[r] = acc_bits(acc_add(e[p], acc_from_bits<A>(v[r])));
-            const uint32_t e0 = (uint32_t)t * Ge::kTileElems
-                              + (uint32_t)(Ge::kG * (16 * T::Map::jmap(p, q) + c) + 4 * T::Map::sub(p, q));
+            const uint32_t e0 = slot_offset<DT, NT, REV>(t, 16 * T::Map::jmap(p, q) + c) + 4u * T::Map::sub(p, q);
             if (R.out_vec && e0 + 4 <= R.rem) {
                 __builtin_nontemporal_store(v, (u32x4 *)(R.out + e0 * 4));   // written once, never read back here
             } else {
@@ -571,7 +610,7 @@ template <> struct MinWaves<TCUSCAN_I8_I32, 8>    { static constexpr int value =
 template <> struct MinWaves<TCUSCAN_F16_F32, 16>  { static constexpr int value = 4; };
 template <> struct MinWaves<TCUSCAN_BF16_F32, 16> { static constexpr int value = 4; };
 
-template <int DT, int NT, bool EXCL, int W>
+template <int DT, int NT, bool EXCL, bool REV, int W>
 __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(MinWaves<DT, NT>::value)))
 void scan_kernel(Params P)
 {
@@ -596,12 +635,13 @@ void scan_kernel(Params P)
     const uint32_t tile = blockIdx.x;
     const uint32_t tag = P.tag;
     const uint64_t row = tile / P.tiles_per_row;
-    const uint32_t tr = tile - (uint32_t)row * P.tiles_per_row;
-    const Run R = make_run<DT>(P, row, (uint64_t)tr * kWgElems + (uint64_t)wave * kEPW);
+    const uint32_t tr = tile - (uint32_t)row * P.tiles_per_row;           // position in the carry chain of the row
+    const uint32_t pos = REV ? P.tiles_per_row - 1 - tr : tr;             // position in the row: a reverse scan starts at the end
+    const Run R = make_run<DT>(P, row, (uint64_t)pos * kWgElems + (uint64_t)wave * kEPW);
 
     u32x4 g[NT];
-    load_run<DT, NT>(R, lane, g);
-    const typename T::AConst Aop = T::make(lane, EXCL);
+    load_run<DT, NT, REV>(R, lane, g);
+    const typename T::AConst Aop = T::make(lane, EXCL, REV);
 
     // ---- the total of the run (the up-sweep of this tile in one step)
     const A wave_total = reduce_run<DT, NT>(lane, Aop, g);
@@ -613,7 +653,7 @@ void scan_kernel(Params P)
 #pragma unroll
     for (int w = 0; w < W; ++w) {
         const A v = acc_from_bits<A>(s_wave_total[w]);
-        if (w < wave) wave_off = acc_add(wave_off, v);
+        if (REV ? w > wave : w < wave) wave_off = acc_add(wave_off, v);    // the wavefronts scanned before this one
         wg_total = acc_add(wg_total, v);
     }
 
@@ -642,7 +682,7 @@ void scan_kernel(Params P)
     }
 
     // ---- local scans, down-sweep add and store, with everything before this wavefront's run as carry
-    scan_and_store<DT, NT, EXCL>(lane, Aop, R, g, acc_add(prefix, wave_off));
+    scan_and_store<DT, NT, EXCL, REV>(lane, Aop, R, g, acc_add(prefix, wave_off));
 }
 
 // ---------------------------------------------------------------------- short-row kernel
@@ -652,7 +692,7 @@ void scan_kernel(Params P)
 // the histogram prefix sums in gradient-boosted-tree split finding, one of the paper's two
 // motivating applications.
 
-template <int DT, int NT, bool EXCL>
+template <int DT, int NT, bool EXCL, bool REV>
 __global__ __launch_bounds__(kThreads) void scan_rows_kernel(Params P)
 {
     using T = Tr<DT>;
@@ -663,9 +703,9 @@ __global__ __launch_bounds__(kThreads) void scan_rows_kernel(Params P)
     if (row >= P.rows) return;
     const Run R = make_run<DT>(P, row, 0);
     u32x4 g[NT];
-    load_run<DT, NT>(R, lane, g);
-    const typename T::AConst Aop = T::make(lane, EXCL);
-    scan_and_store<DT, NT, EXCL>(lane, Aop, R, g, acc_from_bits<A>(0u));
+    load_run<DT, NT, REV>(R, lane, g);
+    const typename T::AConst Aop = T::make(lane, EXCL, REV);
+    scan_and_store<DT, NT, EXCL, REV>(lane, Aop, R, g, acc_from_bits<A>(0u));
 }
 
 __global__ void fill_zero_kernel(uint32_t *p, size_t words)
@@ -749,11 +789,23 @@ int choose_tile(int dt, size_t rows, size_t cols)
 std::atomic<uint32_t> g_calls{0};
 
 // Short rows: the smallest run length (1, 2, 4 or 8 MFMA tiles per wavefront) that holds a row.
+// The four (exclusive, reverse) instantiations of one kernel shape.
+template <int DT, int NT> const void *rows_kernel_for(bool excl, bool rev)
+{
+    if (rev) return excl ? (const void *)scan_rows_kernel<DT, NT, true, true> : (const void *)scan_rows_kernel<DT, NT, false, true>;
+    return excl ? (const void *)scan_rows_kernel<DT, NT, true, false> : (const void *)scan_rows_kernel<DT, NT, false, false>;
+}
+template <int DT, int NT, int W> const void *scan_kernel_for(bool excl, bool rev)
+{
+    if (rev) return excl ? (const void *)scan_kernel<DT, NT, true, true, W> : (const void *)scan_kernel<DT, NT, false, true, W>;
+    return excl ? (const void *)scan_kernel<DT, NT, true, false, W> : (const void *)scan_kernel<DT, NT, false, false, W>;
+}
+
 template <int DT, int NT> hipError_t launch_rows_nt(Params P, bool excl, hipStream_t s)
 {
     void *args[] = {&P};
-    const void *fn = excl ? (const void *)scan_rows_kernel<DT, NT, true> : (const void *)scan_rows_kernel<DT, NT, false>;
-    return hipLaunchKernel(fn, dim3((unsigned)((P.rows + kWaves - 1) / kWaves)), dim3(kThreads), args, 0, s);
+    return hipLaunchKernel(rows_kernel_for<DT, NT>(excl, P.reverse != 0), dim3((unsigned)((P.rows + kWaves - 1) / kWaves)),
+                           dim3(kThreads), args, 0, s);
 }
 
 template <int DT> hipError_t launch_rows(Params P, bool excl, hipStream_t s)
@@ -773,10 +825,11 @@ template <int DT> hipError_t launch_dt(Params P, bool excl, int size, hipStream_
     void *args[] = {&P};
     const void *fn;
     using Ti = Tiles<DT>;
+    const bool rev = P.reverse != 0;
     int waves;
-    if (size == kTileHuge)       { waves = Ti::wHuge;  fn = excl ? (const void *)scan_kernel<DT, Ti::kHuge, true, Ti::wHuge>   : (const void *)scan_kernel<DT, Ti::kHuge, false, Ti::wHuge>; }
-    else if (size == kTileLarge) { waves = Ti::wLarge; fn = excl ? (const void *)scan_kernel<DT, Ti::kLarge, true, Ti::wLarge> : (const void *)scan_kernel<DT, Ti::kLarge, false, Ti::wLarge>; }
-    else                         { waves = Ti::wSmall; fn = excl ? (const void *)scan_kernel<DT, Ti::kSmall, true, Ti::wSmall> : (const void *)scan_kernel<DT, Ti::kSmall, false, Ti::wSmall>; }
+    if (size == kTileHuge)       { waves = Ti::wHuge;  fn = scan_kernel_for<DT, Ti::kHuge, Ti::wHuge>(excl, rev); }
+    else if (size == kTileLarge) { waves = Ti::wLarge; fn = scan_kernel_for<DT, Ti::kLarge, Ti::wLarge>(excl, rev); }
+    else                         { waves = Ti::wSmall; fn = scan_kernel_for<DT, Ti::kSmall, Ti::wSmall>(excl, rev); }
     return hipLaunchKernel(fn, dim3(P.num_tiles), dim3(64 * waves), args, 0, s);
 }
 
@@ -788,7 +841,7 @@ hipError_t launch_fill(void *d, size_t bytes, hipStream_t s)
     return hipLaunchKernel((const void *)fill_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), args, 0, s);
 }
 
-tcuscan_status_t run(const void *d_in, void *d_out, size_t rows, size_t cols, int dt, int exclusive,
+tcuscan_status_t run(const void *d_in, void *d_out, size_t rows, size_t cols, int dt, int exclusive, int reverse,
                      void *d_ws, size_t ws_bytes, tcuscan_stream_t stream)
 {
     if (!valid_dtype(dt)) return TCUSCAN_ERR_UNSUPPORTED;
@@ -808,6 +861,7 @@ tcuscan_status_t run(const void *d_in, void *d_out, size_t rows, size_t cols, in
     P.in = d_in; P.out = d_out; P.rows = rows; P.cols = cols;
     P.tiles_per_row = (uint32_t)tpr; P.num_tiles = (uint32_t)(rows * tpr);
     P.ws = need ? (WsHeader *)d_ws : nullptr;
+    P.reverse = reverse ? 1u : 0u;
     // Every call gets a fresh tag, so status words of earlier calls are stale by construction.  A call
     // recorded into a graph is replayed with the SAME tag; it therefore clears its status words first
     // (with a fill kernel, which a graph replays correctly).
@@ -864,20 +918,27 @@ tcuscan_status_t tcuscan_workspace_init(void *d_ws, size_t ws_bytes, tcuscan_str
 tcuscan_status_t tcuscan_inclusive(const void *d_in, void *d_out, size_t n, tcuscan_dtype_t dt,
                                    void *d_ws, size_t ws_bytes, tcuscan_stream_t stream)
 {
-    return run(d_in, d_out, n ? 1 : 0, n, (int)dt, 0, d_ws, ws_bytes, stream);
+    return run(d_in, d_out, n ? 1 : 0, n, (int)dt, 0, 0, d_ws, ws_bytes, stream);
 }
 
 tcuscan_status_t tcuscan_exclusive(const void *d_in, void *d_out, size_t n, tcuscan_dtype_t dt,
                                    void *d_ws, size_t ws_bytes, tcuscan_stream_t stream)
 {
-    return run(d_in, d_out, n ? 1 : 0, n, (int)dt, 1, d_ws, ws_bytes, stream);
+    return run(d_in, d_out, n ? 1 : 0, n, (int)dt, 1, 0, d_ws, ws_bytes, stream);
 }
 
 tcuscan_status_t tcuscan_batched(const void *d_in, void *d_out, size_t rows, size_t cols,
                                  tcuscan_dtype_t dt, int exclusive,
                                  void *d_ws, size_t ws_bytes, tcuscan_stream_t stream)
 {
-    return run(d_in, d_out, rows, cols, (int)dt, exclusive, d_ws, ws_bytes, stream);
+    return run(d_in, d_out, rows, cols, (int)dt, exclusive, 0, d_ws, ws_bytes, stream);
+}
+
+tcuscan_status_t tcuscan_scan(const void *d_in, void *d_out, size_t rows, size_t cols, tcuscan_dtype_t dt, unsigned flags,
+                              void *d_ws, size_t ws_bytes, tcuscan_stream_t stream)
+{
+    if (flags & ~(unsigned)(TCUSCAN_EXCLUSIVE | TCUSCAN_REVERSE)) return TCUSCAN_ERR_INVALID_ARG;
+    return run(d_in, d_out, rows, cols, (int)dt, (flags & TCUSCAN_EXCLUSIVE) != 0, (flags & TCUSCAN_REVERSE) != 0, d_ws, ws_bytes, stream);
 }
 
 tcuscan_status_t tcuscan_workspace_fault(const void *d_ws, tcuscan_stream_t stream, unsigned *h_fault)

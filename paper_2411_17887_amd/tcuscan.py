@@ -17,7 +17,7 @@ I32_I32, F16_F32, I8_I32, F32_F32, BF16_F32 = 0, 1, 2, 3, 4
 DTYPES = {"i32": I32_I32, "f16": F16_F32, "i8": I8_I32, "f32": F32_F32, "bf16": BF16_F32}
 
 EXPORTS = ["tcuscan_workspace_bytes", "tcuscan_workspace_init", "tcuscan_inclusive", "tcuscan_exclusive",
-           "tcuscan_batched", "tcuscan_tile_elems", "tcuscan_large_tile_elems", "tcuscan_huge_tile_elems",
+           "tcuscan_batched", "tcuscan_scan", "tcuscan_tile_elems", "tcuscan_large_tile_elems", "tcuscan_huge_tile_elems",
            "tcuscan_set_tile_policy",
            "tcuscan_workspace_fault", "tcuscan_matmulscan_levels", "tcuscan_matmulscan_levels_radix", "tcuscan_compact_u32",
            "tcuscan_split_radix_sort_u32", "tcuscan_status_string"]
@@ -57,6 +57,7 @@ def load() -> ctypes.CDLL:
         L.tcuscan_inclusive.argtypes = [vp, vp, sz, ci, vp, sz, vp]
         L.tcuscan_exclusive.argtypes = [vp, vp, sz, ci, vp, sz, vp]
         L.tcuscan_batched.argtypes = [vp, vp, sz, sz, ci, ci, vp, sz, vp]
+        L.tcuscan_scan.argtypes = [vp, vp, sz, sz, ci, ctypes.c_uint, vp, sz, vp]
         L.tcuscan_workspace_fault.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_uint)]
         L.tcuscan_matmulscan_levels.argtypes = [vp, vp, sz, ci, ci, vp, vp]
         L.tcuscan_matmulscan_levels_radix.argtypes = [vp, vp, sz, ci, ci, ci, vp, vp]
@@ -64,7 +65,7 @@ def load() -> ctypes.CDLL:
         L.tcuscan_split_radix_sort_u32.argtypes = [vp, vp, sz, ci, vp, vp, vp, vp, vp, sz, vp]
         L.tcuscan_status_string.argtypes = [ci]
         L.tcuscan_status_string.restype = ctypes.c_char_p
-        for f in ("tcuscan_workspace_init", "tcuscan_inclusive", "tcuscan_exclusive", "tcuscan_batched",
+        for f in ("tcuscan_workspace_init", "tcuscan_inclusive", "tcuscan_exclusive", "tcuscan_batched", "tcuscan_scan",
                   "tcuscan_workspace_fault", "tcuscan_matmulscan_levels", "tcuscan_matmulscan_levels_radix",
                   "tcuscan_compact_u32", "tcuscan_split_radix_sort_u32"):
             getattr(L, f).restype = ci
@@ -153,6 +154,16 @@ def batched(x, out, rows: int, cols: int, dt, exclusive_scan: bool = False, ws=N
                                 _stream(stream))
     if rc != OK:
         raise TcuscanError(rc, "tcuscan_batched")
+
+
+EXCLUSIVE, REVERSE = 1, 2      # flag bits of tcuscan_scan
+
+
+def scan(x, out, rows: int, cols: int, dt, flags: int = 0, ws=None, stream=None) -> None:
+    """Row-wise scans with option flags (EXCLUSIVE, REVERSE = suffix sums)."""
+    rc = load().tcuscan_scan(_ptr(x), _ptr(out), rows, cols, _dt(dt), int(flags), *_ws_args(ws), _stream(stream))
+    if rc != OK:
+        raise TcuscanError(rc, "tcuscan_scan")
 
 
 def matmulscan_levels(x, out, dt, rounds: int = -1, matmuls=None, stream=None, n=None, s: int = 16) -> None:

@@ -50,6 +50,12 @@ def run_scan(x: np.ndarray, kind: str, call: str = "inclusive", rows: int | None
         tcuscan.batched(d_in, d_out, rows, cols, kind, exclusive_scan=False, ws=ws)
     elif call == "batched_exclusive":
         tcuscan.batched(d_in, d_out, rows, cols, kind, exclusive_scan=True, ws=ws)
+    elif call == "reverse":
+        tcuscan.scan(d_in, d_out, rows, cols, kind, flags=tcuscan.REVERSE, ws=ws)
+    elif call == "reverse_exclusive":
+        tcuscan.scan(d_in, d_out, rows, cols, kind, flags=tcuscan.REVERSE | tcuscan.EXCLUSIVE, ws=ws)
+    elif call == "scan_flags0":
+        tcuscan.scan(d_in, d_out, rows, cols, kind, flags=0, ws=ws)
     else:
         raise ValueError(call)
     torch.cuda.synchronize()
