@@ -120,6 +120,23 @@ tcuscan_status_t tcuscan_batched(const void *d_in, void *d_out, size_t rows, siz
 tcuscan_status_t tcuscan_scan(const void *d_in, void *d_out, size_t rows, size_t cols, tcuscan_dtype_t dt, unsigned flags,
                               void *d_ws, size_t ws_bytes, tcuscan_stream_t stream);
 
+/*
+ * Segmented scans: `rows` rows of different lengths stored back to back (the CSR layout); row r is the elements
+ * d_offsets[r] .. d_offsets[r+1]-1 of d_in / d_out, and each row is scanned on its own (Section 2.2 step 1 with
+ * segments of arbitrary lengths; empty rows are allowed).  Flags as for tcuscan_scan.
+ *   d_offsets  rows + 1 signed 64-bit element offsets on the DEVICE, non-decreasing, within [0, total]; 8-byte aligned
+ *   total      number of elements d_in and d_out hold (an upper bound for d_offsets[rows]); sizes the launch
+ *   d_ws       tcuscan_segmented_workspace_bytes(rows, total, dt) bytes, zero-filled once like every workspace here
+ * Three launches are enqueued: tiles per row, their exclusive scan (this library's int32 scan), the scan itself.
+ * Rows may start at any element: a row is tiled from the 16-byte boundary at or below its start, the few elements in
+ * front of it are read as zero and not written.  Offsets that decrease or leave [0, total] are not followed: such
+ * rows are skipped, the workspace's fault word is set to 2 (see tcuscan_workspace_fault) and the results of the call
+ * are unspecified (rows may then overlap); no access outside the n = total elements is made.
+ */
+size_t tcuscan_segmented_workspace_bytes(size_t rows, size_t total, tcuscan_dtype_t dt);
+tcuscan_status_t tcuscan_segmented(const void *d_in, void *d_out, const long long *d_offsets, size_t rows, size_t total,
+                                   tcuscan_dtype_t dt, unsigned flags, void *d_ws, size_t ws_bytes, tcuscan_stream_t stream);
+
 /* Elements the small workgroup tile covers (rows no longer than this need no workspace), and the
  * large and huge tiles that long inputs use (more elements wait in registers per compute unit while
  * the carry chain's latency is paid, and fewer status words are published and polled per byte).  All
@@ -139,9 +156,10 @@ tcuscan_status_t tcuscan_set_tile_policy(int policy);
 
 /*
  * Copy the workspace's sticky fault word to *h_fault (host pointer) after draining
- * `stream`.  Non-zero means a carry-chain wait ran into its spin bound in some earlier
+ * `stream`.  1 means a carry-chain wait ran into its spin bound in some earlier
  * call (results of that call are invalid); this never happens in correct operation and
- * exists so that a protocol failure ends in an error instead of a hung GPU.
+ * exists so that a protocol failure ends in an error instead of a hung GPU.  2 means a
+ * segmented scan was given offsets that decrease or leave [0, total].
  */
 tcuscan_status_t tcuscan_workspace_fault(const void *d_ws, tcuscan_stream_t stream, unsigned *h_fault);
 

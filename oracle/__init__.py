@@ -230,6 +230,59 @@ def compare_float_exact_reverse(x, kind, got, exclusive: bool = False, rows=None
     return compare_float_exact(_flip_rows(xx, rows, cols), k, _flip_rows(got, rows, cols), exclusive, rows, cols)
 
 
+# ---- segmented scans: rows of different lengths stored back to back.  By definition every row is scanned on its
+# own, so the functions below only slice the flat arrays at the offsets and hand each row to the functions above.
+
+def _rows_of(offsets):
+    off = np.asarray(offsets, dtype=np.int64)
+    assert off.ndim == 1 and off.size >= 1 and np.all(np.diff(off) >= 0) and off[0] >= 0
+    return [(int(off[r]), int(off[r + 1])) for r in range(off.size - 1)]
+
+
+def scan_segments(x: np.ndarray, kind, offsets, exclusive: bool = False, reverse: bool = False) -> np.ndarray:
+    """Flat output (int32 or float64) with every row [offsets[r], offsets[r+1]) scanned separately; elements of x
+    outside all rows are returned as 0."""
+    k = _kind(kind)
+    x = np.ascontiguousarray(x).reshape(-1)
+    out = np.zeros(x.size, np.int32 if k in _INT_KINDS else np.float64)
+    f = scan_reverse if reverse else scan
+    for a, b in _rows_of(offsets):
+        if b > a:
+            out[a:b] = f(x[a:b], k, exclusive)
+    return out
+
+
+def compare_segments(x: np.ndarray, kind, offsets, got: np.ndarray, exclusive: bool = False, reverse: bool = False,
+                     exact_float: bool = False):
+    """Integers / exact floats: (mismatches, first bad row or -1).  Floats: the worst FloatReport over the rows
+    (largest E1; non-finite and zero-norm counts summed)."""
+    k = _kind(kind)
+    x = np.ascontiguousarray(x).reshape(-1)
+    got = np.ascontiguousarray(got).reshape(-1)
+    ints = k in _INT_KINDS
+    if ints or exact_float:
+        cmp = (compare_int_reverse if reverse else compare_int) if ints else \
+              (compare_float_exact_reverse if reverse else compare_float_exact)
+        bad, first = 0, -1
+        for r, (a, b) in enumerate(_rows_of(offsets)):
+            if b > a:
+                nb, _ = cmp(x[a:b], k, got[a:b], exclusive)
+                if nb and first < 0:
+                    first = r
+                bad += nb
+        return bad, first
+    cmp = compare_float_reverse if reverse else compare_float
+    worst = FloatReport(0.0, 0.0, 0.0, -1, 0, 0)
+    for a, b in _rows_of(offsets):
+        if b > a:
+            rep = cmp(x[a:b], k, got[a:b], exclusive)
+            zero_bad, nonfin = worst.zero_norm_bad + rep.zero_norm_bad, worst.nonfinite + rep.nonfinite
+            if rep.e1 >= worst.e1:
+                worst = FloatReport(rep.e1, rep.max_abs_err, rep.max_abs_ref, a + rep.worst_index, 0, 0)
+            worst.zero_norm_bad, worst.nonfinite = zero_bad, nonfin
+    return worst
+
+
 def half_to_double(bits: int) -> float:
     return float(lib().oracle_half_to_double(int(bits)))
 

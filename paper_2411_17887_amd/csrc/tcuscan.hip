@@ -73,6 +73,9 @@ struct Params {
     uint32_t    tag;         // this call's tag for the status words
     uint32_t    reverse;     // non-zero: suffix sums (every row is scanned from its end)
     WsHeader   *ws;          // null when tiles_per_row == 1
+    // segmented scans only: rows of different lengths stored back to back
+    const long long *offsets;      // rows + 1 element offsets
+    const uint32_t  *tile_start;   // rows + 1: index of each row's first tile (exclusive scan of the tiles per row)
 };
 
 // ---------------------------------------------------------------- small helpers
@@ -453,6 +456,7 @@ struct Run {
     const char *in;          // first input byte of this wavefront's run
     char *out;               // first output byte of the run
     uint32_t rem;            // elements of the row from the start of the run on (saturated; 0 when the run starts past the end)
+    uint32_t lead;           // segmented scans: elements at the start of the run that lie before the row (read as zero, not written)
     bool in_vec, out_vec;    // run starts are 16-byte aligned
 };
 
@@ -469,7 +473,7 @@ template <int DT, int NT, bool REV> __device__ __forceinline__ uint32_t slot_off
 }
 
 // a1: coalesced 128-bit loads, zero-filled past the end of the row (BatchMatMul's zero-pad)
-template <int DT, int NT, bool REV>
+template <int DT, int NT, bool REV, bool SEG = false>
 __device__ __forceinline__ void load_run(const Run &R, int lane, u32x4 (&g)[NT])
 {
     using T = Tr<DT>;
@@ -477,12 +481,12 @@ __device__ __forceinline__ void load_run(const Run &R, int lane, u32x4 (&g)[NT])
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         const uint32_t e0 = slot_offset<DT, NT, REV>(t, lane);                            // element offset inside the run
-        if (R.in_vec && e0 + kG <= R.rem) {
+        if (R.in_vec && e0 + kG <= R.rem && (!SEG || e0 >= R.lead)) {
             g[t] = *(const u32x4 *)(R.in + e0 * T::kEsz);
         } else {
             uint32_t w[4] = {0u, 0u, 0u, 0u};
             for (int i = 0; i < kG; ++i) {
-                if (e0 + i < R.rem) {
+                if (e0 + i < R.rem && (!SEG || e0 + i >= R.lead)) {
                     uint32_t v;
                     if (T::kEsz == 4)      v = ((const uint32_t *)R.in)[e0 + i];
                     else if (T::kEsz == 2) v = ((const uint16_t *)R.in)[e0 + i];
@@ -523,7 +527,7 @@ template <class A> __device__ __forceinline__ A row_exclusive_scan(A v)
 // a2 + a3 + a5 + a6 for the run, tile by tile with a running carry (`carry` = everything before the run).
 // Nothing passes through LDS: lane l feeds the MFMA with the granule it loaded, and results are stored
 // straight from the MFMA's result registers, 1 KiB of consecutive outputs per store instruction.
-template <int DT, int NT, bool EXCL, bool REV>
+template <int DT, int NT, bool EXCL, bool REV, bool SEG = false>
 __device__ __forceinline__ void scan_and_store(int lane, const typename Tr<DT>::AConst &Aop, const Run &R,
                                                const u32x4 (&g)[NT], typename Tr<DT>::acc carry)
 {
@@ -575,11 +579,11 @@ __device__ __forceinline__ void scan_and_store(int lane, const typename Tr<DT>::
             u32x4 v = bits<u32x4>(d[p]);
             for (int r = 0; r < 4; ++r) v[r] = acc_bits(acc_add(e[p], acc_from_bits<A>(v[r])));
             const uint32_t e0 = slot_offset<DT, NT, REV>(t, 16 * T::Map::jmap(p, q) + c) + 4u * T::Map::sub(p, q);
-            if (R.out_vec && e0 + 4 <= R.rem) {
+            if (R.out_vec && e0 + 4 <= R.rem && (!SEG || e0 >= R.lead)) {
                 __builtin_nontemporal_store(v, (u32x4 *)(R.out + e0 * 4));   // written once, never read back here
             } else {
                 for (int r = 0; r < 4; ++r)
-                    if (e0 + r < R.rem) ((uint32_t *)R.out)[e0 + r] = v[r];
+                    if (e0 + r < R.rem && (!SEG || e0 + r >= R.lead)) ((uint32_t *)R.out)[e0 + r] = v[r];
             }
         }
     }
@@ -596,6 +600,33 @@ __device__ __forceinline__ Run make_run(const Params &P, uint64_t row, uint64_t 
     R.out = (char *)P.out + first * 4;
     const uint64_t left = base < P.cols ? P.cols - base : 0;
     R.rem = left < 0x40000000ull ? (uint32_t)left : 0x40000000u;
+    R.lead = 0;
+    R.in_vec = (((uintptr_t)R.in) & 15) == 0;
+    R.out_vec = (((uintptr_t)R.out) & 15) == 0;
+    return R;
+}
+
+// Segmented scans: a row starts wherever the previous one ended, so its first byte is usually not 16-byte aligned.
+// The row is therefore tiled from the aligned address just below its start: the `lead` elements in front of it
+// (fewer than one granule) are read as zero and never written -- BatchMatMul's zero-pad, at the front -- and every
+// full granule behind them takes the 128-bit path.  With both base pointers 16-byte aligned the outputs line up too:
+// lead = off mod (elements per granule), and (off - lead) outputs are a whole number of 16-byte groups.
+template <int DT>
+__device__ __forceinline__ uint32_t seg_lead(const Params &P, long long off)
+{
+    return (uint32_t)((((uintptr_t)P.in + (uint64_t)off * Tr<DT>::kEsz) & 15) / Tr<DT>::kEsz);
+}
+template <int DT>
+__device__ __forceinline__ Run make_seg_run(const Params &P, long long off, uint64_t len, uint32_t lead, uint64_t base)
+{
+    Run R;
+    const long long first = off - (long long)lead + (long long)base;      // element index of the run's first slot
+    R.in = (const char *)P.in + first * Tr<DT>::kEsz;
+    R.out = (char *)P.out + first * 4;
+    const uint64_t vlen = len + lead;
+    const uint64_t left = base < vlen ? vlen - base : 0;
+    R.rem = left < 0x40000000ull ? (uint32_t)left : 0x40000000u;
+    R.lead = base < lead ? lead - (uint32_t)base : 0;
     R.in_vec = (((uintptr_t)R.in) & 15) == 0;
     R.out_vec = (((uintptr_t)R.out) & 15) == 0;
     return R;
@@ -610,7 +641,7 @@ template <> struct MinWaves<TCUSCAN_I8_I32, 8>    { static constexpr int value =
 template <> struct MinWaves<TCUSCAN_F16_F32, 16>  { static constexpr int value = 4; };
 template <> struct MinWaves<TCUSCAN_BF16_F32, 16> { static constexpr int value = 4; };
 
-template <int DT, int NT, bool EXCL, bool REV, int W>
+template <int DT, int NT, bool EXCL, bool REV, int W, bool SEG = false>
 __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(MinWaves<DT, NT>::value)))
 void scan_kernel(Params P)
 {
@@ -631,16 +662,41 @@ void scan_kernel(Params P)
     // guarantee the same without that assumption, but one contended atomic per tile caps the whole
     // kernel at the device's single-address atomic rate.)  Status words carry the call's tag, so
     // words left over from earlier calls read as "not published yet" and need no clearing.
-    const bool chained = P.tiles_per_row > 1;
     const uint32_t tile = blockIdx.x;
     const uint32_t tag = P.tag;
-    const uint64_t row = tile / P.tiles_per_row;
-    const uint32_t tr = tile - (uint32_t)row * P.tiles_per_row;           // position in the carry chain of the row
-    const uint32_t pos = REV ? P.tiles_per_row - 1 - tr : tr;             // position in the row: a reverse scan starts at the end
-    const Run R = make_run<DT>(P, row, (uint64_t)pos * kWgElems + (uint64_t)wave * kEPW);
+    uint64_t row;
+    uint32_t tr, tiles_in_row, first_tile;        // position in the carry chain of the row, its length, the row's first tile
+    Run R;
+    if constexpr (SEG) {
+        // Rows have their own numbers of tiles: tile_start is their exclusive scan, the grid is an upper bound.
+        // The row of this tile is the last one that starts at or before it.
+        const uint32_t *ts = P.tile_start;
+        if (tile >= ts[P.rows]) return;
+        uint64_t lo = 0, hi = P.rows;             // ts[lo] <= tile < ts[hi]
+        while (hi - lo > 1) {
+            const uint64_t mid = (lo + hi) / 2;
+            if (ts[mid] <= tile) lo = mid; else hi = mid;
+        }
+        row = lo;
+        first_tile = ts[row];
+        tiles_in_row = ts[row + 1] - first_tile;
+        tr = tile - first_tile;
+        const long long off = P.offsets[row];
+        const uint64_t len = (uint64_t)(P.offsets[row + 1] - off);
+        const uint32_t pos = REV ? tiles_in_row - 1 - tr : tr;
+        R = make_seg_run<DT>(P, off, len, seg_lead<DT>(P, off), (uint64_t)pos * kWgElems + (uint64_t)wave * kEPW);
+    } else {
+        row = tile / P.tiles_per_row;
+        tiles_in_row = P.tiles_per_row;
+        first_tile = (uint32_t)row * P.tiles_per_row;
+        tr = tile - first_tile;
+        const uint32_t pos = REV ? tiles_in_row - 1 - tr : tr;            // position in the row: a reverse scan starts at the end
+        R = make_run<DT>(P, row, (uint64_t)pos * kWgElems + (uint64_t)wave * kEPW);
+    }
+    const bool chained = tiles_in_row > 1;
 
     u32x4 g[NT];
-    load_run<DT, NT, REV>(R, lane, g);
+    load_run<DT, NT, REV, SEG>(R, lane, g);
     const typename T::AConst Aop = T::make(lane, EXCL, REV);
 
     // ---- the total of the run (the up-sweep of this tile in one step)
@@ -660,7 +716,7 @@ void scan_kernel(Params P)
     // ---- a4: carry chain between workgroup tiles of the same row
     A prefix = acc_from_bits<A>(0u);
     if (chained) {
-        uint64_t *row_status = (uint64_t *)(P.ws + 1) + row * P.tiles_per_row * kStatusStride;
+        uint64_t *row_status = (uint64_t *)(P.ws + 1) + (uint64_t)first_tile * kStatusStride;
         if (wave == 0) {
             if (tr == 0) {
                 if (lane == 0)
@@ -682,7 +738,7 @@ void scan_kernel(Params P)
     }
 
     // ---- local scans, down-sweep add and store, with everything before this wavefront's run as carry
-    scan_and_store<DT, NT, EXCL, REV>(lane, Aop, R, g, acc_add(prefix, wave_off));
+    scan_and_store<DT, NT, EXCL, REV, SEG>(lane, Aop, R, g, acc_add(prefix, wave_off));
 }
 
 // ---------------------------------------------------------------------- short-row kernel
@@ -706,6 +762,28 @@ __global__ __launch_bounds__(kThreads) void scan_rows_kernel(Params P)
     load_run<DT, NT, REV>(R, lane, g);
     const typename T::AConst Aop = T::make(lane, EXCL, REV);
     scan_and_store<DT, NT, EXCL, REV>(lane, Aop, R, g, acc_from_bits<A>(0u));
+}
+
+// Segmented scans, step 1: tiles per row.  A row [off, off + len) is tiled from the 16-byte boundary at or below its
+// start, so it needs ceil((lead + len) / tile) tiles (none when it is empty).  Offsets that decrease or leave
+// [0, total] give the row no tiles and raise the fault word instead of letting the scan touch memory outside the
+// caller's arrays.  Entry `rows` is zero: the exclusive scan of this array then ends with the total number of tiles.
+__global__ void seg_tiles_kernel(const long long *offsets, size_t rows, size_t total, uintptr_t in_addr, uint32_t esz,
+                                 uint32_t tile, int32_t *counts, WsHeader *ws)
+{
+    const size_t r = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r > rows) return;
+    int32_t c = 0;
+    if (r < rows) {
+        const long long off = offsets[r], end = offsets[r + 1];
+        if (off < 0 || end < off || (unsigned long long)end > total) {
+            __hip_atomic_store(&ws->fault, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else if (end > off) {
+            const uint64_t lead = ((in_addr + (uint64_t)off * esz) & 15) / esz;
+            c = (int32_t)((lead + (uint64_t)(end - off) + tile - 1) / tile);
+        }
+    }
+    counts[r] = c;
 }
 
 __global__ void fill_zero_kernel(uint32_t *p, size_t words)
@@ -862,6 +940,7 @@ tcuscan_status_t run(const void *d_in, void *d_out, size_t rows, size_t cols, in
     P.tiles_per_row = (uint32_t)tpr; P.num_tiles = (uint32_t)(rows * tpr);
     P.ws = need ? (WsHeader *)d_ws : nullptr;
     P.reverse = reverse ? 1u : 0u;
+    P.offsets = nullptr; P.tile_start = nullptr;
     // Every call gets a fresh tag, so status words of earlier calls are stale by construction.  A call
     // recorded into a graph is replayed with the SAME tag; it therefore clears its status words first
     // (with a fill kernel, which a graph replays correctly).
@@ -879,6 +958,101 @@ tcuscan_status_t run(const void *d_in, void *d_out, size_t rows, size_t cols, in
     case TCUSCAN_I8_I32:   e = launch_dt<TCUSCAN_I8_I32>(P, exclusive != 0, size, s); break;
     case TCUSCAN_F32_F32:  e = launch_dt<TCUSCAN_F32_F32>(P, exclusive != 0, size, s); break;
     default:               e = launch_dt<TCUSCAN_BF16_F32>(P, exclusive != 0, size, s); break;
+    }
+    return e == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
+}
+
+// ---- segmented scans (rows of different lengths, stored back to back)
+
+constexpr int kSegShortNT = 2;      // the short-segment tile: one wavefront, two MFMA tiles (128 granules)
+
+size_t seg_tile_elems(int dt, size_t rows, size_t total)
+{
+    // average row length decides: rows much longer than the one-wavefront tile take the small workgroup tile
+    const size_t gran = 16 / in_size(dt);
+    const size_t short_tile = (size_t)kSegShortNT * 64 * gran;
+    return (rows == 0 || total / rows >= 4 * short_tile) ? kSmallTile : short_tile;
+}
+
+struct SegLayout {
+    size_t max_tiles;        // upper bound on the number of tiles = grid size
+    size_t counts_off, starts_off, inner_off, inner_bytes, total_bytes;
+};
+
+bool seg_layout(int dt, size_t rows, size_t total, SegLayout &L)
+{
+    const size_t tile = seg_tile_elems(dt, rows, total);
+    L.max_tiles = total / tile + 2 * rows + 1;           // a row of len elements has at most len / tile + 2 tiles
+    if (L.max_tiles > 0x7FFFFFFFull || rows + 1 > 0x7FFFFFFFull) return false;
+    auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
+    L.counts_off = up(sizeof(WsHeader) + 8 * kStatusStride * L.max_tiles);
+    L.starts_off = up(L.counts_off + 4 * (rows + 1));
+    L.inner_off = up(L.starts_off + 4 * (rows + 1));
+    L.inner_bytes = tcuscan_workspace_bytes(1, rows + 1, TCUSCAN_I32_I32);
+    L.total_bytes = L.inner_off + L.inner_bytes;
+    return true;
+}
+
+template <int DT, int NT, int W> const void *seg_kernel_for(bool excl, bool rev)
+{
+    if (rev) return excl ? (const void *)scan_kernel<DT, NT, true, true, W, true> : (const void *)scan_kernel<DT, NT, false, true, W, true>;
+    return excl ? (const void *)scan_kernel<DT, NT, true, false, W, true> : (const void *)scan_kernel<DT, NT, false, false, W, true>;
+}
+
+template <int DT> hipError_t launch_seg(Params P, bool excl, bool big, hipStream_t s)
+{
+    void *args[] = {&P};
+    using Ti = Tiles<DT>;
+    if (big) return hipLaunchKernel(seg_kernel_for<DT, Ti::kSmall, Ti::wSmall>(excl, P.reverse != 0), dim3(P.num_tiles), dim3(64 * Ti::wSmall), args, 0, s);
+    return hipLaunchKernel(seg_kernel_for<DT, kSegShortNT, 1>(excl, P.reverse != 0), dim3(P.num_tiles), dim3(64), args, 0, s);
+}
+
+tcuscan_status_t run_segmented(const void *d_in, void *d_out, const long long *d_offsets, size_t rows, size_t total, int dt,
+                               int exclusive, int reverse, void *d_ws, size_t ws_bytes, tcuscan_stream_t stream)
+{
+    if (!valid_dtype(dt)) return TCUSCAN_ERR_UNSUPPORTED;
+    if (rows == 0 || total == 0) return TCUSCAN_OK;
+    if (!d_in || !d_out || !d_offsets) return TCUSCAN_ERR_INVALID_ARG;
+    if (((uintptr_t)d_in % in_size(dt)) != 0 || ((uintptr_t)d_out % 4) != 0 || ((uintptr_t)d_offsets % 8) != 0) return TCUSCAN_ERR_INVALID_ARG;
+    if (d_in == d_out && in_size(dt) != 4) return TCUSCAN_ERR_INVALID_ARG;
+    SegLayout L;
+    if (!seg_layout(dt, rows, total, L)) return TCUSCAN_ERR_UNSUPPORTED;
+    if (!d_ws || ws_bytes < L.total_bytes || ((uintptr_t)d_ws % 8) != 0) return TCUSCAN_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const size_t tile = seg_tile_elems(dt, rows, total);
+    int32_t *counts = (int32_t *)((char *)d_ws + L.counts_off);
+    uint32_t *starts = (uint32_t *)((char *)d_ws + L.starts_off);
+    {   // step 1: tiles per row
+        const long long *off = d_offsets; size_t r = rows, t = total; uintptr_t in_addr = (uintptr_t)d_in;
+        uint32_t esz = (uint32_t)in_size(dt), tl = (uint32_t)tile; WsHeader *h = (WsHeader *)d_ws;
+        void *args[] = {&off, &r, &t, &in_addr, &esz, &tl, &counts, &h};
+        if (hipLaunchKernel((const void *)seg_tiles_kernel, dim3((unsigned)((rows + 1 + 255) / 256)), dim3(256), args, 0, s) != hipSuccess)
+            return TCUSCAN_ERR_HIP;
+    }
+    // step 2: first tile of every row = exclusive scan of the counts (this library's own int32 scan)
+    tcuscan_status_t st = run(counts, starts, 1, rows + 1, TCUSCAN_I32_I32, 1, 0, L.inner_bytes ? (char *)d_ws + L.inner_off : nullptr,
+                              L.inner_bytes, stream);
+    if (st != TCUSCAN_OK) return st;
+    // step 3: the scan itself; the grid is the upper bound on the number of tiles, surplus workgroups leave at once
+    Params P;
+    P.in = d_in; P.out = d_out; P.rows = rows; P.cols = 0;
+    P.tiles_per_row = 0; P.num_tiles = (uint32_t)L.max_tiles;
+    P.ws = (WsHeader *)d_ws;
+    P.reverse = reverse ? 1u : 0u;
+    P.offsets = d_offsets; P.tile_start = starts;
+    P.tag = g_calls.fetch_add(1u, std::memory_order_relaxed) % kTagMod + 1u;
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &cs) != hipSuccess) { (void)hipGetLastError(); cs = hipStreamCaptureStatusNone; }
+    if (cs == hipStreamCaptureStatusActive &&
+        launch_fill((char *)d_ws + sizeof(WsHeader), 8 * kStatusStride * L.max_tiles, s) != hipSuccess) return TCUSCAN_ERR_HIP;
+    const bool big = tile == kSmallTile;
+    hipError_t e;
+    switch (dt) {
+    case TCUSCAN_I32_I32:  e = launch_seg<TCUSCAN_I32_I32>(P, exclusive != 0, big, s); break;
+    case TCUSCAN_F16_F32:  e = launch_seg<TCUSCAN_F16_F32>(P, exclusive != 0, big, s); break;
+    case TCUSCAN_I8_I32:   e = launch_seg<TCUSCAN_I8_I32>(P, exclusive != 0, big, s); break;
+    case TCUSCAN_F32_F32:  e = launch_seg<TCUSCAN_F32_F32>(P, exclusive != 0, big, s); break;
+    default:               e = launch_seg<TCUSCAN_BF16_F32>(P, exclusive != 0, big, s); break;
     }
     return e == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
 }
@@ -939,6 +1113,21 @@ tcuscan_status_t tcuscan_scan(const void *d_in, void *d_out, size_t rows, size_t
 {
     if (flags & ~(unsigned)(TCUSCAN_EXCLUSIVE | TCUSCAN_REVERSE)) return TCUSCAN_ERR_INVALID_ARG;
     return run(d_in, d_out, rows, cols, (int)dt, (flags & TCUSCAN_EXCLUSIVE) != 0, (flags & TCUSCAN_REVERSE) != 0, d_ws, ws_bytes, stream);
+}
+
+size_t tcuscan_segmented_workspace_bytes(size_t rows, size_t total, tcuscan_dtype_t dt)
+{
+    SegLayout L;
+    if (!valid_dtype((int)dt) || rows == 0 || total == 0 || !seg_layout((int)dt, rows, total, L)) return 0;
+    return L.total_bytes;
+}
+
+tcuscan_status_t tcuscan_segmented(const void *d_in, void *d_out, const long long *d_offsets, size_t rows, size_t total,
+                                   tcuscan_dtype_t dt, unsigned flags, void *d_ws, size_t ws_bytes, tcuscan_stream_t stream)
+{
+    if (flags & ~(unsigned)(TCUSCAN_EXCLUSIVE | TCUSCAN_REVERSE)) return TCUSCAN_ERR_INVALID_ARG;
+    return run_segmented(d_in, d_out, d_offsets, rows, total, (int)dt, (flags & TCUSCAN_EXCLUSIVE) != 0, (flags & TCUSCAN_REVERSE) != 0,
+                         d_ws, ws_bytes, stream);
 }
 
 tcuscan_status_t tcuscan_workspace_fault(const void *d_ws, tcuscan_stream_t stream, unsigned *h_fault)

@@ -17,7 +17,7 @@ I32_I32, F16_F32, I8_I32, F32_F32, BF16_F32 = 0, 1, 2, 3, 4
 DTYPES = {"i32": I32_I32, "f16": F16_F32, "i8": I8_I32, "f32": F32_F32, "bf16": BF16_F32}
 
 EXPORTS = ["tcuscan_workspace_bytes", "tcuscan_workspace_init", "tcuscan_inclusive", "tcuscan_exclusive",
-           "tcuscan_batched", "tcuscan_scan", "tcuscan_tile_elems", "tcuscan_large_tile_elems", "tcuscan_huge_tile_elems",
+           "tcuscan_batched", "tcuscan_scan", "tcuscan_segmented_workspace_bytes", "tcuscan_segmented", "tcuscan_tile_elems", "tcuscan_large_tile_elems", "tcuscan_huge_tile_elems",
            "tcuscan_set_tile_policy",
            "tcuscan_workspace_fault", "tcuscan_matmulscan_levels", "tcuscan_matmulscan_levels_radix", "tcuscan_compact_u32",
            "tcuscan_split_radix_sort_u32", "tcuscan_status_string"]
@@ -58,6 +58,9 @@ def load() -> ctypes.CDLL:
         L.tcuscan_exclusive.argtypes = [vp, vp, sz, ci, vp, sz, vp]
         L.tcuscan_batched.argtypes = [vp, vp, sz, sz, ci, ci, vp, sz, vp]
         L.tcuscan_scan.argtypes = [vp, vp, sz, sz, ci, ctypes.c_uint, vp, sz, vp]
+        L.tcuscan_segmented_workspace_bytes.argtypes = [sz, sz, ci]
+        L.tcuscan_segmented_workspace_bytes.restype = sz
+        L.tcuscan_segmented.argtypes = [vp, vp, vp, sz, sz, ci, ctypes.c_uint, vp, sz, vp]
         L.tcuscan_workspace_fault.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_uint)]
         L.tcuscan_matmulscan_levels.argtypes = [vp, vp, sz, ci, ci, vp, vp]
         L.tcuscan_matmulscan_levels_radix.argtypes = [vp, vp, sz, ci, ci, ci, vp, vp]
@@ -65,7 +68,7 @@ def load() -> ctypes.CDLL:
         L.tcuscan_split_radix_sort_u32.argtypes = [vp, vp, sz, ci, vp, vp, vp, vp, vp, sz, vp]
         L.tcuscan_status_string.argtypes = [ci]
         L.tcuscan_status_string.restype = ctypes.c_char_p
-        for f in ("tcuscan_workspace_init", "tcuscan_inclusive", "tcuscan_exclusive", "tcuscan_batched", "tcuscan_scan",
+        for f in ("tcuscan_workspace_init", "tcuscan_inclusive", "tcuscan_exclusive", "tcuscan_batched", "tcuscan_scan", "tcuscan_segmented",
                   "tcuscan_workspace_fault", "tcuscan_matmulscan_levels", "tcuscan_matmulscan_levels_radix",
                   "tcuscan_compact_u32", "tcuscan_split_radix_sort_u32"):
             getattr(L, f).restype = ci
@@ -164,6 +167,25 @@ def scan(x, out, rows: int, cols: int, dt, flags: int = 0, ws=None, stream=None)
     rc = load().tcuscan_scan(_ptr(x), _ptr(out), rows, cols, _dt(dt), int(flags), *_ws_args(ws), _stream(stream))
     if rc != OK:
         raise TcuscanError(rc, "tcuscan_scan")
+
+
+def segmented_workspace_bytes(rows: int, total: int, dt) -> int:
+    return int(load().tcuscan_segmented_workspace_bytes(rows, total, _dt(dt)))
+
+
+def new_segmented_workspace(rows: int, total: int, dt):
+    """A zero-filled workspace for tcuscan_segmented (None when nothing is to be done)."""
+    import torch
+    nbytes = segmented_workspace_bytes(rows, total, dt)
+    return torch.zeros(nbytes // 8 + 1, dtype=torch.int64, device="cuda") if nbytes else None
+
+
+def segmented(x, out, offsets, rows: int, total: int, dt, flags: int = 0, ws=None, stream=None) -> None:
+    """Row-wise scans of rows stored back to back; `offsets`: int64 device tensor of rows + 1 element offsets."""
+    rc = load().tcuscan_segmented(_ptr(x), _ptr(out), _ptr(offsets), rows, total, _dt(dt), int(flags), *_ws_args(ws),
+                                  _stream(stream))
+    if rc != OK:
+        raise TcuscanError(rc, "tcuscan_segmented")
 
 
 def matmulscan_levels(x, out, dt, rounds: int = -1, matmuls=None, stream=None, n=None, s: int = 16) -> None:

@@ -1,0 +1,187 @@
+"""GPU parity for segmented scans (tcuscan_segmented: rows of different lengths stored back to back) against the
+CPU oracle, which scans every row on its own.  Same bars as the other suites; elements outside all rows must be
+left untouched."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2411_17887_amd import inputs, tcuscan
+from gpu_util import to_device, out_dtype
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f16": 1e-3, "bf16": 1e-3, "f32": 1e-5}
+INT_GEN = {"i32": inputs.int32_full, "i8": inputs.int8_full}
+TRI_GEN = {"f32": inputs.tri_f32, "f16": inputs.tri_f16, "bf16": inputs.tri_bf16_bits}
+RND_GEN = {"f32": inputs.f32_normal, "f16": inputs.f16_uniform01, "bf16": inputs.bf16_uniform_pm1}
+KINDS = ["i32", "f16", "i8", "f32", "bf16"]
+GUARD = -77
+
+
+def offsets_from(lengths, start=0):
+    return np.concatenate([[start], start + np.cumsum(np.asarray(lengths, dtype=np.int64))]).astype(np.int64)
+
+
+def run_segmented(x, kind, off, total=None, flags=0, ws=None, inplace=False):
+    import torch
+    total = x.size if total is None else total
+    rows = off.size - 1
+    d_in = to_device(x, kind)
+    d_out = d_in if inplace else torch.full((x.size,), GUARD, dtype=out_dtype(kind), device="cuda")
+    d_off = torch.from_numpy(off).cuda()
+    if ws is None:
+        ws = tcuscan.new_segmented_workspace(rows, total, kind)
+    tcuscan.segmented(d_in, d_out, d_off, rows, total, kind, flags=flags, ws=ws)
+    torch.cuda.synchronize()
+    fault = tcuscan.workspace_fault(ws) if ws is not None else 0
+    return d_out.cpu().numpy().copy(), fault
+
+
+def check(x, kind, off, got, excl, rev, exact_float=False):
+    if kind in INT_GEN or exact_float:
+        nb, first = oracle.compare_segments(x, kind, off, got, exclusive=excl, reverse=rev, exact_float=kind not in INT_GEN)
+        assert nb == 0, f"{kind}: {nb} mismatches, first bad row {first}"
+    else:
+        rep = oracle.compare_segments(x, kind, off, got, exclusive=excl, reverse=rev)
+        assert rep.ok(TOL[kind]), f"{kind}: {rep}"
+    # nothing outside the rows is written
+    mask = np.ones(x.size, bool)
+    mask[int(off[0]):int(off[-1])] = False
+    assert np.all(got[mask] == GUARD)
+
+
+def lengths_mix(rng, rows, mean):
+    """Row lengths with the spread of a sparse matrix / ragged batch: many short rows, a few long ones, some empty."""
+    l = rng.geometric(1.0 / max(mean, 1), size=rows) - 1
+    l[rng.integers(0, rows, size=max(rows // 50, 1))] = 0
+    if rows >= 8:
+        l[rng.integers(0, rows, size=max(rows // 100, 1))] = mean * 40 + 13
+    return l.astype(np.int64)
+
+
+@pytest.mark.parametrize("flags", [0, 1, 2, 3])
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("rows,mean", [(1, 5000), (7, 3), (300, 50), (2000, 700), (40, 30000), (5, 300000)])
+def test_ragged_rows(kind, rows, mean, flags):
+    rng = np.random.default_rng(rows * 7 + mean)
+    off = offsets_from(lengths_mix(rng, rows, mean), start=int(rng.integers(0, 9)))
+    n = int(off[-1]) + 5
+    excl, rev = bool(flags & 1), bool(flags & 2)
+    gen = INT_GEN.get(kind) or TRI_GEN[kind]
+    x = gen(n, 100 + rows)
+    got, fault = run_segmented(x, kind, off, flags=flags)
+    assert fault == 0
+    check(x, kind, off, got, excl, rev, exact_float=True)
+    if kind not in INT_GEN and flags in (0, 3):
+        x = RND_GEN[kind](n, 200 + rows)
+        got, fault = run_segmented(x, kind, off, flags=flags)
+        assert fault == 0
+        check(x, kind, off, got, excl, rev)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_every_start_alignment_and_length_around_the_tiles(kind):
+    """Rows that start at every offset modulo a granule and have lengths around the tile sizes."""
+    short = 2 * 64 * {"i32": 4, "f32": 4, "f16": 8, "bf16": 8, "i8": 16}[kind]
+    lens = []
+    for base in (1, 15, 16, 17, 63, 64, 65, short - 1, short, short + 1, 2 * short + 3, 8191, 8192, 8193, 3 * 8192 + 5):
+        lens += [base, 1 + len(lens) % 17]                     # a filler row shifts the next start
+    off = offsets_from(lens, start=1)
+    gen = INT_GEN.get(kind) or TRI_GEN[kind]
+    x = gen(int(off[-1]) + 3, 31)
+    for flags in (0, 1, 2, 3):
+        got, fault = run_segmented(x, kind, off, flags=flags)
+        assert fault == 0
+        check(x, kind, off, got, bool(flags & 1), bool(flags & 2), exact_float=True)
+    # the same rows through the long-row tile (a large `total` raises the average row length)
+    got, fault = run_segmented(x, kind, off[:4], total=x.size, flags=0)
+    check(x, kind, off[:4], got, False, False, exact_float=True)
+
+
+def test_equal_rows_match_the_batched_call():
+    import torch
+    rows, cols = 37, 10_001
+    x = inputs.int32_full(rows * cols, 5)
+    off = (np.arange(rows + 1, dtype=np.int64) * cols)
+    got, _ = run_segmented(x, "i32", off)
+    d_in = to_device(x, "i32")
+    d_out = torch.empty(rows * cols, dtype=torch.int32, device="cuda")
+    tcuscan.batched(d_in, d_out, rows, cols, "i32", ws=tcuscan.new_workspace(rows, cols, "i32"))
+    assert np.array_equal(got, d_out.cpu().numpy())
+
+
+def test_many_rows_and_workspace_reuse():
+    rng = np.random.default_rng(99)
+    rows = 200_000
+    off = offsets_from(lengths_mix(rng, rows, 60))
+    n = int(off[-1])
+    x = inputs.mask_i8(n, 8)
+    ws = tcuscan.new_segmented_workspace(rows, n, "i8")
+    for flags in (1, 0, 3):
+        got, fault = run_segmented(x, "i8", off, flags=flags, ws=ws)
+        assert fault == 0
+        check(x, "i8", off, got, bool(flags & 1), bool(flags & 2))
+    xf = inputs.f32_normal(n, 9)
+    wsf = tcuscan.new_segmented_workspace(rows, n, "f32")
+    got, fault = run_segmented(xf, "f32", off, ws=wsf)
+    check(xf, "f32", off, got, False, False)
+
+
+def test_long_rows_full_size():
+    # 2^27 elements in 64 rows of very different lengths (the long-row tile, chains of up to thousands of tiles)
+    rng = np.random.default_rng(3)
+    cuts = np.sort(rng.integers(0, 1 << 27, size=63))
+    off = np.concatenate([[0], cuts, [1 << 27]]).astype(np.int64)
+    x = inputs.bf16_uniform_pm1(1 << 27, 21)
+    got, fault = run_segmented(x, "bf16", off, flags=0)
+    assert fault == 0
+    check(x, "bf16", off, got, False, False)
+    x = inputs.mask_i8(1 << 27, 22)
+    got, fault = run_segmented(x, "i8", off, flags=3)
+    check(x, "i8", off, got, True, True)
+
+
+def test_in_place_and_empty_calls():
+    import torch
+    rng = np.random.default_rng(12)
+    off = offsets_from(lengths_mix(rng, 500, 90), start=2)
+    x = inputs.int32_full(int(off[-1]) + 1, 13)
+    got, fault = run_segmented(x, "i32", off, inplace=True)
+    want = oracle.scan_segments(x, "i32", off)
+    inside = slice(int(off[0]), int(off[-1]))
+    assert fault == 0 and np.array_equal(got[inside], want[inside])
+    assert got[0] == x[0] and got[1] == x[1] and got[-1] == x[-1]          # outside the rows: untouched
+    t = torch.zeros(16, dtype=torch.int32, device="cuda")
+    o = torch.zeros(3, dtype=torch.int64, device="cuda")
+    tcuscan.segmented(t, t, o, 0, 16, "i32")                                # no rows: nothing enqueued
+    tcuscan.segmented(t, t, o, 2, 0, "i32")
+    assert tcuscan.segmented_workspace_bytes(0, 16, "i32") == 0
+
+
+def test_bad_offsets_are_not_followed_and_raise_the_fault_word():
+    x = inputs.int32_full(1000, 14)
+    off = np.array([0, 100, 100, 400, 5000], np.int64)                     # the last row leaves [0, total]
+    got, fault = run_segmented(x, "i32", off)
+    assert fault == 2
+    want = oracle.scan_segments(x, "i32", off[:4])
+    assert np.array_equal(got[:400], want[:400])                            # the valid rows are scanned
+    assert np.all(got[400:] == GUARD)                                       # the bad one is skipped
+    for bad in ([0, 300, 200, 250, 1000], [-5, 10, 20, 30, 40], [0, 10, 20, 30, 1001]):
+        got, fault = run_segmented(x, "i32", np.array(bad, np.int64))
+        assert fault == 2                                                   # results unspecified, but flagged and in bounds
+
+
+def test_refusals():
+    import torch
+    t = torch.zeros(64, dtype=torch.int32, device="cuda")
+    o = torch.zeros(3, dtype=torch.int64, device="cuda")
+    ws = tcuscan.new_segmented_workspace(2, 64, "i32")
+    with pytest.raises(tcuscan.TcuscanError) as e:
+        tcuscan.segmented(t, t, o, 2, 64, "i32", flags=8, ws=ws)
+    assert e.value.code == tcuscan.ERR_INVALID_ARG
+    with pytest.raises(tcuscan.TcuscanError) as e:
+        tcuscan.segmented(t, t, o, 2, 64, "i32", ws=None)
+    assert e.value.code == tcuscan.ERR_WORKSPACE
+    with pytest.raises(tcuscan.TcuscanError) as e:
+        tcuscan.segmented(t, t, None, 2, 64, "i32", ws=ws)
+    assert e.value.code == tcuscan.ERR_INVALID_ARG
