@@ -143,6 +143,66 @@ def measure_levels(steps: int):
     return res
 
 
+def measure_variants(steps: int):
+    """Reverse scans on the C3 / C5 shapes and segmented scans on two ragged layouts (seeded geometric row lengths)."""
+    import torch
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    res = {}
+    n = 1 << 28
+    d_in = torch.from_numpy(inputs.mask_i8(n, inputs.CONFIGS["C3"]["seed"])).cuda()
+    d_out = torch.empty(n, dtype=torch.int32, device="cuda")
+    ws = tcuscan.new_workspace(1, n, "i8")
+    ms = timed(lambda: tcuscan.scan(d_in, d_out, 1, n, "i8", flags=tcuscan.REVERSE | tcuscan.EXCLUSIVE, ws=ws))
+    res["reverse_C3_shape"] = {"workload": "exclusive suffix sums, n=2^28, int8 {0,1} -> int32", "ms": ms,
+                               "gelems_per_s": n / ms / 1e6, "frac_of_peak": n * 5 / ms / 1e6 / PEAK_HBM_GBPS}
+    del d_in, ws
+    rows, cols = 4096, 65536
+    xb = torch.from_numpy(inputs.bf16_uniform_pm1(rows * cols, 5).view(np.int16)).cuda().view(torch.bfloat16)
+    d_of = d_out.view(torch.float32)
+    ws = tcuscan.new_workspace(rows, cols, "bf16")
+    ms = timed(lambda: tcuscan.scan(xb, d_of, rows, cols, "bf16", flags=tcuscan.REVERSE, ws=ws))
+    res["reverse_C5_shape"] = {"workload": "inclusive suffix sums, 4096 x 65536, bf16 -> fp32", "ms": ms,
+                               "gelems_per_s": rows * cols / ms / 1e6, "frac_of_peak": rows * cols * 6 / ms / 1e6 / PEAK_HBM_GBPS}
+    # segmented: (a) 2^27 bf16 elements in 64 rows cut at seeded random places; (b) 2^26 fp32 elements in rows of
+    # geometric length, mean 200 (the length mix of a sparse matrix / a ragged batch), a few empty and a few long ones
+    rng = np.random.default_rng(241117887)
+    m = 1 << 27
+    off = np.concatenate([[0], np.sort(rng.integers(0, m, size=63)), [m]]).astype(np.int64)
+    d_off = torch.from_numpy(off).cuda()
+    ws = tcuscan.new_segmented_workspace(64, m, "bf16")
+    ms = timed(lambda: tcuscan.segmented(xb, d_of, d_off, 64, m, "bf16", ws=ws))
+    res["segmented_long_rows"] = {"workload": "2^27 bf16 -> fp32 in 64 rows of random lengths", "ms": ms,
+                                  "gelems_per_s": m / ms / 1e6, "frac_of_peak": m * 6 / ms / 1e6 / PEAK_HBM_GBPS}
+    del xb, ws
+    m = 1 << 26
+    lens = rng.geometric(1.0 / 200, size=int(m / 199)) - 1
+    lens[:: 97] = 0
+    lens[:: 1009] = 8000 + 13
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    off = off[off <= m]
+    nrows = off.size - 1
+    xf = torch.from_numpy(inputs.f32_normal(m, 6)).cuda()
+    d_off = torch.from_numpy(off).cuda()
+    ws = tcuscan.new_segmented_workspace(nrows, m, "f32")
+    ms = timed(lambda: tcuscan.segmented(xf, d_of, d_off, nrows, m, "f32", ws=ws))
+    covered = int(off[-1])
+    res["segmented_short_rows"] = {"workload": f"{covered} fp32 elements in {nrows} rows, geometric lengths (mean 200), some empty, some of 8013",
+                                   "ms": ms, "gelems_per_s": covered / ms / 1e6, "frac_of_peak": covered * 8 / ms / 1e6 / PEAK_HBM_GBPS}
+    return res
+
+
 def measure_apps(steps: int):
     """Stream compaction on the C3 mask (n = 2^28) and the 32-pass split radix sort (n = 2^26 random 32-bit keys)."""
     import torch
@@ -272,6 +332,7 @@ def main() -> int:
             others[name] = {k: r[k] for k in ("workload", "kernel_ms", "gelems_per_s", "achieved_GBps", "frac_of_peak")}
         others["algorithm1_round_by_round"] = measure_levels(5)
         others.update(measure_apps(5))
+        others.update(measure_variants(10))
     ceiling = copy_ceiling_gbps()
 
     line = {

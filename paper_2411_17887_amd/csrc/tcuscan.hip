@@ -76,6 +76,7 @@ struct Params {
     // segmented scans only: rows of different lengths stored back to back
     const long long *offsets;      // rows + 1 element offsets
     const uint32_t  *tile_start;   // rows + 1: index of each row's first tile (exclusive scan of the tiles per row)
+    const uint32_t  *tile_row;     // the row of every tile
 };
 
 // ---------------------------------------------------------------- small helpers
@@ -668,16 +669,11 @@ void scan_kernel(Params P)
     uint32_t tr, tiles_in_row, first_tile;        // position in the carry chain of the row, its length, the row's first tile
     Run R;
     if constexpr (SEG) {
-        // Rows have their own numbers of tiles: tile_start is their exclusive scan, the grid is an upper bound.
-        // The row of this tile is the last one that starts at or before it.
+        // Rows have their own numbers of tiles: tile_start is their exclusive scan, tile_row its inverse; the grid
+        // is an upper bound on the number of tiles.
         const uint32_t *ts = P.tile_start;
         if (tile >= ts[P.rows]) return;
-        uint64_t lo = 0, hi = P.rows;             // ts[lo] <= tile < ts[hi]
-        while (hi - lo > 1) {
-            const uint64_t mid = (lo + hi) / 2;
-            if (ts[mid] <= tile) lo = mid; else hi = mid;
-        }
-        row = lo;
+        row = P.tile_row[tile];
         first_tile = ts[row];
         tiles_in_row = ts[row + 1] - first_tile;
         tr = tile - first_tile;
@@ -784,6 +780,22 @@ __global__ void seg_tiles_kernel(const long long *offsets, size_t rows, size_t t
         }
     }
     counts[r] = c;
+}
+
+// Segmented scans, step 3: the row of every tile -- the last row that starts at or before the tile (rows without
+// tiles share their start with the next row and are skipped by taking the last).  One thread per tile, a binary
+// search each; done here, where thousands of independent searches overlap, rather than at the head of every
+// workgroup of the scan, where the search would be pure latency.
+__global__ void seg_rows_kernel(const uint32_t *tile_start, size_t rows, uint32_t *tile_row, uint32_t max_tiles)
+{
+    const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= max_tiles || t >= tile_start[rows]) return;
+    size_t lo = 0, hi = rows;                     // tile_start[lo] <= t < tile_start[hi]
+    while (hi - lo > 1) {
+        const size_t mid = (lo + hi) / 2;
+        if (tile_start[mid] <= t) lo = mid; else hi = mid;
+    }
+    tile_row[t] = (uint32_t)lo;
 }
 
 __global__ void fill_zero_kernel(uint32_t *p, size_t words)
@@ -940,7 +952,7 @@ tcuscan_status_t run(const void *d_in, void *d_out, size_t rows, size_t cols, in
     P.tiles_per_row = (uint32_t)tpr; P.num_tiles = (uint32_t)(rows * tpr);
     P.ws = need ? (WsHeader *)d_ws : nullptr;
     P.reverse = reverse ? 1u : 0u;
-    P.offsets = nullptr; P.tile_start = nullptr;
+    P.offsets = nullptr; P.tile_start = nullptr; P.tile_row = nullptr;
     // Every call gets a fresh tag, so status words of earlier calls are stale by construction.  A call
     // recorded into a graph is replayed with the SAME tag; it therefore clears its status words first
     // (with a fill kernel, which a graph replays correctly).
@@ -966,28 +978,37 @@ tcuscan_status_t run(const void *d_in, void *d_out, size_t rows, size_t cols, in
 
 constexpr int kSegShortNT = 2;      // the short-segment tile: one wavefront, two MFMA tiles (128 granules)
 
-size_t seg_tile_elems(int dt, size_t rows, size_t total)
+// The tile a segmented scan uses is decided by the average row length (the only thing the host knows): one
+// wavefront per tile for short rows, the small workgroup tile, or the large one for very long rows.
+enum SegTile { kSegShort = 0, kSegSmall = 1, kSegLarge = 2 };
+
+int seg_tile_class(int dt, size_t rows, size_t total)
 {
-    // average row length decides: rows much longer than the one-wavefront tile take the small workgroup tile
-    const size_t gran = 16 / in_size(dt);
-    const size_t short_tile = (size_t)kSegShortNT * 64 * gran;
-    return (rows == 0 || total / rows >= 4 * short_tile) ? kSmallTile : short_tile;
+    const size_t short_tile = (size_t)kSegShortNT * 64 * (16 / in_size(dt));
+    const size_t avg = rows ? total / rows : total;
+    return avg < 4 * short_tile ? kSegShort : avg < ((size_t)1 << 19) ? kSegSmall : kSegLarge;
+}
+
+size_t seg_tile_elems(int dt, int cls)
+{
+    return cls == kSegShort ? (size_t)kSegShortNT * 64 * (16 / in_size(dt)) : cls == kSegSmall ? kSmallTile : tile_elems(dt, kTileLarge);
 }
 
 struct SegLayout {
     size_t max_tiles;        // upper bound on the number of tiles = grid size
-    size_t counts_off, starts_off, inner_off, inner_bytes, total_bytes;
+    size_t counts_off, starts_off, rowmap_off, inner_off, inner_bytes, total_bytes;
 };
 
 bool seg_layout(int dt, size_t rows, size_t total, SegLayout &L)
 {
-    const size_t tile = seg_tile_elems(dt, rows, total);
+    const size_t tile = seg_tile_elems(dt, seg_tile_class(dt, rows, total));
     L.max_tiles = total / tile + 2 * rows + 1;           // a row of len elements has at most len / tile + 2 tiles
     if (L.max_tiles > 0x7FFFFFFFull || rows + 1 > 0x7FFFFFFFull) return false;
     auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
     L.counts_off = up(sizeof(WsHeader) + 8 * kStatusStride * L.max_tiles);
     L.starts_off = up(L.counts_off + 4 * (rows + 1));
-    L.inner_off = up(L.starts_off + 4 * (rows + 1));
+    L.rowmap_off = up(L.starts_off + 4 * (rows + 1));
+    L.inner_off = up(L.rowmap_off + 4 * L.max_tiles);
     L.inner_bytes = tcuscan_workspace_bytes(1, rows + 1, TCUSCAN_I32_I32);
     L.total_bytes = L.inner_off + L.inner_bytes;
     return true;
@@ -999,12 +1020,14 @@ template <int DT, int NT, int W> const void *seg_kernel_for(bool excl, bool rev)
     return excl ? (const void *)scan_kernel<DT, NT, true, false, W, true> : (const void *)scan_kernel<DT, NT, false, false, W, true>;
 }
 
-template <int DT> hipError_t launch_seg(Params P, bool excl, bool big, hipStream_t s)
+template <int DT> hipError_t launch_seg(Params P, bool excl, int cls, hipStream_t s)
 {
     void *args[] = {&P};
     using Ti = Tiles<DT>;
-    if (big) return hipLaunchKernel(seg_kernel_for<DT, Ti::kSmall, Ti::wSmall>(excl, P.reverse != 0), dim3(P.num_tiles), dim3(64 * Ti::wSmall), args, 0, s);
-    return hipLaunchKernel(seg_kernel_for<DT, kSegShortNT, 1>(excl, P.reverse != 0), dim3(P.num_tiles), dim3(64), args, 0, s);
+    const bool rev = P.reverse != 0;
+    if (cls == kSegLarge) return hipLaunchKernel(seg_kernel_for<DT, Ti::kLarge, Ti::wLarge>(excl, rev), dim3(P.num_tiles), dim3(64 * Ti::wLarge), args, 0, s);
+    if (cls == kSegSmall) return hipLaunchKernel(seg_kernel_for<DT, Ti::kSmall, Ti::wSmall>(excl, rev), dim3(P.num_tiles), dim3(64 * Ti::wSmall), args, 0, s);
+    return hipLaunchKernel(seg_kernel_for<DT, kSegShortNT, 1>(excl, rev), dim3(P.num_tiles), dim3(64), args, 0, s);
 }
 
 tcuscan_status_t run_segmented(const void *d_in, void *d_out, const long long *d_offsets, size_t rows, size_t total, int dt,
@@ -1019,9 +1042,11 @@ tcuscan_status_t run_segmented(const void *d_in, void *d_out, const long long *d
     if (!seg_layout(dt, rows, total, L)) return TCUSCAN_ERR_UNSUPPORTED;
     if (!d_ws || ws_bytes < L.total_bytes || ((uintptr_t)d_ws % 8) != 0) return TCUSCAN_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
-    const size_t tile = seg_tile_elems(dt, rows, total);
+    const int cls = seg_tile_class(dt, rows, total);
+    const size_t tile = seg_tile_elems(dt, cls);
     int32_t *counts = (int32_t *)((char *)d_ws + L.counts_off);
     uint32_t *starts = (uint32_t *)((char *)d_ws + L.starts_off);
+    uint32_t *rowmap = (uint32_t *)((char *)d_ws + L.rowmap_off);
     {   // step 1: tiles per row
         const long long *off = d_offsets; size_t r = rows, t = total; uintptr_t in_addr = (uintptr_t)d_in;
         uint32_t esz = (uint32_t)in_size(dt), tl = (uint32_t)tile; WsHeader *h = (WsHeader *)d_ws;
@@ -1033,26 +1058,31 @@ tcuscan_status_t run_segmented(const void *d_in, void *d_out, const long long *d
     tcuscan_status_t st = run(counts, starts, 1, rows + 1, TCUSCAN_I32_I32, 1, 0, L.inner_bytes ? (char *)d_ws + L.inner_off : nullptr,
                               L.inner_bytes, stream);
     if (st != TCUSCAN_OK) return st;
-    // step 3: the scan itself; the grid is the upper bound on the number of tiles, surplus workgroups leave at once
+    {   // step 3: the row of every tile
+        const uint32_t *ts = starts; size_t r = rows; uint32_t mt = (uint32_t)L.max_tiles;
+        void *args[] = {&ts, &r, &rowmap, &mt};
+        if (hipLaunchKernel((const void *)seg_rows_kernel, dim3((unsigned)((L.max_tiles + 255) / 256)), dim3(256), args, 0, s) != hipSuccess)
+            return TCUSCAN_ERR_HIP;
+    }
+    // step 4: the scan itself; the grid is the upper bound on the number of tiles, surplus workgroups leave at once
     Params P;
     P.in = d_in; P.out = d_out; P.rows = rows; P.cols = 0;
     P.tiles_per_row = 0; P.num_tiles = (uint32_t)L.max_tiles;
     P.ws = (WsHeader *)d_ws;
     P.reverse = reverse ? 1u : 0u;
-    P.offsets = d_offsets; P.tile_start = starts;
+    P.offsets = d_offsets; P.tile_start = starts; P.tile_row = rowmap;
     P.tag = g_calls.fetch_add(1u, std::memory_order_relaxed) % kTagMod + 1u;
     hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
     if (hipStreamIsCapturing(s, &cs) != hipSuccess) { (void)hipGetLastError(); cs = hipStreamCaptureStatusNone; }
     if (cs == hipStreamCaptureStatusActive &&
         launch_fill((char *)d_ws + sizeof(WsHeader), 8 * kStatusStride * L.max_tiles, s) != hipSuccess) return TCUSCAN_ERR_HIP;
-    const bool big = tile == kSmallTile;
     hipError_t e;
     switch (dt) {
-    case TCUSCAN_I32_I32:  e = launch_seg<TCUSCAN_I32_I32>(P, exclusive != 0, big, s); break;
-    case TCUSCAN_F16_F32:  e = launch_seg<TCUSCAN_F16_F32>(P, exclusive != 0, big, s); break;
-    case TCUSCAN_I8_I32:   e = launch_seg<TCUSCAN_I8_I32>(P, exclusive != 0, big, s); break;
-    case TCUSCAN_F32_F32:  e = launch_seg<TCUSCAN_F32_F32>(P, exclusive != 0, big, s); break;
-    default:               e = launch_seg<TCUSCAN_BF16_F32>(P, exclusive != 0, big, s); break;
+    case TCUSCAN_I32_I32:  e = launch_seg<TCUSCAN_I32_I32>(P, exclusive != 0, cls, s); break;
+    case TCUSCAN_F16_F32:  e = launch_seg<TCUSCAN_F16_F32>(P, exclusive != 0, cls, s); break;
+    case TCUSCAN_I8_I32:   e = launch_seg<TCUSCAN_I8_I32>(P, exclusive != 0, cls, s); break;
+    case TCUSCAN_F32_F32:  e = launch_seg<TCUSCAN_F32_F32>(P, exclusive != 0, cls, s); break;
+    default:               e = launch_seg<TCUSCAN_BF16_F32>(P, exclusive != 0, cls, s); break;
     }
     return e == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
 }
