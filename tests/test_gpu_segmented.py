@@ -185,3 +185,47 @@ def test_refusals():
     with pytest.raises(tcuscan.TcuscanError) as e:
         tcuscan.segmented(t, t, None, 2, 64, "i32", ws=ws)
     assert e.value.code == tcuscan.ERR_INVALID_ARG
+
+
+def test_graph_capture_of_segmented_and_reverse_calls():
+    """All launches of a segmented call (tile counts, their scan, the tile-to-row map, the scan) and a reverse scan
+    are recorded into one graph; replays with new data and new offsets, with eager calls on the same workspaces in
+    between, must match the eager results (the recorded calls clear their status words with fill kernels)."""
+    import torch
+    rows, n = 3000, 1 << 20
+    kind = "i32"
+    ws = tcuscan.new_segmented_workspace(rows, n, kind)
+    wsr = tcuscan.new_workspace(1, n, kind)
+    d_in = torch.zeros(n, dtype=torch.int32, device="cuda")
+    d_off = torch.zeros(rows + 1, dtype=torch.int64, device="cuda")
+    d_seg = torch.empty(n, dtype=torch.int32, device="cuda")
+    d_rev = torch.empty(n, dtype=torch.int32, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                                             # warm-up outside capture
+        tcuscan.segmented(d_in, d_seg, d_off, rows, n, kind, ws=ws, stream=side)
+        tcuscan.scan(d_in, d_rev, 1, n, kind, flags=tcuscan.REVERSE, ws=wsr, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        tcuscan.segmented(d_in, d_seg, d_off, rows, n, kind, flags=tcuscan.EXCLUSIVE, ws=ws, stream=side)
+        tcuscan.scan(d_in, d_rev, 1, n, kind, flags=tcuscan.REVERSE, ws=wsr, stream=side)
+    eager = torch.empty_like(d_seg)
+    for rep in range(4):
+        rng = np.random.default_rng(50 + rep)
+        cuts = np.sort(rng.integers(0, n, size=rows - 1))
+        off = np.concatenate([[0], cuts, [n]]).astype(np.int64)
+        x = inputs.int32_full(n, 60 + rep)
+        d_in.copy_(torch.from_numpy(x).cuda())
+        d_off.copy_(torch.from_numpy(off).cuda())
+        d_seg.fill_(GUARD); d_rev.fill_(GUARD)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert oracle.compare_segments(x, kind, off, d_seg.cpu().numpy(), exclusive=True) == (0, -1)
+        assert oracle.compare_int_reverse(x, kind, d_rev.cpu().numpy()) == (0, -1)
+        tcuscan.segmented(d_in, eager, d_off, rows, n, kind, flags=tcuscan.REVERSE, ws=ws)   # eager, same workspace
+        torch.cuda.synchronize()
+        assert oracle.compare_segments(x, kind, off, eager.cpu().numpy(), reverse=True) == (0, -1)
+    assert tcuscan.workspace_fault(ws) == 0 and tcuscan.workspace_fault(wsr) == 0
