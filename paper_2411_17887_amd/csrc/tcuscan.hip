@@ -29,7 +29,10 @@
 //            to result rows so that each store instruction writes 1 KiB of consecutive outputs
 //            (partial lines per instruction measured 30 % slower).  No data pass through LDS.
 //
-// The C entry points at the bottom validate arguments on the host and launch this kernel.
+// Variants of the same kernel: reverse scans (suffix sums: upper triangular blocks, granules mirrored, the
+// chain runs from the end of the row) and segmented scans (rows of different lengths stored back to back: a
+// tile looks up its row in a map the host side builds with two small kernels and this library's own int32
+// scan).  The C entry points at the bottom validate arguments on the host and launch these kernels.
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -46,7 +49,7 @@ typedef _Float16     f16x8  __attribute__((ext_vector_type(8)));
 typedef __bf16       bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x4  __attribute__((ext_vector_type(4)));   // one 16-byte granule
 
-constexpr int kWaves   = 4;           // wavefronts per workgroup
+constexpr int kWaves   = 4;           // wavefronts per workgroup of the short-row kernel (one row each)
 constexpr int kThreads = 64 * kWaves;
 
 // Workspace header (256 bytes), followed by one 64-bit status word per tile, each word alone in a
