@@ -127,8 +127,9 @@ tcuscan_status_t tcuscan_scan(const void *d_in, void *d_out, size_t rows, size_t
  *   d_offsets  rows + 1 signed 64-bit element offsets on the DEVICE, non-decreasing, within [0, total]; 8-byte aligned
  *   total      number of elements d_in and d_out hold (an upper bound for d_offsets[rows]); sizes the launch
  *   d_ws       tcuscan_segmented_workspace_bytes(rows, total, dt) bytes, zero-filled once like every workspace here
- * Four launches are enqueued: tiles per row, their exclusive scan (this library's int32 scan), the row of every
- * tile, the scan itself.  The tile size follows the average row length total / rows.
+ * Four launches are enqueued: tiles per row, their exclusive scan (this library's int32 scan), one descriptor per
+ * tile (its row's extent and its place in the row), the scan itself.  The tile size follows the average row length
+ * total / rows.
  * Rows may start at any element: a row is tiled from the 16-byte boundary at or below its start, the few elements in
  * front of it are read as zero and not written.  Offsets that decrease or leave [0, total] are not followed: such
  * rows are skipped, the workspace's fault word is set to 2 (see tcuscan_workspace_fault) and the results of the call

@@ -76,11 +76,19 @@ struct Params {
     uint32_t    tag;         // this call's tag for the status words
     uint32_t    reverse;     // non-zero: suffix sums (every row is scanned from its end)
     WsHeader   *ws;          // null when tiles_per_row == 1
-    // segmented scans only: rows of different lengths stored back to back
-    const long long *offsets;      // rows + 1 element offsets
-    const uint32_t  *tile_start;   // rows + 1: index of each row's first tile (exclusive scan of the tiles per row)
-    const uint32_t  *tile_row;     // the row of every tile
+    // segmented scans only: what every tile has to know about its row (built by seg_desc_kernel)
+    const struct TileDesc *tile_desc;
 };
+
+// One per tile of a segmented scan (32 bytes, read with one scalar load).
+struct TileDesc {
+    long long off;                 // first element of the tile's row
+    unsigned long long len;        // length of the row
+    uint32_t first_tile;           // index of the row's first tile
+    uint32_t tiles_in_row;         // 0: no such tile (the grid is an upper bound)
+    uint32_t pad[2];
+};
+static_assert(sizeof(TileDesc) == 32, "descriptor size");
 
 // ---------------------------------------------------------------- small helpers
 
@@ -461,6 +469,7 @@ struct Run {
     char *out;               // first output byte of the run
     uint32_t rem;            // elements of the row from the start of the run on (saturated; 0 when the run starts past the end)
     uint32_t lead;           // segmented scans: elements at the start of the run that lie before the row (read as zero, not written)
+    uint32_t cap;            // segmented scans: elements from the start of the run to the end of the caller's array (saturated)
     bool in_vec, out_vec;    // run starts are 16-byte aligned
 };
 
@@ -477,6 +486,20 @@ template <int DT, int NT, bool REV> __device__ __forceinline__ uint32_t slot_off
 }
 
 // a1: coalesced 128-bit loads, zero-filled past the end of the row (BatchMatMul's zero-pad)
+// Keep bytes [lo, hi) of a granule, zero the rest.
+__device__ __forceinline__ u32x4 keep_bytes(u32x4 v, int lo, int hi)
+{
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        int a = lo - 4 * w, b = hi - 4 * w;
+        a = a < 0 ? 0 : (a > 4 ? 4 : a);
+        b = b < 0 ? 0 : (b > 4 ? 4 : b);
+        const uint32_t m = b > a ? (uint32_t)((((1ull << (8 * b)) - 1) >> (8 * a)) << (8 * a)) : 0u;
+        v[w] &= m;
+    }
+    return v;
+}
+
 template <int DT, int NT, bool REV, bool SEG = false>
 __device__ __forceinline__ void load_run(const Run &R, int lane, u32x4 (&g)[NT])
 {
@@ -487,6 +510,15 @@ __device__ __forceinline__ void load_run(const Run &R, int lane, u32x4 (&g)[NT])
         const uint32_t e0 = slot_offset<DT, NT, REV>(t, lane);                            // element offset inside the run
         if (R.in_vec && e0 + kG <= R.rem && (!SEG || e0 >= R.lead)) {
             g[t] = *(const u32x4 *)(R.in + e0 * T::kEsz);
+        } else if (SEG && R.in_vec && e0 + kG <= R.cap) {
+            // Segmented scans: a granule that straddles a row boundary still lies inside the caller's array; it is
+            // loaded whole and the neighbouring row's elements are masked out (rows are short there, and an element-wise
+            // load of every boundary granule costs more instructions than the rest of the tile).
+            g[t] = u32x4{0u, 0u, 0u, 0u};
+            if (e0 < R.rem && e0 + kG > R.lead) {
+                const int lo = e0 >= R.lead ? 0 : (int)(R.lead - e0), hi = e0 + kG <= R.rem ? kG : (int)(R.rem - e0);
+                g[t] = keep_bytes(*(const u32x4 *)(R.in + e0 * T::kEsz), lo * T::kEsz, hi * T::kEsz);
+            }
         } else {
             uint32_t w[4] = {0u, 0u, 0u, 0u};
             for (int i = 0; i < kG; ++i) {
@@ -605,6 +637,7 @@ __device__ __forceinline__ Run make_run(const Params &P, uint64_t row, uint64_t 
     const uint64_t left = base < P.cols ? P.cols - base : 0;
     R.rem = left < 0x40000000ull ? (uint32_t)left : 0x40000000u;
     R.lead = 0;
+    R.cap = R.rem;
     R.in_vec = (((uintptr_t)R.in) & 15) == 0;
     R.out_vec = (((uintptr_t)R.out) & 15) == 0;
     return R;
@@ -631,8 +664,12 @@ __device__ __forceinline__ Run make_seg_run(const Params &P, long long off, uint
     const uint64_t left = base < vlen ? vlen - base : 0;
     R.rem = left < 0x40000000ull ? (uint32_t)left : 0x40000000u;
     R.lead = base < lead ? lead - (uint32_t)base : 0;
-    R.in_vec = (((uintptr_t)R.in) & 15) == 0;
-    R.out_vec = (((uintptr_t)R.out) & 15) == 0;
+    const long long to_end = (long long)P.cols - first;                   // P.cols holds the number of elements of the arrays
+    R.cap = to_end <= 0 ? 0u : to_end < 0x40000000ll ? (uint32_t)to_end : 0x40000000u;
+    // (first < 0: a row that starts within the first granule of an array that is itself not 16-byte aligned; the
+    // aligned address below it lies before the array, so that run goes element by element)
+    R.in_vec = first >= 0 && (((uintptr_t)R.in) & 15) == 0;
+    R.out_vec = first >= 0 && (((uintptr_t)R.out) & 15) == 0;
     return R;
 }
 
@@ -645,12 +682,16 @@ template <> struct MinWaves<TCUSCAN_I8_I32, 8>    { static constexpr int value =
 template <> struct MinWaves<TCUSCAN_F16_F32, 16>  { static constexpr int value = 4; };
 template <> struct MinWaves<TCUSCAN_BF16_F32, 16> { static constexpr int value = 4; };
 
-template <int DT, int NT, bool EXCL, bool REV, int W, bool SEG = false>
-__global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(MinWaves<DT, NT>::value)))
+// PACK > 1 (one-wavefront tiles only): a workgroup is PACK independent tiles, one per wavefront -- nothing is shared,
+// no barrier is executed; it only makes the grid PACK times smaller (the segmented scan of short rows launches an
+// upper bound on the number of tiles, and workgroups that find nothing to do still cost a dispatch each).
+template <int DT, int NT, bool EXCL, bool REV, int W, bool SEG = false, int PACK = 1>
+__global__ __launch_bounds__(64 * W * PACK) __attribute__((amdgpu_waves_per_eu(MinWaves<DT, NT>::value)))
 void scan_kernel(Params P)
 {
     using T = Tr<DT>;
     using A = typename T::acc;
+    static_assert(PACK == 1 || W == 1, "only one-wavefront tiles are packed");
     constexpr uint32_t kEPW = NT * Geo<DT>::kTileElems;   // elements per wavefront
     constexpr uint32_t kWgElems = kEPW * W;               // elements per workgroup tile (W wavefronts)
 
@@ -658,7 +699,8 @@ void scan_kernel(Params P)
     __shared__ uint32_t s_bcast;
 
     const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // wave-uniform: keeps tile bookkeeping in SGPRs
+    const int wave_in_wg = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // wave-uniform: keeps tile bookkeeping in SGPRs
+    const int wave = PACK == 1 ? wave_in_wg : 0;          // position inside the tile
 
     // ---- which tile.  Tiles are taken in workgroup-index order: a tile only ever waits for tiles with
     // a smaller index, which the hardware dispatched earlier (or at the same time), so the lowest
@@ -666,22 +708,24 @@ void scan_kernel(Params P)
     // guarantee the same without that assumption, but one contended atomic per tile caps the whole
     // kernel at the device's single-address atomic rate.)  Status words carry the call's tag, so
     // words left over from earlier calls read as "not published yet" and need no clearing.
-    const uint32_t tile = blockIdx.x;
+    const uint32_t tile = PACK == 1 ? blockIdx.x : blockIdx.x * PACK + wave_in_wg;
     const uint32_t tag = P.tag;
     uint64_t row;
     uint32_t tr, tiles_in_row, first_tile;        // position in the carry chain of the row, its length, the row's first tile
     Run R;
     if constexpr (SEG) {
-        // Rows have their own numbers of tiles: tile_start is their exclusive scan, tile_row its inverse; the grid
-        // is an upper bound on the number of tiles.
-        const uint32_t *ts = P.tile_start;
-        if (tile >= ts[P.rows]) return;
-        row = P.tile_row[tile];
-        first_tile = ts[row];
-        tiles_in_row = ts[row + 1] - first_tile;
+        // Rows have their own numbers of tiles; the grid is an upper bound on their sum.  Everything a tile needs to
+        // know about its row was put into one descriptor per tile beforehand: looked up here, it would be a chain of
+        // four dependent loads at the head of every workgroup.
+        if (tile >= P.num_tiles) return;
+        const TileDesc d = P.tile_desc[tile];
+        if (d.tiles_in_row == 0) return;
+        row = 0;
+        first_tile = d.first_tile;
+        tiles_in_row = d.tiles_in_row;
         tr = tile - first_tile;
-        const long long off = P.offsets[row];
-        const uint64_t len = (uint64_t)(P.offsets[row + 1] - off);
+        const long long off = d.off;
+        const uint64_t len = d.len;
         const uint32_t pos = REV ? tiles_in_row - 1 - tr : tr;
         R = make_seg_run<DT>(P, off, len, seg_lead<DT>(P, off), (uint64_t)pos * kWgElems + (uint64_t)wave * kEPW);
     } else {
@@ -702,14 +746,17 @@ void scan_kernel(Params P)
     const A wave_total = reduce_run<DT, NT>(lane, Aop, g);
 
     // ---- level 2: wavefront totals through LDS
-    if (lane == 0) s_wave_total[wave] = acc_bits(wave_total);
-    __syncthreads();
-    A wave_off = acc_from_bits<A>(0u), wg_total = acc_from_bits<A>(0u);
+    A wave_off = acc_from_bits<A>(0u), wg_total = wave_total;
+    if constexpr (W > 1) {
+        if (lane == 0) s_wave_total[wave] = acc_bits(wave_total);
+        __syncthreads();
+        wg_total = acc_from_bits<A>(0u);
 #pragma unroll
-    for (int w = 0; w < W; ++w) {
-        const A v = acc_from_bits<A>(s_wave_total[w]);
-        if (REV ? w > wave : w < wave) wave_off = acc_add(wave_off, v);    // the wavefronts scanned before this one
-        wg_total = acc_add(wg_total, v);
+        for (int w = 0; w < W; ++w) {
+            const A v = acc_from_bits<A>(s_wave_total[w]);
+            if (REV ? w > wave : w < wave) wave_off = acc_add(wave_off, v);    // the wavefronts scanned before this one
+            wg_total = acc_add(wg_total, v);
+        }
     }
 
     // ---- a4: carry chain between workgroup tiles of the same row
@@ -730,10 +777,12 @@ void scan_kernel(Params P)
                     __hip_atomic_store(row_status + (size_t)tr * kStatusStride, status_word(tag, kStatePrefix, acc_bits(acc_add(prefix, wg_total))),
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-            if (lane == 0) s_bcast = acc_bits(prefix);
+            if (W > 1 && lane == 0) s_bcast = acc_bits(prefix);
         }
-        __syncthreads();
-        prefix = acc_from_bits<A>(s_bcast);
+        if constexpr (W > 1) {                    // (a one-wavefront tile has the prefix in every lane already)
+            __syncthreads();
+            prefix = acc_from_bits<A>(s_bcast);
+        }
     }
 
     // ---- local scans, down-sweep add and store, with everything before this wavefront's run as carry
@@ -785,20 +834,27 @@ __global__ void seg_tiles_kernel(const long long *offsets, size_t rows, size_t t
     counts[r] = c;
 }
 
-// Segmented scans, step 3: the row of every tile -- the last row that starts at or before the tile (rows without
-// tiles share their start with the next row and are skipped by taking the last).  One thread per tile, a binary
-// search each; done here, where thousands of independent searches overlap, rather than at the head of every
-// workgroup of the scan, where the search would be pure latency.
-__global__ void seg_rows_kernel(const uint32_t *tile_start, size_t rows, uint32_t *tile_row, uint32_t max_tiles)
+// Segmented scans, step 3: one descriptor per tile of the launch.  The row of a tile is the last row that starts at
+// or before it (rows without tiles share their start with the next row and are skipped by taking the last): a binary
+// search per tile, done here, where thousands of independent searches overlap, rather than at the head of every
+// workgroup of the scan, where it would be pure latency.  Tiles beyond the real total get an empty descriptor.
+__global__ void seg_desc_kernel(const uint32_t *tile_start, const long long *offsets, size_t rows, TileDesc *desc, uint32_t max_tiles)
 {
     const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= max_tiles || t >= tile_start[rows]) return;
-    size_t lo = 0, hi = rows;                     // tile_start[lo] <= t < tile_start[hi]
-    while (hi - lo > 1) {
-        const size_t mid = (lo + hi) / 2;
-        if (tile_start[mid] <= t) lo = mid; else hi = mid;
+    if (t >= max_tiles) return;
+    TileDesc d = {0, 0ull, 0u, 0u, {0u, 0u}};
+    if (t < tile_start[rows]) {
+        size_t lo = 0, hi = rows;                 // tile_start[lo] <= t < tile_start[hi]
+        while (hi - lo > 1) {
+            const size_t mid = (lo + hi) / 2;
+            if (tile_start[mid] <= t) lo = mid; else hi = mid;
+        }
+        d.off = offsets[lo];
+        d.len = (unsigned long long)(offsets[lo + 1] - d.off);
+        d.first_tile = tile_start[lo];
+        d.tiles_in_row = tile_start[lo + 1] - d.first_tile;
     }
-    tile_row[t] = (uint32_t)lo;
+    desc[t] = d;
 }
 
 __global__ void fill_zero_kernel(uint32_t *p, size_t words)
@@ -956,7 +1012,7 @@ tcuscan_status_t run(const void *d_in, void *d_out, size_t rows, size_t cols, in
     P.tiles_per_row = (uint32_t)tpr; P.num_tiles = (uint32_t)(rows * tpr);
     P.ws = need ? (WsHeader *)d_ws : nullptr;
     P.reverse = reverse ? 1u : 0u;
-    P.offsets = nullptr; P.tile_start = nullptr; P.tile_row = nullptr;
+    P.tile_desc = nullptr;
     // Every call gets a fresh tag, so status words of earlier calls are stale by construction.  A call
     // recorded into a graph is replayed with the SAME tag; it therefore clears its status words first
     // (with a fill kernel, which a graph replays correctly).
@@ -981,6 +1037,7 @@ tcuscan_status_t run(const void *d_in, void *d_out, size_t rows, size_t cols, in
 // ---- segmented scans (rows of different lengths, stored back to back)
 
 constexpr int kSegShortNT = 2;      // the short-segment tile: one wavefront, two MFMA tiles (128 granules)
+constexpr int kSegPack = 4;         // ... four of them to a workgroup
 
 // The tile a segmented scan uses is decided by the average row length (the only thing the host knows): one
 // wavefront per tile for short rows, the small workgroup tile, or the large one for very long rows.
@@ -1012,16 +1069,16 @@ bool seg_layout(int dt, size_t rows, size_t total, SegLayout &L)
     L.counts_off = up(sizeof(WsHeader) + 8 * kStatusStride * L.max_tiles);
     L.starts_off = up(L.counts_off + 4 * (rows + 1));
     L.rowmap_off = up(L.starts_off + 4 * (rows + 1));
-    L.inner_off = up(L.rowmap_off + 4 * L.max_tiles);
+    L.inner_off = up(L.rowmap_off + sizeof(TileDesc) * L.max_tiles);
     L.inner_bytes = tcuscan_workspace_bytes(1, rows + 1, TCUSCAN_I32_I32);
     L.total_bytes = L.inner_off + L.inner_bytes;
     return true;
 }
 
-template <int DT, int NT, int W> const void *seg_kernel_for(bool excl, bool rev)
+template <int DT, int NT, int W, int PACK> const void *seg_kernel_for(bool excl, bool rev)
 {
-    if (rev) return excl ? (const void *)scan_kernel<DT, NT, true, true, W, true> : (const void *)scan_kernel<DT, NT, false, true, W, true>;
-    return excl ? (const void *)scan_kernel<DT, NT, true, false, W, true> : (const void *)scan_kernel<DT, NT, false, false, W, true>;
+    if (rev) return excl ? (const void *)scan_kernel<DT, NT, true, true, W, true, PACK> : (const void *)scan_kernel<DT, NT, false, true, W, true, PACK>;
+    return excl ? (const void *)scan_kernel<DT, NT, true, false, W, true, PACK> : (const void *)scan_kernel<DT, NT, false, false, W, true, PACK>;
 }
 
 template <int DT> hipError_t launch_seg(Params P, bool excl, int cls, hipStream_t s)
@@ -1029,9 +1086,9 @@ template <int DT> hipError_t launch_seg(Params P, bool excl, int cls, hipStream_
     void *args[] = {&P};
     using Ti = Tiles<DT>;
     const bool rev = P.reverse != 0;
-    if (cls == kSegLarge) return hipLaunchKernel(seg_kernel_for<DT, Ti::kLarge, Ti::wLarge>(excl, rev), dim3(P.num_tiles), dim3(64 * Ti::wLarge), args, 0, s);
-    if (cls == kSegSmall) return hipLaunchKernel(seg_kernel_for<DT, Ti::kSmall, Ti::wSmall>(excl, rev), dim3(P.num_tiles), dim3(64 * Ti::wSmall), args, 0, s);
-    return hipLaunchKernel(seg_kernel_for<DT, kSegShortNT, 1>(excl, rev), dim3(P.num_tiles), dim3(64), args, 0, s);
+    if (cls == kSegLarge) return hipLaunchKernel(seg_kernel_for<DT, Ti::kLarge, Ti::wLarge, 1>(excl, rev), dim3(P.num_tiles), dim3(64 * Ti::wLarge), args, 0, s);
+    if (cls == kSegSmall) return hipLaunchKernel(seg_kernel_for<DT, Ti::kSmall, Ti::wSmall, 1>(excl, rev), dim3(P.num_tiles), dim3(64 * Ti::wSmall), args, 0, s);
+    return hipLaunchKernel(seg_kernel_for<DT, kSegShortNT, 1, kSegPack>(excl, rev), dim3((P.num_tiles + kSegPack - 1) / kSegPack), dim3(64 * kSegPack), args, 0, s);
 }
 
 tcuscan_status_t run_segmented(const void *d_in, void *d_out, const long long *d_offsets, size_t rows, size_t total, int dt,
@@ -1050,7 +1107,7 @@ tcuscan_status_t run_segmented(const void *d_in, void *d_out, const long long *d
     const size_t tile = seg_tile_elems(dt, cls);
     int32_t *counts = (int32_t *)((char *)d_ws + L.counts_off);
     uint32_t *starts = (uint32_t *)((char *)d_ws + L.starts_off);
-    uint32_t *rowmap = (uint32_t *)((char *)d_ws + L.rowmap_off);
+    TileDesc *desc = (TileDesc *)((char *)d_ws + L.rowmap_off);
     {   // step 1: tiles per row
         const long long *off = d_offsets; size_t r = rows, t = total; uintptr_t in_addr = (uintptr_t)d_in;
         uint32_t esz = (uint32_t)in_size(dt), tl = (uint32_t)tile; WsHeader *h = (WsHeader *)d_ws;
@@ -1062,19 +1119,19 @@ tcuscan_status_t run_segmented(const void *d_in, void *d_out, const long long *d
     tcuscan_status_t st = run(counts, starts, 1, rows + 1, TCUSCAN_I32_I32, 1, 0, L.inner_bytes ? (char *)d_ws + L.inner_off : nullptr,
                               L.inner_bytes, stream);
     if (st != TCUSCAN_OK) return st;
-    {   // step 3: the row of every tile
-        const uint32_t *ts = starts; size_t r = rows; uint32_t mt = (uint32_t)L.max_tiles;
-        void *args[] = {&ts, &r, &rowmap, &mt};
-        if (hipLaunchKernel((const void *)seg_rows_kernel, dim3((unsigned)((L.max_tiles + 255) / 256)), dim3(256), args, 0, s) != hipSuccess)
+    {   // step 3: one descriptor per tile
+        const uint32_t *ts = starts; const long long *off = d_offsets; size_t r = rows; uint32_t mt = (uint32_t)L.max_tiles;
+        void *args[] = {&ts, &off, &r, &desc, &mt};
+        if (hipLaunchKernel((const void *)seg_desc_kernel, dim3((unsigned)((L.max_tiles + 255) / 256)), dim3(256), args, 0, s) != hipSuccess)
             return TCUSCAN_ERR_HIP;
     }
     // step 4: the scan itself; the grid is the upper bound on the number of tiles, surplus workgroups leave at once
     Params P;
-    P.in = d_in; P.out = d_out; P.rows = rows; P.cols = 0;
+    P.in = d_in; P.out = d_out; P.rows = rows; P.cols = total;          // cols: the length of the arrays (no access beyond it)
     P.tiles_per_row = 0; P.num_tiles = (uint32_t)L.max_tiles;
     P.ws = (WsHeader *)d_ws;
     P.reverse = reverse ? 1u : 0u;
-    P.offsets = d_offsets; P.tile_start = starts; P.tile_row = rowmap;
+    P.tile_desc = desc;
     P.tag = g_calls.fetch_add(1u, std::memory_order_relaxed) % kTagMod + 1u;
     hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
     if (hipStreamIsCapturing(s, &cs) != hipSuccess) { (void)hipGetLastError(); cs = hipStreamCaptureStatusNone; }
