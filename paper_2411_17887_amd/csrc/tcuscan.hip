@@ -682,16 +682,12 @@ template <> struct MinWaves<TCUSCAN_I8_I32, 8>    { static constexpr int value =
 template <> struct MinWaves<TCUSCAN_F16_F32, 16>  { static constexpr int value = 4; };
 template <> struct MinWaves<TCUSCAN_BF16_F32, 16> { static constexpr int value = 4; };
 
-// PACK > 1 (one-wavefront tiles only): a workgroup is PACK independent tiles, one per wavefront -- nothing is shared,
-// no barrier is executed; it only makes the grid PACK times smaller (the segmented scan of short rows launches an
-// upper bound on the number of tiles, and workgroups that find nothing to do still cost a dispatch each).
-template <int DT, int NT, bool EXCL, bool REV, int W, bool SEG = false, int PACK = 1>
-__global__ __launch_bounds__(64 * W * PACK) __attribute__((amdgpu_waves_per_eu(MinWaves<DT, NT>::value)))
+template <int DT, int NT, bool EXCL, bool REV, int W, bool SEG = false>
+__global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(MinWaves<DT, NT>::value)))
 void scan_kernel(Params P)
 {
     using T = Tr<DT>;
     using A = typename T::acc;
-    static_assert(PACK == 1 || W == 1, "only one-wavefront tiles are packed");
     constexpr uint32_t kEPW = NT * Geo<DT>::kTileElems;   // elements per wavefront
     constexpr uint32_t kWgElems = kEPW * W;               // elements per workgroup tile (W wavefronts)
 
@@ -699,8 +695,7 @@ void scan_kernel(Params P)
     __shared__ uint32_t s_bcast;
 
     const int lane = threadIdx.x & 63;
-    const int wave_in_wg = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // wave-uniform: keeps tile bookkeeping in SGPRs
-    const int wave = PACK == 1 ? wave_in_wg : 0;          // position inside the tile
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // wave-uniform: keeps tile bookkeeping in SGPRs
 
     // ---- which tile.  Tiles are taken in workgroup-index order: a tile only ever waits for tiles with
     // a smaller index, which the hardware dispatched earlier (or at the same time), so the lowest
@@ -708,7 +703,7 @@ void scan_kernel(Params P)
     // guarantee the same without that assumption, but one contended atomic per tile caps the whole
     // kernel at the device's single-address atomic rate.)  Status words carry the call's tag, so
     // words left over from earlier calls read as "not published yet" and need no clearing.
-    const uint32_t tile = PACK == 1 ? blockIdx.x : blockIdx.x * PACK + wave_in_wg;
+    const uint32_t tile = blockIdx.x;
     const uint32_t tag = P.tag;
     uint64_t row;
     uint32_t tr, tiles_in_row, first_tile;        // position in the carry chain of the row, its length, the row's first tile
@@ -787,6 +782,82 @@ void scan_kernel(Params P)
 
     // ---- local scans, down-sweep add and store, with everything before this wavefront's run as carry
     scan_and_store<DT, NT, EXCL, REV, SEG>(lane, Aop, R, g, acc_add(prefix, wave_off));
+}
+
+// ------------------------------------------------------------- segmented scans, short rows
+//
+// Rows of a few hundred elements: a tile is one wavefront's run of kSegShortNT MFMA tiles, a wavefront takes
+// kSegUnroll consecutive tiles and a workgroup is kSegPack such wavefronts that share nothing (no LDS, no barrier).
+// A wavefront moves little data per tile, and descriptor -> loads -> products -> stores is a chain of waits, so
+// the descriptors and loads of all its tiles are issued before anything is waited for; packing makes the grid smaller
+// (it is an upper bound, and a workgroup that finds nothing to do still costs a dispatch).  Rows longer than a tile
+// are chained through status words like everywhere else; a wavefront finishes its tiles in order, so a tile still
+// waits only for tiles that were started no later than itself.
+constexpr int kSegShortNT = 2;
+constexpr int kSegUnroll = 2;
+constexpr int kSegPack = 4;
+
+template <int DT, bool EXCL, bool REV>
+__global__ __launch_bounds__(64 * kSegPack) void seg_short_kernel(Params P)
+{
+    using T = Tr<DT>;
+    using A = typename T::acc;
+    constexpr int NT = kSegShortNT, U = kSegUnroll;
+    constexpr uint32_t kTile = NT * Geo<DT>::kTileElems;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const uint32_t tile0 = (blockIdx.x * kSegPack + (uint32_t)wave) * U;
+
+    TileDesc d[U];
+    bool live[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        live[u] = tile0 + u < P.num_tiles;
+        if (live[u]) d[u] = P.tile_desc[tile0 + u];
+        live[u] = live[u] && d[u].tiles_in_row != 0;
+    }
+    if (!live[0]) return;                             // tiles without a row are the last ones of the grid
+
+    Run R[U];
+    u32x4 g[U][NT];
+    uint32_t tr[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (!live[u]) continue;
+        tr[u] = tile0 + u - d[u].first_tile;
+        const uint32_t pos = REV ? d[u].tiles_in_row - 1 - tr[u] : tr[u];
+        R[u] = make_seg_run<DT>(P, d[u].off, d[u].len, seg_lead<DT>(P, d[u].off), (uint64_t)pos * kTile);
+        load_run<DT, NT, REV, true>(R[u], lane, g[u]);
+    }
+    const typename T::AConst Aop = T::make(lane, EXCL, REV);
+
+    // totals first, for all tiles: whoever waits for them is not held up by this wavefront's own look-back
+    A total[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (!live[u]) continue;
+        total[u] = reduce_run<DT, NT>(lane, Aop, g[u]);
+        if (d[u].tiles_in_row > 1 && lane == 0) {
+            uint64_t *row_status = (uint64_t *)(P.ws + 1) + (uint64_t)d[u].first_tile * kStatusStride;
+            __hip_atomic_store(row_status + (size_t)tr[u] * kStatusStride,
+                               status_word(P.tag, tr[u] == 0 ? kStatePrefix : kStateAggregate, acc_bits(total[u])),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (!live[u]) continue;
+        A prefix = acc_from_bits<A>(0u);
+        if (d[u].tiles_in_row > 1 && tr[u] != 0) {
+            uint64_t *row_status = (uint64_t *)(P.ws + 1) + (uint64_t)d[u].first_tile * kStatusStride;
+            prefix = look_back<A>(row_status, (int)tr[u], P.tag, P.ws);
+            if (lane == 0)
+                __hip_atomic_store(row_status + (size_t)tr[u] * kStatusStride,
+                                   status_word(P.tag, kStatePrefix, acc_bits(acc_add(prefix, total[u]))),
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        scan_and_store<DT, NT, EXCL, REV, true>(lane, Aop, R[u], g[u], prefix);
+    }
 }
 
 // ---------------------------------------------------------------------- short-row kernel
@@ -1036,8 +1107,6 @@ tcuscan_status_t run(const void *d_in, void *d_out, size_t rows, size_t cols, in
 
 // ---- segmented scans (rows of different lengths, stored back to back)
 
-constexpr int kSegShortNT = 2;      // the short-segment tile: one wavefront, two MFMA tiles (128 granules)
-constexpr int kSegPack = 4;         // ... four of them to a workgroup
 
 // The tile a segmented scan uses is decided by the average row length (the only thing the host knows): one
 // wavefront per tile for short rows, the small workgroup tile, or the large one for very long rows.
@@ -1075,10 +1144,15 @@ bool seg_layout(int dt, size_t rows, size_t total, SegLayout &L)
     return true;
 }
 
-template <int DT, int NT, int W, int PACK> const void *seg_kernel_for(bool excl, bool rev)
+template <int DT, int NT, int W> const void *seg_kernel_for(bool excl, bool rev)
 {
-    if (rev) return excl ? (const void *)scan_kernel<DT, NT, true, true, W, true, PACK> : (const void *)scan_kernel<DT, NT, false, true, W, true, PACK>;
-    return excl ? (const void *)scan_kernel<DT, NT, true, false, W, true, PACK> : (const void *)scan_kernel<DT, NT, false, false, W, true, PACK>;
+    if (rev) return excl ? (const void *)scan_kernel<DT, NT, true, true, W, true> : (const void *)scan_kernel<DT, NT, false, true, W, true>;
+    return excl ? (const void *)scan_kernel<DT, NT, true, false, W, true> : (const void *)scan_kernel<DT, NT, false, false, W, true>;
+}
+template <int DT> const void *seg_short_kernel_for(bool excl, bool rev)
+{
+    if (rev) return excl ? (const void *)seg_short_kernel<DT, true, true> : (const void *)seg_short_kernel<DT, false, true>;
+    return excl ? (const void *)seg_short_kernel<DT, true, false> : (const void *)seg_short_kernel<DT, false, false>;
 }
 
 template <int DT> hipError_t launch_seg(Params P, bool excl, int cls, hipStream_t s)
@@ -1086,9 +1160,10 @@ template <int DT> hipError_t launch_seg(Params P, bool excl, int cls, hipStream_
     void *args[] = {&P};
     using Ti = Tiles<DT>;
     const bool rev = P.reverse != 0;
-    if (cls == kSegLarge) return hipLaunchKernel(seg_kernel_for<DT, Ti::kLarge, Ti::wLarge, 1>(excl, rev), dim3(P.num_tiles), dim3(64 * Ti::wLarge), args, 0, s);
-    if (cls == kSegSmall) return hipLaunchKernel(seg_kernel_for<DT, Ti::kSmall, Ti::wSmall, 1>(excl, rev), dim3(P.num_tiles), dim3(64 * Ti::wSmall), args, 0, s);
-    return hipLaunchKernel(seg_kernel_for<DT, kSegShortNT, 1, kSegPack>(excl, rev), dim3((P.num_tiles + kSegPack - 1) / kSegPack), dim3(64 * kSegPack), args, 0, s);
+    if (cls == kSegLarge) return hipLaunchKernel(seg_kernel_for<DT, Ti::kLarge, Ti::wLarge>(excl, rev), dim3(P.num_tiles), dim3(64 * Ti::wLarge), args, 0, s);
+    if (cls == kSegSmall) return hipLaunchKernel(seg_kernel_for<DT, Ti::kSmall, Ti::wSmall>(excl, rev), dim3(P.num_tiles), dim3(64 * Ti::wSmall), args, 0, s);
+    constexpr unsigned per_wg = kSegPack * kSegUnroll;
+    return hipLaunchKernel(seg_short_kernel_for<DT>(excl, rev), dim3((P.num_tiles + per_wg - 1) / per_wg), dim3(64 * kSegPack), args, 0, s);
 }
 
 tcuscan_status_t run_segmented(const void *d_in, void *d_out, const long long *d_offsets, size_t rows, size_t total, int dt,
