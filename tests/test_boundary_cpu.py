@@ -99,3 +99,30 @@ def test_binding_raises_with_the_status_text():
             def element_size(self): return 4
         tcuscan.inclusive(T(), T(), "f32", stream=0)
     assert e.value.code == tcuscan.ERR_INVALID_ARG and "invalid argument" in str(e.value)
+
+
+def test_new_entry_points_reject_bad_arguments_on_the_host():
+    """tcuscan_scan (flags), tcuscan_segmented and the radix executor: everything the host can refuse, it refuses
+    before a launch (these calls return without touching the fake pointers)."""
+    # unknown flag bits; empty shapes are fine whatever the flags
+    assert call("tcuscan_scan", FAKE, FAKE + (1 << 30), 1, 10, tcuscan.F32_F32, 4, 0, 0, 0) == tcuscan.ERR_INVALID_ARG
+    assert call("tcuscan_scan", 0, 0, 0, 10, tcuscan.F32_F32, 3, 0, 0, 0) == tcuscan.OK
+    assert call("tcuscan_scan", FAKE, 0, 1, 10, tcuscan.F32_F32, 2, 0, 0, 0) == tcuscan.ERR_INVALID_ARG
+    # segmented: sizing is monotone in both arguments, zero for nothing to do, and the call checks its arguments
+    assert tcuscan.segmented_workspace_bytes(0, 100, "f32") == 0 and tcuscan.segmented_workspace_bytes(5, 0, "f32") == 0
+    assert tcuscan.segmented_workspace_bytes(5, 100, 9) == 0
+    a = tcuscan.segmented_workspace_bytes(10, 1000, "i8")
+    assert 0 < a <= tcuscan.segmented_workspace_bytes(20, 1000, "i8") <= tcuscan.segmented_workspace_bytes(20, 100000, "i8")
+    assert call("tcuscan_segmented", 0, 0, 0, 0, 100, tcuscan.F32_F32, 0, 0, 0, 0) == tcuscan.OK          # no rows
+    assert call("tcuscan_segmented", FAKE, FAKE + (1 << 30), 0, 2, 100, tcuscan.F32_F32, 0, FAKE, 1 << 20, 0) == tcuscan.ERR_INVALID_ARG
+    assert call("tcuscan_segmented", FAKE, FAKE + (1 << 30), FAKE + 4, 2, 100, tcuscan.F32_F32, 0, FAKE, 1 << 20, 0) == tcuscan.ERR_INVALID_ARG
+    assert call("tcuscan_segmented", FAKE, FAKE + (1 << 30), FAKE, 2, 100, tcuscan.F32_F32, 8, FAKE, 1 << 20, 0) == tcuscan.ERR_INVALID_ARG
+    assert call("tcuscan_segmented", FAKE, FAKE + (1 << 30), FAKE, 2, 100, tcuscan.F32_F32, 0, 0, 0, 0) == tcuscan.ERR_WORKSPACE
+    need = tcuscan.segmented_workspace_bytes(2, 100, "f32")
+    assert call("tcuscan_segmented", FAKE, FAKE + (1 << 30), FAKE, 2, 100, tcuscan.F32_F32, 0, FAKE, need - 1, 0) == tcuscan.ERR_WORKSPACE
+    assert call("tcuscan_segmented", FAKE, FAKE, FAKE, 2, 100, tcuscan.F16_F32, 0, FAKE, need, 0) == tcuscan.ERR_INVALID_ARG   # in place, 16-bit
+    assert call("tcuscan_segmented", FAKE, FAKE + (1 << 30), FAKE, 2, 100, 7, 0, FAKE, need, 0) == tcuscan.ERR_UNSUPPORTED
+    # radix executor: only s = 4, 16, 32 and n = s^k
+    for s, n in [(2, 16), (8, 64), (4, 5), (32, 1000), (16, 0)]:
+        assert call("tcuscan_matmulscan_levels_radix", FAKE, FAKE + (1 << 30), n, tcuscan.I32_I32, s, -1, 0, 0) == tcuscan.ERR_UNSUPPORTED
+    assert call("tcuscan_matmulscan_levels_radix", 0, FAKE, 16, tcuscan.I32_I32, 4, -1, 0, 0) == tcuscan.ERR_INVALID_ARG
