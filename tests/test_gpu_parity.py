@@ -383,3 +383,29 @@ def test_random_shapes_dtypes_and_offsets(tile_policy):
             x = TRI_GEN[kind](n, case)
             got = run_scan(x, kind, call, rows=rows, cols=cols, in_offset=in_off, out_offset=out_off)
             check(x, kind, got, exclusive=ex, rows=rows, cols=cols, exact_float=True)
+
+
+def test_more_than_2_to_the_31_elements():
+    """Element indices beyond 31 and 32 bits: n = 2^32 + 2^31 + 12345 int8 {0,1} values (6 GiB in, 24 GiB out on the
+    device), checked on sampled windows -- the first and last 2^24 elements and one window across 2^32 -- whose
+    carries-in come from a popcount of everything before the window (exact, no scan involved)."""
+    import torch
+    n = (1 << 32) + (1 << 31) + 12345
+    g = torch.Generator(device="cuda").manual_seed(1234)
+    d_in = torch.randint(0, 2, (n,), dtype=torch.int8, device="cuda", generator=g)
+    d_out = torch.empty(n, dtype=torch.int32, device="cuda")
+    ws = tcuscan.new_workspace(1, n, "i8")
+    tcuscan.exclusive(d_in, d_out, "i8", ws=ws, n=n)
+    torch.cuda.synchronize()
+    assert tcuscan.workspace_fault(ws) == 0
+    w = 1 << 24
+    for start in (0, (1 << 32) - w // 2, n - w):
+        # carry into the window: number of ones before it, counted in int64 chunks (a reduction, not a scan)
+        before = 0
+        for a in range(0, start, 1 << 30):
+            before += int(d_in[a:min(a + (1 << 30), start)].sum(dtype=torch.int64).item())
+        x = d_in[start:start + w].cpu().numpy()
+        got = d_out[start:start + w].cpu().numpy()
+        want = oracle.scan_int64(x, "i8", exclusive=True) + before
+        assert np.array_equal(got.astype(np.int64) & 0xFFFFFFFF, want & 0xFFFFFFFF), f"window at {start}"
+    del d_in, d_out

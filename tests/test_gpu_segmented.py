@@ -229,3 +229,35 @@ def test_graph_capture_of_segmented_and_reverse_calls():
         torch.cuda.synchronize()
         assert oracle.compare_segments(x, kind, off, eager.cpu().numpy(), reverse=True) == (0, -1)
     assert tcuscan.workspace_fault(ws) == 0 and tcuscan.workspace_fault(wsr) == 0
+
+
+def test_offsets_beyond_32_bits():
+    """Three rows in 2^32 + 100000 int8 elements: row starts beyond 2^31 and 2^32.  Checked on windows at the row
+    starts and ends; the carry into a window is a popcount of the row's elements before it."""
+    import torch
+    n = (1 << 32) + 100_000
+    off = np.array([0, (1 << 31) + 5, (1 << 32) + 77, n], np.int64)
+    g = torch.Generator(device="cuda").manual_seed(4321)
+    d_in = torch.randint(0, 2, (n,), dtype=torch.int8, device="cuda", generator=g)
+    d_out = torch.empty(n, dtype=torch.int32, device="cuda")
+    d_off = torch.from_numpy(off).cuda()
+    ws = tcuscan.new_segmented_workspace(3, n, "i8")
+    tcuscan.segmented(d_in, d_out, d_off, 3, n, "i8", ws=ws)
+    torch.cuda.synchronize()
+    assert tcuscan.workspace_fault(ws) == 0
+    w = 1 << 22
+
+    def ones_between(a, b):
+        s = 0
+        for c in range(a, b, 1 << 30):
+            s += int(d_in[c:min(c + (1 << 30), b)].sum(dtype=torch.int64).item())
+        return s
+
+    for r in range(3):
+        a, b = int(off[r]), int(off[r + 1])
+        for start in (a, max(a, b - w)):
+            stop = min(start + w, b)
+            x = d_in[start:stop].cpu().numpy()
+            got = d_out[start:stop].cpu().numpy().astype(np.int64)
+            want = oracle.scan_int64(x, "i8") + ones_between(a, start)
+            assert np.array_equal(got, want), f"row {r}, window at {start}"
