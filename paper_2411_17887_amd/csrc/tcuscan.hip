@@ -58,7 +58,7 @@ constexpr int kThreads = 64 * kWaves;
 // of the whole kernel's run time).
 constexpr size_t kStatusStride = 8;    // in 64-bit words
 struct WsHeader {
-    uint32_t fault;    // sticky: a look-back wait hit its spin bound
+    uint32_t fault;    // sticky: 1 = a look-back wait hit its spin bound, 2 = a segmented scan was given bad offsets
     uint32_t pad[63];
 };
 static_assert(sizeof(WsHeader) == 256, "header size");
@@ -71,7 +71,7 @@ constexpr uint32_t kSpinLimit      = 1u << 24;   // look-back polls before givin
 struct Params {
     const void *in;
     void       *out;
-    uint64_t    rows, cols;
+    uint64_t    rows, cols;  // segmented scans: cols = number of elements of the arrays
     uint32_t    tiles_per_row, num_tiles;
     uint32_t    tag;         // this call's tag for the status words
     uint32_t    reverse;     // non-zero: suffix sums (every row is scanned from its end)
