@@ -231,6 +231,11 @@ def measure_apps(steps: int):
     nbytes = 5 * n + 9 * n + 4 * kept
     res = {"compaction": {"workload": "n=2^28 int8 {0,1} mask, 32-bit values", "ms": ms, "gelems_per_s": n / (ms * 1e-3) / 1e9,
                           "kept": kept, "algorithmic_GBps": nbytes / (ms * 1e-3) / 1e9}}
+    # the same without a positions buffer: the scatter is fused into the scan kernel (mask n + values 4n read, 4 * kept written)
+    ms_f = timed(lambda: tcuscan.compact_u32(vals, mask, out, None, count=cnt, ws=ws), steps)
+    res["compaction_fused"] = {"workload": "n=2^28 int8 {0,1} mask, 32-bit values, no positions buffer (one kernel)", "ms": ms_f,
+                               "gelems_per_s": n / (ms_f * 1e-3) / 1e9, "kept": int(cnt.item()),
+                               "algorithmic_GBps": (5 * n + 4 * kept) / (ms_f * 1e-3) / 1e9}
     del vals, out, pos, mask
     torch.cuda.empty_cache()
     m = 1 << 26

@@ -199,7 +199,9 @@ tcuscan_status_t tcuscan_matmulscan_levels_radix(const void *d_in, void *d_out, 
  *
  * Stream compaction: d_out receives, in order, the 32-bit d_values[i] whose d_mask[i] (int8) is non-zero
  * (mask entries must be 0 or 1).
- *   d_positions  scratch, n int32: on return the exclusive scan of the mask (the destination indices)
+ *   d_positions  n int32: on return the exclusive scan of the mask (the destination indices), or NULL: then the
+ *                positions are not materialised and the scatter is fused into the scan (one pass over mask and
+ *                values, one kernel)
  *   d_count      optional device word: number of kept elements
  */
 tcuscan_status_t tcuscan_compact_u32(const void *d_values, const void *d_mask, void *d_out, size_t n,

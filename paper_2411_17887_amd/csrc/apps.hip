@@ -6,6 +6,7 @@
 // library's int8 -> int32 MFMA scan; the kernels here only build the mask and move the elements.
 //
 //   compaction : pos = exclusive_scan(mask);  out[pos[i]] = values[i] where mask[i] != 0
+//                (without a positions buffer the scatter is fused into the scan kernel: tcuscan.hip, compact_store)
 //   split(b)   : f[i] = (bit b of key[i] == 0);  pos = exclusive_scan(f);  Z = pos[n-1] + f[n-1]
 //                key i goes to  pos[i]            if f[i]      (zeros keep their order, in front)
 //                          to  Z + (i - pos[i])   otherwise   (ones keep their order, behind)
@@ -15,6 +16,9 @@
 #include <stdint.h>
 
 #include "../../include/tcuscan.h"
+
+extern "C" tcuscan_status_t tcuscan_internal_compact_fused(const void *d_values, const void *d_mask, void *d_out, size_t n, unsigned *d_count,
+                                                           void *d_ws, size_t ws_bytes, tcuscan_stream_t stream);   // tcuscan.hip
 
 namespace {
 
@@ -94,7 +98,11 @@ tcuscan_status_t tcuscan_compact_u32(const void *d_values, const void *d_mask, v
 {
     if (n == 0) return TCUSCAN_OK;
     if (n > 0xFFFFFFFFull) return TCUSCAN_ERR_UNSUPPORTED;                       // positions are 32-bit
-    if (!d_values || !d_mask || !d_out || !d_positions) return TCUSCAN_ERR_INVALID_ARG;
+    if (!d_values || !d_mask || !d_out) return TCUSCAN_ERR_INVALID_ARG;
+    if (!d_positions) {                                                          // nobody wants the positions: one fused pass
+        if (((uintptr_t)d_values % 4) || ((uintptr_t)d_out % 4) || ((uintptr_t)d_count % 4)) return TCUSCAN_ERR_INVALID_ARG;
+        return tcuscan_internal_compact_fused(d_values, d_mask, d_out, n, d_count, d_ws, ws_bytes, stream);
+    }
     if (((uintptr_t)d_values % 4) || ((uintptr_t)d_out % 4) || ((uintptr_t)d_positions % 4) || ((uintptr_t)d_count % 4))
         return TCUSCAN_ERR_INVALID_ARG;
     tcuscan_status_t st = tcuscan_exclusive(d_mask, d_positions, n, TCUSCAN_I8_I32, d_ws, ws_bytes, stream);

@@ -13,21 +13,24 @@ def keys_u32(n, seed):
     return inputs.int32_full(n, seed).view(np.uint32)
 
 
-def gpu_compact(v, m):
+def gpu_compact(v, m, fused=False, offset=0):
+    """fused: no positions buffer, the scatter happens inside the scan kernel.  offset: shift the value / mask pointers
+    by that many elements (pointers that are not 16-byte aligned)."""
     import torch
     n = v.size
-    d_v = torch.from_numpy(v.view(np.int32)).cuda()
-    d_m = torch.from_numpy(m).cuda()
+    d_v = torch.from_numpy(np.concatenate([np.zeros(offset, np.int32), v.view(np.int32)])).cuda()[offset:]
+    d_m = torch.from_numpy(np.concatenate([np.zeros(offset, np.int8), m])).cuda()[offset:]
     d_out = torch.full((n + 2,), -5, dtype=torch.int32, device="cuda")
-    d_pos = torch.empty(n, dtype=torch.int32, device="cuda")
-    d_cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    d_pos = None if fused else torch.empty(n, dtype=torch.int32, device="cuda")
+    d_cnt = torch.full((1,), -1, dtype=torch.int32, device="cuda")
     ws = tcuscan.new_workspace(1, n, "i8")
     tcuscan.compact_u32(d_v, d_m, d_out, d_pos, count=d_cnt, ws=ws)
     torch.cuda.synchronize()
+    assert ws is None or tcuscan.workspace_fault(ws) == 0
     cnt = int(d_cnt.item())
     out = d_out.cpu().numpy()
     assert np.all(out[cnt:] == -5)                      # nothing written past the kept elements
-    return out[:cnt].view(np.uint32), d_pos.cpu().numpy(), cnt
+    return out[:cnt].view(np.uint32), (None if fused else d_pos.cpu().numpy()), cnt
 
 
 @pytest.mark.parametrize("n", [1, 15, 4097, 8192 * 3 + 5, (1 << 22) + 9, 1 << 26])
@@ -41,6 +44,35 @@ def test_compaction(n):
     for mm in (np.zeros(min(n, 100000), np.int8), np.ones(min(n, 100000), np.int8)):
         g, _, c = gpu_compact(v[: mm.size], mm)
         assert c == int(mm.sum()) and np.array_equal(g, v[: mm.size][mm != 0])
+
+
+@pytest.mark.parametrize("n", [1, 3, 15, 16, 17, 255, 257, 4097, 8191, 8192, 8193, 8192 * 3 + 5, 65536 * 5 + 77, (1 << 22) + 9, 1 << 26,
+                               (1 << 28) + 3])
+def test_fused_compaction_without_a_positions_buffer(n):
+    v, m = keys_u32(n, n + 7), inputs.mask_i8(n, n + 8)
+    got, _, cnt = gpu_compact(v, m, fused=True)
+    ref = apps.compact(v, m)[0] if n <= (1 << 22) + 9 else v[m != 0]
+    assert cnt == ref.size and np.array_equal(got, ref)
+    if n <= (1 << 22) + 9:
+        for off in (1, 3):                                  # unaligned values and mask
+            g, _, c = gpu_compact(v, m, fused=True, offset=off)
+            assert c == ref.size and np.array_equal(g, ref)
+        for mm in (np.zeros(n, np.int8), np.ones(n, np.int8)):
+            g, _, c = gpu_compact(v, mm, fused=True)
+            assert c == int(mm.sum()) and np.array_equal(g, v[mm != 0])
+
+
+def test_fused_compaction_every_tile_size():
+    try:
+        for policy in (1, 2, 3):
+            tcuscan.set_tile_policy(policy)
+            n = 7 * 65536 + 4321
+            v, m = keys_u32(n, 90 + policy), inputs.mask_i8(n, 91 + policy)
+            got, _, cnt = gpu_compact(v, m, fused=True)
+            ref = apps.compact(v, m)[0]
+            assert cnt == ref.size and np.array_equal(got, ref)
+    finally:
+        tcuscan.set_tile_policy(tcuscan.TILE_AUTO)
 
 
 def gpu_sort(k, vals=None, bits=32):
