@@ -247,10 +247,21 @@ def measure_apps(steps: int):
     def sort_once():
         keys.copy_(keys0)
         tcuscan.split_radix_sort_u32(keys, tmp, flags, p2, bits=32, ws=ws2)
+    def is_sorted():
+        k = keys.view(torch.int32).to(torch.int64) & 0xFFFFFFFF
+        return bool((k[1:] >= k[:-1]).all().item())
+
     ms2 = timed(sort_once, max(2, steps // 2))
-    ok = bool((keys[1:].view(torch.int32).to(torch.int64) & 0xFFFFFFFF >= keys[:-1].view(torch.int32).to(torch.int64) & 0xFFFFFFFF).all().item())
-    res["split_radix_sort"] = {"workload": "n=2^26 random 32-bit keys, 32 split passes (one mask scan each), includes one 256 MiB copy per run",
-                               "ms": ms2, "mkeys_per_s": m / (ms2 * 1e-3) / 1e6, "sorted": ok}
+    res["split_radix_sort"] = {"workload": "n=2^26 random 32-bit keys, 32 fused split passes (mask from the keys, MFMA scan, scatter: one "
+                                           "kernel each), includes one 256 MiB copy per run",
+                               "ms": ms2, "mkeys_per_s": m / (ms2 * 1e-3) / 1e6, "sorted": is_sorted()}
+    tcuscan.set_sort_fusion(False)
+    try:
+        ms3 = timed(sort_once, max(2, steps // 2))
+        res["split_radix_sort_three_kernels"] = {"workload": "the same with mask kernel + tcuscan_exclusive + scatter kernel per pass",
+                                                 "ms": ms3, "mkeys_per_s": m / (ms3 * 1e-3) / 1e6, "sorted": is_sorted()}
+    finally:
+        tcuscan.set_sort_fusion(True)
     return res
 
 

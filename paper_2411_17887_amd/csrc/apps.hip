@@ -19,6 +19,10 @@
 
 extern "C" tcuscan_status_t tcuscan_internal_compact_fused(const void *d_values, const void *d_mask, void *d_out, size_t n, unsigned *d_count,
                                                            void *d_ws, size_t ws_bytes, tcuscan_stream_t stream);   // tcuscan.hip
+extern "C" tcuscan_status_t tcuscan_internal_bit_zero_counts(const void *d_keys, size_t n, unsigned *d_counts32, tcuscan_stream_t stream);
+extern "C" tcuscan_status_t tcuscan_internal_split_pass(const void *d_keys, const void *d_vals, void *d_keys_out, void *d_vals_out, size_t n,
+                                                        int bit, const unsigned *d_zeros_total, void *d_ws, size_t ws_bytes,
+                                                        tcuscan_stream_t stream);
 
 namespace {
 
@@ -88,6 +92,8 @@ __global__ __launch_bounds__(kThreads) void copy_u32_kernel(const uint32_t *__re
 
 unsigned blocks_for(size_t items) { return (unsigned)((items + kThreads - 1) / kThreads); }
 
+bool g_force_unfused_sort = false;      // measurement / test knob, see tcuscan_set_sort_fusion
+
 }  // namespace
 
 extern "C" {
@@ -131,7 +137,23 @@ tcuscan_status_t tcuscan_split_radix_sort_u32(void *d_keys, void *d_vals, size_t
     uint32_t *src_v = (uint32_t *)d_vals, *dst_v = (uint32_t *)d_vals_tmp;
     int8_t *flags = (int8_t *)d_flags;
     int32_t *pos = (int32_t *)d_positions;
-    for (int bit = 0; bit < bits; ++bit) {
+    // Fused passes (the default): the mask and the positions are never written; the split kernel builds the mask from
+    // the keys, scans it and scatters in one go.  The number of keys with a 0 in each bit is taken once, up front (it
+    // does not change when the keys are permuted), into the first 32 words of d_positions.  The unfused form below
+    // (mask kernel, tcuscan_exclusive, scatter kernel) remains for n < 32 and as the plain statement of the reduction.
+    const bool fused = n >= 32 && !g_force_unfused_sort;
+    if (fused) {
+        unsigned *counts = (unsigned *)d_positions;
+        tcuscan_status_t st = tcuscan_internal_bit_zero_counts(d_keys, n, counts, stream);
+        if (st != TCUSCAN_OK) return st;
+        for (int bit = 0; bit < bits; ++bit) {
+            st = tcuscan_internal_split_pass(src_k, src_v, dst_k, dst_v, n, bit, counts + bit, d_ws, ws_bytes, stream);
+            if (st != TCUSCAN_OK) return st;
+            uint32_t *t = src_k; src_k = dst_k; dst_k = t;
+            t = src_v; src_v = dst_v; dst_v = t;
+        }
+    }
+    for (int bit = 0; !fused && bit < bits; ++bit) {
         {
             const uint32_t *k = src_k; void *args[] = {&k, &flags, &n, &bit};
             if (hipLaunchKernel((const void *)bit_is_zero_kernel, dim3(blocks_for((n + 15) / 16)), dim3(kThreads), args, 0, s) != hipSuccess)
@@ -162,3 +184,9 @@ tcuscan_status_t tcuscan_split_radix_sort_u32(void *d_keys, void *d_vals, size_t
 }
 
 }  // extern "C"
+
+extern "C" tcuscan_status_t tcuscan_set_sort_fusion(int fused)
+{
+    g_force_unfused_sort = fused == 0;
+    return TCUSCAN_OK;
+}

@@ -857,6 +857,179 @@ void scan_kernel(Params P)
     }
 }
 
+// ------------------------------------------------------------- fused split (one pass of the radix sort)
+//
+// Blelloch's split on bit b: keys whose bit is 0 go to the front, the others behind them, both in their old order.
+// The mask "bit b is 0" is never written: a lane builds the 16 mask bytes of its granule from 16 keys it loads, the
+// scan runs as in the fused compaction (2 * zeros before + own flag in one product), and the keys -- loaded again, 16
+// bytes per lane where its results are -- are ordered per result block in an LDS slot (zeros first, then ones) and
+// written as two consecutive ranges.  The number of zeros of the whole array, which the ones' destinations need, does
+// not depend on the order of the keys: all 32 counts are taken once, before the first pass.
+
+__global__ __launch_bounds__(256) void bit_zero_counts_kernel(const uint32_t *__restrict__ keys, size_t n, uint32_t *counts)
+{
+    __shared__ uint32_t s_cnt[32];
+    if (threadIdx.x < 32) s_cnt[threadIdx.x] = 0u;
+    __syncthreads();
+    uint32_t cnt[32];
+#pragma unroll
+    for (int b = 0; b < 32; ++b) cnt[b] = 0u;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+        const uint32_t z = ~keys[i];
+#pragma unroll
+        for (int b = 0; b < 32; ++b) cnt[b] += (z >> b) & 1u;
+    }
+#pragma unroll
+    for (int b = 0; b < 32; ++b) {
+        const uint32_t w = wave_sum(cnt[b]);
+        if ((threadIdx.x & 63) == 0 && w) atomicAdd(&s_cnt[b], w);
+    }
+    __syncthreads();
+    if (threadIdx.x < 32 && s_cnt[threadIdx.x]) atomicAdd(&counts[threadIdx.x], s_cnt[threadIdx.x]);
+}
+
+struct SplitArgs {
+    const uint32_t *keys, *vals;       // vals may be null
+    uint32_t *keys_out, *vals_out;
+    const uint32_t *zeros_total;       // number of keys whose bit is 0
+    int bit;
+};
+
+template <int NT, int W>
+__global__ __launch_bounds__(64 * W) void split_kernel(Params P, SplitArgs S)
+{
+    constexpr int DT = TCUSCAN_I8_I32;
+    using T = Tr<DT>;
+    constexpr uint32_t kEPW = NT * Geo<DT>::kTileElems;
+    constexpr uint32_t kWgElems = kEPW * W;
+    __shared__ uint32_t s_wave_total[W];
+    __shared__ uint32_t s_bcast;
+    __shared__ uint32_t s_pack[W][kPackSlot];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const uint32_t tile = blockIdx.x, tag = P.tag;
+    const uint64_t n = P.cols;
+    const uint64_t base = (uint64_t)tile * kWgElems + (uint64_t)wave * kEPW;        // first key of this wavefront's run
+    const uint32_t rem = base < n ? (n - base < 0x40000000ull ? (uint32_t)(n - base) : 0x40000000u) : 0u;
+    const uint32_t *kin = S.keys + base;
+    const bool vec = (((uintptr_t)kin) & 15) == 0;
+    const int bit = S.bit;
+
+    // ---- the mask granules: lane l covers keys 16 l .. 16 l + 15 of every MFMA tile (4 loads of 16 bytes)
+    u32x4 g[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t e0 = (uint32_t)t * 1024u + 16u * lane + 4u * k;
+            u32x4 x = {~0u, ~0u, ~0u, ~0u};                                         // keys past the end: flag 0
+            if (vec && e0 + 4 <= rem) {
+                x = *(const u32x4 *)(kin + e0);
+            } else {
+                for (int i = 0; i < 4; ++i)
+                    if (e0 + i < rem) x[i] = kin[e0 + i];
+            }
+            uint32_t w = 0;
+            for (int i = 0; i < 4; ++i) w |= (((x[i] >> bit) & 1u) ^ 1u) << (8 * i);
+            if (e0 + 4 > rem)                                                        // ragged tail: only real keys count
+                for (int i = 0; i < 4; ++i)
+                    if (e0 + i >= rem) w &= ~(0xFFu << (8 * i));
+            g[t][k] = w;
+        }
+    }
+    const typename T::AConst Aop = T::make_compact(lane);
+    const uint32_t wave_total = reduce_run<DT, NT>(lane, Aop, g);
+    if (lane == 0) s_wave_total[wave] = wave_total;
+    __syncthreads();
+    uint32_t wave_off = 0u, wg_total = 0u;
+#pragma unroll
+    for (int w = 0; w < W; ++w) {
+        const uint32_t v = s_wave_total[w];
+        if (w < wave) wave_off += v;
+        wg_total += v;
+    }
+    uint32_t prefix = 0u;
+    if (P.num_tiles > 1) {
+        uint64_t *row_status = (uint64_t *)(P.ws + 1);
+        if (wave == 0) {
+            if (tile == 0) {
+                if (lane == 0)
+                    __hip_atomic_store(row_status, status_word(tag, kStatePrefix, wg_total), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+                if (lane == 0)
+                    __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStateAggregate, wg_total),
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                prefix = look_back<uint32_t>(row_status, (int)tile, tag, P.ws);
+                if (lane == 0)
+                    __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStatePrefix, prefix + wg_total),
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            if (lane == 0) s_bcast = prefix;
+        }
+        __syncthreads();
+        prefix = s_bcast;
+    }
+
+    // ---- destinations and scatter, one result block (256 keys) at a time
+    const uint32_t zeros_total = *S.zeros_total;
+    uint32_t carry = prefix + wave_off;                         // zeros before the block
+    uint32_t *slot = s_pack[wave];
+    const int c = lane & 15, q = lane >> 4;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        i32x4 d[T::kBlocks];
+        T::mma(Aop, g[t], lane, true, false, d);               // 2 * zeros before + own flag
+        const u32x4 tt = bits<u32x4>(T::totals(Aop, g[t]));
+#pragma unroll
+        for (int p = 0; p < T::kBlocks; ++p) {
+            const uint32_t ex = row_exclusive_scan(tt[p]);
+            const uint32_t zeros = uniform_from_lane(ex + tt[p], 15);               // zeros in this block
+            const uint32_t b0 = (uint32_t)t * 1024u + 256u * p;                      // first key of the block, run-relative
+            const uint32_t valid = b0 < rem ? (rem - b0 < 256u ? rem - b0 : 256u) : 0u;
+            const uint32_t in_blk = 16u * c + 4u * q;                                // this lane's four keys inside the block
+            const uint32_t e0 = b0 + in_blk;
+            const uint64_t ones_before = base + b0 - carry;                          // ones before the block, in the whole array
+            uint32_t at[4];
+            for (int r = 0; r < 4; ++r) {
+                const uint32_t w = (uint32_t)d[p][r], zb = ex + (w >> 1);
+                at[r] = (w & 1u) ? zb : zeros + (in_blk + r - zb);                   // zeros first, then ones, both in order
+                if (e0 + r >= rem || at[r] >= (uint32_t)kPackSlot) at[r] = ~0u;
+            }
+            for (int pass = 0; pass < 2; ++pass) {
+                const uint32_t *src = pass == 0 ? S.keys : S.vals;
+                uint32_t *dst = pass == 0 ? S.keys_out : S.vals_out;
+                if (!src) break;
+                if (valid) {
+                    u32x4 x = {0u, 0u, 0u, 0u};
+                    const uint32_t *sp = src + base;
+                    if ((((uintptr_t)sp) & 15) == 0 && e0 + 4 <= rem) {
+                        x = *(const u32x4 *)(sp + e0);
+                    } else {
+                        for (int r = 0; r < 4; ++r)
+                            if (e0 + r < rem) x[r] = sp[e0 + r];
+                    }
+                    for (int r = 0; r < 4; ++r)
+                        if (at[r] != ~0u) slot[at[r]] = x[r];
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+                for (int k = 0; k < kPackSlot / 64; ++k) {
+                    const uint32_t i = 64u * k + lane;
+                    if (i < zeros) dst[carry + i] = slot[i];
+                    else if (i < valid) dst[(uint64_t)zeros_total + ones_before + (i - zeros)] = slot[i];
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            }
+            carry += zeros;
+        }
+    }
+}
+
 // ------------------------------------------------------------- segmented scans, short rows
 //
 // Rows of a few hundred elements: a tile is one wavefront's run of kSegShortNT MFMA tiles, a wavefront takes
@@ -1305,6 +1478,49 @@ template <int NT, int W> hipError_t launch_compact(Params P, hipStream_t s)
 }
 
 }  // namespace
+
+// Used by tcuscan_split_radix_sort_u32 (apps.hip): the zero counts of all 32 bits, and one fused split pass.
+extern "C" __attribute__((visibility("hidden")))
+tcuscan_status_t tcuscan_internal_bit_zero_counts(const void *d_keys, size_t n, unsigned *d_counts32, tcuscan_stream_t stream)
+{
+    hipStream_t s = (hipStream_t)stream;
+    if (launch_fill(d_counts32, 32 * sizeof(unsigned), s) != hipSuccess) return TCUSCAN_ERR_HIP;
+    const uint32_t *k = (const uint32_t *)d_keys; uint32_t *c = d_counts32;
+    void *args[] = {&k, &n, &c};
+    const unsigned grid = (unsigned)((n + 255) / 256 < 2048 ? (n + 255) / 256 : 2048);
+    return hipLaunchKernel((const void *)bit_zero_counts_kernel, dim3(grid), dim3(256), args, 0, s) == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
+}
+
+extern "C" __attribute__((visibility("hidden")))
+tcuscan_status_t tcuscan_internal_split_pass(const void *d_keys, const void *d_vals, void *d_keys_out, void *d_vals_out, size_t n, int bit,
+                                             const unsigned *d_zeros_total, void *d_ws, size_t ws_bytes, tcuscan_stream_t stream)
+{
+    constexpr int NT = 8, W = 4;                                   // 32768 keys per workgroup
+    const size_t tile = (size_t)NT * W * 1024;
+    const size_t tiles = (n + tile - 1) / tile;
+    if (tiles > 0x7FFFFFFFull) return TCUSCAN_ERR_UNSUPPORTED;
+    const size_t need = tiles > 1 ? sizeof(WsHeader) + 8 * kStatusStride * tiles : 0;
+    if (need && (!d_ws || ws_bytes < need || ((uintptr_t)d_ws % 8) != 0)) return TCUSCAN_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    Params P;
+    P.in = d_keys; P.out = d_keys_out; P.rows = 1; P.cols = n;
+    P.tiles_per_row = (uint32_t)tiles; P.num_tiles = (uint32_t)tiles;
+    P.ws = need ? (WsHeader *)d_ws : nullptr;
+    P.reverse = 0; P.tile_desc = nullptr; P.packed = nullptr; P.count = nullptr;
+    P.tag = g_calls.fetch_add(1u, std::memory_order_relaxed) % kTagMod + 1u;
+    if (need) {
+        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(s, &cs) != hipSuccess) { (void)hipGetLastError(); cs = hipStreamCaptureStatusNone; }
+        if (cs == hipStreamCaptureStatusActive &&
+            launch_fill((char *)d_ws + sizeof(WsHeader), 8 * kStatusStride * tiles, s) != hipSuccess) return TCUSCAN_ERR_HIP;
+    }
+    SplitArgs S;
+    S.keys = (const uint32_t *)d_keys; S.vals = (const uint32_t *)d_vals;
+    S.keys_out = (uint32_t *)d_keys_out; S.vals_out = (uint32_t *)d_vals_out;
+    S.zeros_total = d_zeros_total; S.bit = bit;
+    void *args[] = {&P, &S};
+    return hipLaunchKernel((const void *)split_kernel<NT, W>, dim3((unsigned)tiles), dim3(64 * W), args, 0, s) == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
+}
 
 // Used by tcuscan_compact_u32 (apps.hip) when the caller does not ask for the positions: one pass over the mask
 // and the values, nothing else written than the kept values.  Not part of the public interface.

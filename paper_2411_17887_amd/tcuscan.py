@@ -20,7 +20,7 @@ EXPORTS = ["tcuscan_workspace_bytes", "tcuscan_workspace_init", "tcuscan_inclusi
            "tcuscan_batched", "tcuscan_scan", "tcuscan_segmented_workspace_bytes", "tcuscan_segmented", "tcuscan_tile_elems", "tcuscan_large_tile_elems", "tcuscan_huge_tile_elems",
            "tcuscan_set_tile_policy",
            "tcuscan_workspace_fault", "tcuscan_matmulscan_levels", "tcuscan_matmulscan_levels_radix", "tcuscan_compact_u32",
-           "tcuscan_split_radix_sort_u32", "tcuscan_status_string"]
+           "tcuscan_split_radix_sort_u32", "tcuscan_set_sort_fusion", "tcuscan_status_string"]
 
 _lib = None
 
@@ -53,6 +53,8 @@ def load() -> ctypes.CDLL:
         L.tcuscan_huge_tile_elems.restype = sz
         L.tcuscan_set_tile_policy.argtypes = [ci]
         L.tcuscan_set_tile_policy.restype = ci
+        L.tcuscan_set_sort_fusion.argtypes = [ci]
+        L.tcuscan_set_sort_fusion.restype = ci
         L.tcuscan_workspace_init.argtypes = [vp, sz, vp]
         L.tcuscan_inclusive.argtypes = [vp, vp, sz, ci, vp, sz, vp]
         L.tcuscan_exclusive.argtypes = [vp, vp, sz, ci, vp, sz, vp]
@@ -207,6 +209,10 @@ def compact_u32(values, mask, out, positions, count=None, ws=None, stream=None) 
                                     *_ws_args(ws), _stream(stream))
     if rc != OK:
         raise TcuscanError(rc, "tcuscan_compact_u32")
+
+
+def set_sort_fusion(fused: bool) -> None:
+    load().tcuscan_set_sort_fusion(int(bool(fused)))
 
 
 def split_radix_sort_u32(keys, keys_tmp, flags, positions, vals=None, vals_tmp=None, bits: int = 32, ws=None, stream=None) -> None:

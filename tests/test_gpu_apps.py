@@ -90,15 +90,29 @@ def gpu_sort(k, vals=None, bits=32):
     return d_k.cpu().numpy().view(np.uint32), (d_v.cpu().numpy().view(np.uint32) if vals is not None else None)
 
 
-@pytest.mark.parametrize("n", [1, 2, 17, 1000, 8192 * 5 + 3, (1 << 20) + 1])
-def test_sort_full_keys(n):
+@pytest.fixture(params=[True, False], ids=["fused", "three_kernels"])
+def sort_form(request):
+    """Both forms of a split pass: the fused kernel (default) and mask kernel + scan + scatter kernel."""
+    tcuscan.set_sort_fusion(request.param)
+    yield request.param
+    tcuscan.set_sort_fusion(True)
+
+
+@pytest.mark.parametrize("n", [1, 2, 17, 31, 32, 33, 255, 257, 1000, 8192 * 5 + 3, 32768, 32769, 5 * 32768 - 1, (1 << 20) + 1])
+def test_sort_full_keys(n, sort_form):
     k = keys_u32(n, 2 * n + 1)
     got, _ = gpu_sort(k)
     ref, _ = apps.split_radix_sort(k) if n <= 50000 else (np.sort(k), None)
     assert np.array_equal(got, ref)
 
 
-def test_sort_is_stable_and_moves_payloads():
+def test_sort_large_and_unaligned(sort_form):
+    k = keys_u32((1 << 24) + 12345, 99)
+    got, _ = gpu_sort(k, bits=32)
+    assert np.array_equal(got, np.sort(k))
+
+
+def test_sort_is_stable_and_moves_payloads(sort_form):
     n = 300007
     k = keys_u32(n, 5) & np.uint32(0x3FF)
     payload = np.arange(n, dtype=np.uint32)
@@ -111,7 +125,7 @@ def test_sort_is_stable_and_moves_payloads():
     assert np.array_equal(gk, k[order]) and np.array_equal(gv, payload[order])
 
 
-def test_sort_special_inputs():
+def test_sort_special_inputs(sort_form):
     n = 70001
     for k in (np.arange(n, dtype=np.uint32), np.arange(n, dtype=np.uint32)[::-1].copy(), np.full(n, 0xDEADBEEF, np.uint32),
               np.where(np.arange(n) % 2 == 0, np.uint32(0xFFFFFFFF), np.uint32(0))):
