@@ -78,9 +78,6 @@ struct Params {
     WsHeader   *ws;          // null when tiles_per_row == 1
     // segmented scans only: what every tile has to know about its row (built by seg_desc_kernel)
     const struct TileDesc *tile_desc;
-    // fused stream compaction only (`out` then points to the 32-bit values that run parallel to the mask)
-    uint32_t *packed;      // the kept values, in order
-    uint32_t *count;       // optional: number of kept values
 };
 
 // One per tile of a segmented scan (32 bytes, read with one scalar load).
@@ -583,7 +580,6 @@ __device__ __forceinline__ void scan_and_store(int lane, const typename Tr<DT>::
     using T = Tr<DT>;
     using A = typename T::acc;
     using A4 = typename T::acc4;
-    using Ge = Geo<DT>;
     constexpr int kBlocks = T::kBlocks;
     const int c = lane & 15, q = lane >> 4;         // result layout: column, row group
 #pragma unroll
@@ -634,59 +630,6 @@ __device__ __forceinline__ void scan_and_store(int lane, const typename Tr<DT>::
                 for (int r = 0; r < 4; ++r)
                     if (e0 + r < R.rem && (!SEG || e0 + r >= R.lead)) ((uint32_t *)R.out)[e0 + r] = v[r];
             }
-        }
-    }
-}
-
-// Fused stream compaction (int8 0/1 mask): the scan's last step, with the store of the positions replaced by the
-// scatter itself.  `R.out` addresses the 32-bit values that run parallel to the mask; a lane loads the four values
-// whose results it holds (16 bytes; a wavefront's load covers 1 KiB).  The kept values of one result block -- 256
-// consecutive elements of the input -- form one consecutive range of the output: they are put in order in a 1 KiB LDS
-// slot of the wavefront and written from there with consecutive lanes on consecutive words (the direct scatter, four
-// half-empty scattered stores per block, measured 525 us for n = 2^28 against the two-kernel path's 820).
-constexpr int kPackSlot = 256;      // words of LDS per wavefront
-template <int NT>
-__device__ __forceinline__ void compact_store(int lane, const Tr<TCUSCAN_I8_I32>::AConst &Aop, const Run &R, const u32x4 (&g)[NT],
-                                              uint32_t carry, uint32_t *__restrict__ packed, uint32_t *slot)
-{
-    constexpr int DT = TCUSCAN_I8_I32;
-    using T = Tr<DT>;
-    const int c = lane & 15, q = lane >> 4;
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        i32x4 d[T::kBlocks];
-        T::mma(Aop, g[t], lane, true, false, d);                        // 2 * ones before + the element
-        const u32x4 tt = bits<u32x4>(T::totals(Aop, g[t]));
-#pragma unroll
-        for (int p = 0; p < T::kBlocks; ++p) {
-            const uint32_t ex = row_exclusive_scan(tt[p]);             // kept elements of the block before this lane's granule
-            const uint32_t kept = uniform_from_lane(ex + tt[p], 15);   // ... and in the whole block
-            const uint32_t e0 = slot_offset<DT, NT, false>(t, 16 * p + c) + 4u * q;
-            if (e0 < R.rem) {
-                u32x4 x = {0u, 0u, 0u, 0u};
-                if (R.out_vec && e0 + 4 <= R.rem) {
-                    x = *(const u32x4 *)(R.out + e0 * 4);
-                } else {
-                    for (int r = 0; r < 4; ++r)
-                        if (e0 + r < R.rem) x[r] = ((const uint32_t *)R.out)[e0 + r];
-                }
-                for (int r = 0; r < 4; ++r) {
-                    const uint32_t w = (uint32_t)d[p][r], at = ex + (w >> 1);
-                    if (e0 + r < R.rem && (w & 1u) && at < (uint32_t)kPackSlot) slot[at] = x[r];
-                }
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-            for (int k = 0; k < kPackSlot / 64; ++k) {
-                const uint32_t i = 64u * k + lane;
-                if (i < kept) packed[carry + i] = slot[i];
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");     // the slot is reused by the next block
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            carry += kept;
         }
     }
 }
@@ -748,7 +691,7 @@ template <> struct MinWaves<TCUSCAN_I8_I32, 8>    { static constexpr int value =
 template <> struct MinWaves<TCUSCAN_F16_F32, 16>  { static constexpr int value = 4; };
 template <> struct MinWaves<TCUSCAN_BF16_F32, 16> { static constexpr int value = 4; };
 
-template <int DT, int NT, bool EXCL, bool REV, int W, bool SEG = false, bool COMPACT = false>
+template <int DT, int NT, bool EXCL, bool REV, int W, bool SEG = false>
 __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(MinWaves<DT, NT>::value)))
 void scan_kernel(Params P)
 {
@@ -759,7 +702,6 @@ void scan_kernel(Params P)
 
     __shared__ uint32_t s_wave_total[W];
     __shared__ uint32_t s_bcast;
-    __shared__ uint32_t s_pack[COMPACT ? W : 1][COMPACT ? kPackSlot : 1];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // wave-uniform: keeps tile bookkeeping in SGPRs
@@ -802,8 +744,7 @@ void scan_kernel(Params P)
 
     u32x4 g[NT];
     load_run<DT, NT, REV, SEG>(R, lane, g);
-    typename T::AConst Aop;
-    if constexpr (COMPACT) Aop = T::make_compact(lane); else Aop = T::make(lane, EXCL, REV);
+    const typename T::AConst Aop = T::make(lane, EXCL, REV);
 
     // ---- the total of the run (the up-sweep of this tile in one step)
     const A wave_total = reduce_run<DT, NT>(lane, Aop, g);
@@ -849,22 +790,22 @@ void scan_kernel(Params P)
     }
 
     // ---- local scans, down-sweep add and store, with everything before this wavefront's run as carry
-    if constexpr (COMPACT) {
-        if (P.count && tile == P.num_tiles - 1 && threadIdx.x == 0) *P.count = acc_bits(acc_add(prefix, wg_total));
-        compact_store<NT>(lane, Aop, R, g, acc_bits(acc_add(prefix, wave_off)), P.packed, s_pack[COMPACT ? wave : 0]);
-    } else {
-        scan_and_store<DT, NT, EXCL, REV, SEG>(lane, Aop, R, g, acc_add(prefix, wave_off));
-    }
+    scan_and_store<DT, NT, EXCL, REV, SEG>(lane, Aop, R, g, acc_add(prefix, wave_off));
 }
 
-// ------------------------------------------------------------- fused split (one pass of the radix sort)
+// ------------------------------------------------------------- fused split and fused stream compaction
 //
-// Blelloch's split on bit b: keys whose bit is 0 go to the front, the others behind them, both in their old order.
-// The mask "bit b is 0" is never written: a lane builds the 16 mask bytes of its granule from 16 keys it loads, the
-// scan runs as in the fused compaction (2 * zeros before + own flag in one product), and the keys -- loaded again, 16
-// bytes per lane where its results are -- are ordered per result block in an LDS slot (zeros first, then ones) and
-// written as two consecutive ranges.  The number of zeros of the whole array, which the ones' destinations need, does
-// not depend on the order of the keys: all 32 counts are taken once, before the first pass.
+// Blelloch's split on bit b (one pass of the radix sort): keys whose bit is 0 go to the front, the others behind them,
+// both in their old order.  The mask "bit b is 0" is never written and the keys are read once: a lane loads its keys
+// where its results will be (16 bytes per result block, every load instruction 1 KiB contiguous), takes the mask bytes
+// from them and passes them to the lanes that feed the product (a 4 x 4 transpose between registers and 16-lane rows:
+// four lane swaps per MFMA tile).  The scan is the usual one (run totals first, carry chain between workgroups) with
+// an operand that returns 2 * (flagged before) + own flag: destination and flag in one product.  The words of a
+// wavefront's run, still in registers, are put in order in an LDS slot (zeros, then ones) and leave it as two
+// consecutive ranges, 16 bytes per lane.  The number of zeros of the whole array, which the ones' destinations need,
+// does not depend on the order of the keys: all 32 counts are taken once, before the first pass.
+//
+// Stream compaction is the same kernel body with the flags read from the mask array and only the first range stored.
 
 __global__ __launch_bounds__(256) void bit_zero_counts_kernel(const uint32_t *__restrict__ keys, size_t n, uint32_t *counts)
 {
@@ -874,10 +815,24 @@ __global__ __launch_bounds__(256) void bit_zero_counts_kernel(const uint32_t *__
     uint32_t cnt[32];
 #pragma unroll
     for (int b = 0; b < 32; ++b) cnt[b] = 0u;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
-        const uint32_t z = ~keys[i];
+    // bits b, b + 8, b + 16, b + 24 are counted together in the four bytes of one word, which is emptied into the
+    // 32-bit counters before a byte can overflow (255 keys)
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i0 < n; i0 += 255u * stride) {
+        uint32_t packed[8];
 #pragma unroll
-        for (int b = 0; b < 32; ++b) cnt[b] += (z >> b) & 1u;
+        for (int b = 0; b < 8; ++b) packed[b] = 0u;
+        size_t i = i0;
+#pragma unroll 4
+        for (int k = 0; k < 255 && i < n; ++k, i += stride) {
+            const uint32_t z = ~keys[i];
+#pragma unroll
+            for (int b = 0; b < 8; ++b) packed[b] += (z >> b) & 0x01010101u;
+        }
+#pragma unroll
+        for (int b = 0; b < 8; ++b)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) cnt[b + 8 * j] += (packed[b] >> (8 * j)) & 0xFFu;
     }
 #pragma unroll
     for (int b = 0; b < 32; ++b) {
@@ -895,51 +850,106 @@ struct SplitArgs {
     int bit;
 };
 
-template <int NT, int W>
-__global__ __launch_bounds__(64 * W) void split_kernel(Params P, SplitArgs S)
+// g[k] of the lane in row P (row = 16 lanes) becomes w[P] of the lane in row k, same column: the mask words move
+// from the lanes that hold the keys (result layout) to the lanes that feed the product (one granule of 16 bytes each).
+__device__ __forceinline__ u32x4 rows_transpose(const uint32_t (&w)[4])
 {
-    constexpr int DT = TCUSCAN_I8_I32;
-    using T = Tr<DT>;
-    constexpr uint32_t kEPW = NT * Geo<DT>::kTileElems;
-    constexpr uint32_t kWgElems = kEPW * W;
-    __shared__ uint32_t s_wave_total[W];
-    __shared__ uint32_t s_bcast;
-    __shared__ uint32_t s_pack[W][kPackSlot];
+    const auto x = __builtin_amdgcn_permlane32_swap(w[0], w[2], false, false);    // {rows 0,1 of both, rows 2,3 of both}
+    const auto y = __builtin_amdgcn_permlane32_swap(w[1], w[3], false, false);
+    const auto lo = __builtin_amdgcn_permlane16_swap(x[0], y[0], false, false);   // {even rows of both, odd rows of both}
+    const auto hi = __builtin_amdgcn_permlane16_swap(x[1], y[1], false, false);
+    return u32x4{lo[0], lo[1], hi[0], hi[1]};
+}
 
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const uint32_t tile = blockIdx.x, tag = P.tag;
-    const uint64_t n = P.cols;
-    const uint64_t base = (uint64_t)tile * kWgElems + (uint64_t)wave * kEPW;        // first key of this wavefront's run
-    const uint32_t rem = base < n ? (n - base < 0x40000000ull ? (uint32_t)(n - base) : 0x40000000u) : 0u;
-    const uint32_t *kin = S.keys + base;
-    const bool vec = (((uintptr_t)kin) & 15) == 0;
-    const int bit = S.bit;
+// 16 bytes of a result block for this lane: words e0 .. e0 + 3 of a run of rem words (fill beyond the end).
+__device__ __forceinline__ u32x4 load_block_words(const uint32_t *run, bool vec, uint32_t e0, uint32_t rem, uint32_t fill)
+{
+    u32x4 x = {fill, fill, fill, fill};
+    if (vec && e0 + 4 <= rem) {
+        x = *(const u32x4 *)(run + e0);
+    } else {
+        for (int i = 0; i < 4; ++i)
+            if (e0 + i < rem) x[i] = run[e0 + i];
+    }
+    return x;
+}
 
-    // ---- the mask granules: lane l covers keys 16 l .. 16 l + 15 of every MFMA tile (4 loads of 16 bytes)
-    u32x4 g[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const uint32_t e0 = (uint32_t)t * 1024u + 16u * lane + 4u * k;
-            u32x4 x = {~0u, ~0u, ~0u, ~0u};                                         // keys past the end: flag 0
-            if (vec && e0 + 4 <= rem) {
-                x = *(const u32x4 *)(kin + e0);
-            } else {
-                for (int i = 0; i < 4; ++i)
-                    if (e0 + i < rem) x[i] = kin[e0 + i];
-            }
-            uint32_t w = 0;
-            for (int i = 0; i < 4; ++i) w |= (((x[i] >> bit) & 1u) ^ 1u) << (8 * i);
-            if (e0 + 4 > rem)                                                        // ragged tail: only real keys count
-                for (int i = 0; i < 4; ++i)
-                    if (e0 + i >= rem) w &= ~(0xFFu << (8 * i));
-            g[t][k] = w;
+// One ordered range of the slot to global memory.  The range was placed in the slot at the same offset inside a
+// 16-byte group as it has in global memory (a = that offset in words), so a lane moves whole aligned groups: one
+// 16-byte LDS read and one 16-byte store that is 1 KiB contiguous over the wavefront; the two ragged groups at the ends
+// go word by word.  q0: first word of the range's groups in the slot (a multiple of 4); gq: the global address that
+// word 0 of those groups stands for; lim: words from gq on that exist in the destination.
+__device__ __forceinline__ void split_store_range(int lane, const uint32_t *slot, uint32_t q0, uint32_t a, uint32_t cnt,
+                                                  uint32_t *gq, uint32_t lim)
+{
+    const uint32_t end = (a + cnt < lim ? a + cnt : lim), groups = (end + 3u) >> 2;
+    for (uint32_t j = (uint32_t)lane; j < groups; j += 64u) {
+        const u32x4 v = *(const u32x4 *)(slot + q0 + 4u * j);
+        const uint32_t lo = 4u * j;
+        if (lo >= a && lo + 4u <= end) {
+            *(u32x4 *)(gq + lo) = v;
+        } else {
+            for (int i = 0; i < 4; ++i)
+                if (lo + i >= a && lo + i < end) gq[lo + i] = v[i];
         }
     }
-    const typename T::AConst Aop = T::make_compact(lane);
-    const uint32_t wave_total = reduce_run<DT, NT>(lane, Aop, g);
+}
+
+// The words x (keys, payloads or values, in result layout) of one wavefront's run to their places: those with the
+// flag ("zeros": the split flags a key whose bit is 0) from dst[zero_at] on and, if ONES, the others from dst[one_at]
+// on, both in their old order.  The run is ordered in the wavefront's LDS slot
+// first (zeros, then ones; destinations from the product 2 * zeros before + own flag) and leaves it in two ranges.
+template <int NT, uint32_t SLOT, bool ONES>
+__device__ __forceinline__ void split_scatter(int lane, const typename Tr<TCUSCAN_I8_I32>::AConst &Aop, const u32x4 (&g)[NT],
+                                              const u32x4 (&x)[NT][4], uint32_t *dst, uint64_t zero_at, uint64_t one_at,
+                                              uint32_t zeros_run, uint32_t rem, uint64_t n, uint32_t *slot)
+{
+    using T = Tr<TCUSCAN_I8_I32>;
+    constexpr uint32_t kEPW = NT * 1024u;
+    const uint32_t valid = rem < kEPW ? rem : kEPW;
+    uint32_t *dz = dst + zero_at, *d1 = dst + one_at;
+    const uint32_t a0 = (uint32_t)((uintptr_t)dz >> 2) & 3u, a1 = (uint32_t)((uintptr_t)d1 >> 2) & 3u;
+    const uint32_t base1 = ((a0 + zeros_run + 3u) & ~3u) + a1;              // where the ones start in the slot
+    const int c = lane & 15, q = lane >> 4;
+    const uint32_t in_blk = 16u * c + 4u * q;
+    uint32_t before = 0u;                                                    // zeros in the earlier blocks of the run
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        i32x4 d[T::kBlocks];
+        T::mma(Aop, g[t], lane, true, false, d);                            // 2 * zeros before + own flag
+        const u32x4 tt = bits<u32x4>(T::totals(Aop, g[t]));
+#pragma unroll
+        for (int p = 0; p < T::kBlocks; ++p) {
+            const uint32_t ex = row_exclusive_scan(tt[p]);
+            const uint32_t zeros = uniform_from_lane(ex + tt[p], 15);       // zeros in this block
+            const uint32_t idx0 = (uint32_t)t * 1024u + 256u * p + in_blk;
+            for (int r = 0; r < 4; ++r) {
+                const uint32_t w = (uint32_t)d[p][r], zb = before + ex + (w >> 1), idx = idx0 + r;
+                const uint32_t at = (w & 1u) ? a0 + zb : base1 + (idx - zb);
+                if (idx < rem && at < SLOT && (ONES || (w & 1u))) slot[at] = x[t][p][r];
+            }
+            before += zeros;
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const uint64_t room0 = zero_at < n ? n - zero_at : 0u, room1 = one_at < n ? n - one_at : 0u;
+    split_store_range(lane, slot, 0u, a0, zeros_run, dz - a0, a0 + (uint32_t)(room0 < 0x40000000ull ? room0 : 0x40000000ull));
+    if constexpr (ONES)
+        split_store_range(lane, slot, base1 - a1, a1, valid - zeros_run, d1 - a1, a1 + (uint32_t)(room1 < 0x40000000ull ? room1 : 0x40000000ull));
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// From a wavefront's flag count to what lies before its run in the whole array: totals of the workgroup's wavefronts
+// through LDS, then the carry chain between workgroups (as in scan_kernel; one row, tiles in workgroup-index order).
+template <int W>
+__device__ __forceinline__ void flags_before_run(const Params &P, int lane, int wave, uint32_t wave_total, uint32_t *s_wave_total,
+                                                 uint32_t *s_bcast, uint32_t &before_run, uint32_t &run_total, uint32_t &through_wg)
+{
+    const uint32_t tile = blockIdx.x, tag = P.tag;
     if (lane == 0) s_wave_total[wave] = wave_total;
     __syncthreads();
     uint32_t wave_off = 0u, wg_total = 0u;
@@ -949,6 +959,7 @@ __global__ __launch_bounds__(64 * W) void split_kernel(Params P, SplitArgs S)
         if (w < wave) wave_off += v;
         wg_total += v;
     }
+    run_total = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_wave_total[wave]);
     uint32_t prefix = 0u;
     if (P.num_tiles > 1) {
         uint64_t *row_status = (uint64_t *)(P.ws + 1);
@@ -965,69 +976,125 @@ __global__ __launch_bounds__(64 * W) void split_kernel(Params P, SplitArgs S)
                     __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStatePrefix, prefix + wg_total),
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-            if (lane == 0) s_bcast = prefix;
+            if (lane == 0) *s_bcast = prefix;
         }
         __syncthreads();
-        prefix = s_bcast;
+        prefix = *s_bcast;
     }
+    before_run = prefix + wave_off;
+    through_wg = prefix + wg_total;
+}
 
-    // ---- destinations and scatter, one result block (256 keys) at a time
-    const uint32_t zeros_total = *S.zeros_total;
-    uint32_t carry = prefix + wave_off;                         // zeros before the block
-    uint32_t *slot = s_pack[wave];
-    const int c = lane & 15, q = lane >> 4;
+// The 16-byte words of a wavefront's run in result layout: block p of MFMA tile t, words 16 c + 4 q .. + 3 of it.
+template <int NT>
+__device__ __forceinline__ void load_run_words(int lane, const uint32_t *run, uint32_t rem, uint32_t fill, u32x4 (&x)[NT][4])
+{
+    const uint32_t in_blk = 16u * (lane & 15) + 4u * (lane >> 4);
+    const bool vec = (((uintptr_t)run) & 15) == 0;
+    if (vec && rem >= NT * 1024u) {                             // a whole run: straight-line loads
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int p = 0; p < 4; ++p) x[t][p] = *(const u32x4 *)(run + (uint32_t)t * 1024u + 256u * p + in_blk);
+    } else {
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int p = 0; p < 4; ++p) x[t][p] = load_block_words(run, vec, (uint32_t)t * 1024u + 256u * p + in_blk, rem, fill);
+    }
+}
+
+template <int NT, int W, bool VALS>
+__global__ __launch_bounds__(64 * W) void split_kernel(Params P, SplitArgs S)
+{
+    constexpr int DT = TCUSCAN_I8_I32;
+    using T = Tr<DT>;
+    static_assert(T::kBlocks == 4, "four result blocks of 256 per MFMA tile");
+    constexpr uint32_t kEPW = NT * Geo<DT>::kTileElems;
+    constexpr uint32_t kSlot = kEPW + 16u;                      // both ranges, each shifted by up to 3 words and rounded up
+    __shared__ uint32_t s_wave_total[W];
+    __shared__ uint32_t s_bcast;
+    __shared__ __attribute__((aligned(16))) uint32_t s_pack[W][kSlot];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const uint64_t n = P.cols;
+    const uint64_t base = ((uint64_t)blockIdx.x * W + wave) * kEPW;                 // first key of this wavefront's run
+    const uint32_t rem = base < n ? (n - base < 0x40000000ull ? (uint32_t)(n - base) : 0x40000000u) : 0u;
+    const int bit = S.bit;
+
+    // ---- the keys, and from them the mask granules (keys past the end read as all ones: flag 0)
+    u32x4 key[NT][4], g[NT];
+    load_run_words<NT>(lane, S.keys + base, rem, ~0u, key);
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        i32x4 d[T::kBlocks];
-        T::mma(Aop, g[t], lane, true, false, d);               // 2 * zeros before + own flag
-        const u32x4 tt = bits<u32x4>(T::totals(Aop, g[t]));
+        uint32_t w[4];
 #pragma unroll
-        for (int p = 0; p < T::kBlocks; ++p) {
-            const uint32_t ex = row_exclusive_scan(tt[p]);
-            const uint32_t zeros = uniform_from_lane(ex + tt[p], 15);               // zeros in this block
-            const uint32_t b0 = (uint32_t)t * 1024u + 256u * p;                      // first key of the block, run-relative
-            const uint32_t valid = b0 < rem ? (rem - b0 < 256u ? rem - b0 : 256u) : 0u;
-            const uint32_t in_blk = 16u * c + 4u * q;                                // this lane's four keys inside the block
-            const uint32_t e0 = b0 + in_blk;
-            const uint64_t ones_before = base + b0 - carry;                          // ones before the block, in the whole array
-            uint32_t at[4];
-            for (int r = 0; r < 4; ++r) {
-                const uint32_t w = (uint32_t)d[p][r], zb = ex + (w >> 1);
-                at[r] = (w & 1u) ? zb : zeros + (in_blk + r - zb);                   // zeros first, then ones, both in order
-                if (e0 + r >= rem || at[r] >= (uint32_t)kPackSlot) at[r] = ~0u;
-            }
-            for (int pass = 0; pass < 2; ++pass) {
-                const uint32_t *src = pass == 0 ? S.keys : S.vals;
-                uint32_t *dst = pass == 0 ? S.keys_out : S.vals_out;
-                if (!src) break;
-                if (valid) {
-                    u32x4 x = {0u, 0u, 0u, 0u};
-                    const uint32_t *sp = src + base;
-                    if ((((uintptr_t)sp) & 15) == 0 && e0 + 4 <= rem) {
-                        x = *(const u32x4 *)(sp + e0);
-                    } else {
-                        for (int r = 0; r < 4; ++r)
-                            if (e0 + r < rem) x[r] = sp[e0 + r];
-                    }
-                    for (int r = 0; r < 4; ++r)
-                        if (at[r] != ~0u) slot[at[r]] = x[r];
-                }
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        for (int p = 0; p < 4; ++p) {
+            w[p] = 0u;
+            for (int i = 0; i < 4; ++i) w[p] |= ((~key[t][p][i] >> bit) & 1u) << (8 * i);
+        }
+        g[t] = rows_transpose(w);
+    }
+    const typename T::AConst Aop = T::make_compact(lane);
+    uint32_t zero_at, zeros_run, through_wg;
+    flags_before_run<W>(P, lane, wave, reduce_run<DT, NT>(lane, Aop, g), s_wave_total, &s_bcast, zero_at, zeros_run, through_wg);
+
+    // ---- destinations and scatter of the run
+    u32x4 val[VALS ? NT : 1][4];
+    if constexpr (VALS) load_run_words<NT>(lane, S.vals + base, rem, 0u, val);
+    const uint64_t one_at = (uint64_t)*S.zeros_total + (base - zero_at);     // behind all zeros, after the ones before this run
+    split_scatter<NT, kSlot, true>(lane, Aop, g, key, S.keys_out, zero_at, one_at, zeros_run, rem, n, s_pack[wave]);
+    if constexpr (VALS) split_scatter<NT, kSlot, true>(lane, Aop, g, val, S.vals_out, zero_at, one_at, zeros_run, rem, n, s_pack[wave]);
+}
+
+struct CompactArgs {
+    const uint8_t *mask;               // 0 / 1 bytes
+    const uint32_t *values;
+    uint32_t *out;                     // the kept values, in order
+    uint32_t *count;                   // optional: how many
+};
+
+template <int NT, int W>
+__global__ __launch_bounds__(64 * W) void compact_kernel(Params P, CompactArgs C)
+{
+    constexpr int DT = TCUSCAN_I8_I32;
+    using T = Tr<DT>;
+    static_assert(T::kBlocks == 4, "four result blocks of 256 per MFMA tile");
+    constexpr uint32_t kEPW = NT * Geo<DT>::kTileElems;
+    constexpr uint32_t kSlot = kEPW + 16u;
+    __shared__ uint32_t s_wave_total[W];
+    __shared__ uint32_t s_bcast;
+    __shared__ __attribute__((aligned(16))) uint32_t s_pack[W][kSlot];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const uint64_t n = P.cols;
+    const uint64_t base = ((uint64_t)blockIdx.x * W + wave) * kEPW;                 // first element of this wavefront's run
+    const uint32_t rem = base < n ? (n - base < 0x40000000ull ? (uint32_t)(n - base) : 0x40000000u) : 0u;
+
+    // ---- the mask granules (lane l: bytes 16 l .. 16 l + 15 of every MFMA tile; nothing beyond the end) and the values
+    const uint8_t *m = C.mask + base;
+    u32x4 g[NT], val[NT][4];
+    if ((((uintptr_t)m) & 15) == 0 && rem >= kEPW) {
 #pragma unroll
-                for (int k = 0; k < kPackSlot / 64; ++k) {
-                    const uint32_t i = 64u * k + lane;
-                    if (i < zeros) dst[carry + i] = slot[i];
-                    else if (i < valid) dst[(uint64_t)zeros_total + ones_before + (i - zeros)] = slot[i];
-                }
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            }
-            carry += zeros;
+        for (int t = 0; t < NT; ++t) g[t] = *(const u32x4 *)(m + (uint32_t)t * 1024u + 16u * lane);
+    } else {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const uint32_t e0 = (uint32_t)t * 1024u + 16u * lane;
+            u32x4 x = {0u, 0u, 0u, 0u};
+            for (int i = 0; i < 16; ++i)
+                if (e0 + i < rem) x[i >> 2] |= (uint32_t)m[e0 + i] << (8 * (i & 3));
+            g[t] = x;
         }
     }
+    load_run_words<NT>(lane, C.values + base, rem, 0u, val);
+    const typename T::AConst Aop = T::make_compact(lane);
+    uint32_t kept_at, kept_run, through_wg;
+    flags_before_run<W>(P, lane, wave, reduce_run<DT, NT>(lane, Aop, g), s_wave_total, &s_bcast, kept_at, kept_run, through_wg);
+    if (C.count && blockIdx.x == P.num_tiles - 1 && threadIdx.x == 0) *C.count = through_wg;
+    split_scatter<NT, kSlot, false>(lane, Aop, g, val, C.out, kept_at, 0u, kept_run, rem, n, s_pack[wave]);
 }
 
 // ------------------------------------------------------------- segmented scans, short rows
@@ -1329,7 +1396,7 @@ tcuscan_status_t run(const void *d_in, void *d_out, size_t rows, size_t cols, in
     P.tiles_per_row = (uint32_t)tpr; P.num_tiles = (uint32_t)(rows * tpr);
     P.ws = need ? (WsHeader *)d_ws : nullptr;
     P.reverse = reverse ? 1u : 0u;
-    P.tile_desc = nullptr; P.packed = nullptr; P.count = nullptr;
+    P.tile_desc = nullptr;
     // Every call gets a fresh tag, so status words of earlier calls are stale by construction.  A call
     // recorded into a graph is replayed with the SAME tag; it therefore clears its status words first
     // (with a fill kernel, which a graph replays correctly).
@@ -1452,7 +1519,7 @@ tcuscan_status_t run_segmented(const void *d_in, void *d_out, const long long *d
     P.tiles_per_row = 0; P.num_tiles = (uint32_t)L.max_tiles;
     P.ws = (WsHeader *)d_ws;
     P.reverse = reverse ? 1u : 0u;
-    P.tile_desc = desc; P.packed = nullptr; P.count = nullptr;
+    P.tile_desc = desc;
     P.tag = g_calls.fetch_add(1u, std::memory_order_relaxed) % kTagMod + 1u;
     hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
     if (hipStreamIsCapturing(s, &cs) != hipSuccess) { (void)hipGetLastError(); cs = hipStreamCaptureStatusNone; }
@@ -1469,13 +1536,31 @@ tcuscan_status_t run_segmented(const void *d_in, void *d_out, const long long *d
     return e == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
 }
 
-// ---- fused stream compaction
+// ---- fused split and fused stream compaction: one row of n elements in tiles of `tile`, chained through d_ws
 
-template <int NT, int W> hipError_t launch_compact(Params P, hipStream_t s)
+tcuscan_status_t flag_kernel_params(Params &P, size_t n, size_t tile, void *d_ws, size_t ws_bytes, hipStream_t s)
 {
-    void *args[] = {&P};
-    return hipLaunchKernel((const void *)scan_kernel<TCUSCAN_I8_I32, NT, true, false, W, false, true>, dim3(P.num_tiles), dim3(64 * W), args, 0, s);
+    const size_t tiles = (n + tile - 1) / tile;
+    if (tiles > 0x7FFFFFFFull) return TCUSCAN_ERR_UNSUPPORTED;
+    const size_t need = tiles > 1 ? sizeof(WsHeader) + 8 * kStatusStride * tiles : 0;
+    if (need && (!d_ws || ws_bytes < need || ((uintptr_t)d_ws % 8) != 0)) return TCUSCAN_ERR_WORKSPACE;
+    P.in = nullptr; P.out = nullptr; P.rows = 1; P.cols = n;
+    P.tiles_per_row = (uint32_t)tiles; P.num_tiles = (uint32_t)tiles;
+    P.ws = need ? (WsHeader *)d_ws : nullptr;
+    P.reverse = 0; P.tile_desc = nullptr;
+    P.tag = g_calls.fetch_add(1u, std::memory_order_relaxed) % kTagMod + 1u;
+    if (need) {
+        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(s, &cs) != hipSuccess) { (void)hipGetLastError(); cs = hipStreamCaptureStatusNone; }
+        if (cs == hipStreamCaptureStatusActive &&
+            launch_fill((char *)d_ws + sizeof(WsHeader), 8 * kStatusStride * tiles, s) != hipSuccess) return TCUSCAN_ERR_HIP;
+    }
+    return TCUSCAN_OK;
 }
+
+// 2048 elements per wavefront (their words stay in registers from the load to the scatter), 8 wavefronts: 16384 per
+// workgroup, 64.5 KiB of LDS, two workgroups per compute unit.
+constexpr int kFlagNT = 2, kFlagW = 8;
 
 }  // namespace
 
@@ -1495,31 +1580,18 @@ extern "C" __attribute__((visibility("hidden")))
 tcuscan_status_t tcuscan_internal_split_pass(const void *d_keys, const void *d_vals, void *d_keys_out, void *d_vals_out, size_t n, int bit,
                                              const unsigned *d_zeros_total, void *d_ws, size_t ws_bytes, tcuscan_stream_t stream)
 {
-    constexpr int NT = 8, W = 4;                                   // 32768 keys per workgroup
-    const size_t tile = (size_t)NT * W * 1024;
-    const size_t tiles = (n + tile - 1) / tile;
-    if (tiles > 0x7FFFFFFFull) return TCUSCAN_ERR_UNSUPPORTED;
-    const size_t need = tiles > 1 ? sizeof(WsHeader) + 8 * kStatusStride * tiles : 0;
-    if (need && (!d_ws || ws_bytes < need || ((uintptr_t)d_ws % 8) != 0)) return TCUSCAN_ERR_WORKSPACE;
+    constexpr int NT = kFlagNT, W = kFlagW;
     hipStream_t s = (hipStream_t)stream;
     Params P;
-    P.in = d_keys; P.out = d_keys_out; P.rows = 1; P.cols = n;
-    P.tiles_per_row = (uint32_t)tiles; P.num_tiles = (uint32_t)tiles;
-    P.ws = need ? (WsHeader *)d_ws : nullptr;
-    P.reverse = 0; P.tile_desc = nullptr; P.packed = nullptr; P.count = nullptr;
-    P.tag = g_calls.fetch_add(1u, std::memory_order_relaxed) % kTagMod + 1u;
-    if (need) {
-        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-        if (hipStreamIsCapturing(s, &cs) != hipSuccess) { (void)hipGetLastError(); cs = hipStreamCaptureStatusNone; }
-        if (cs == hipStreamCaptureStatusActive &&
-            launch_fill((char *)d_ws + sizeof(WsHeader), 8 * kStatusStride * tiles, s) != hipSuccess) return TCUSCAN_ERR_HIP;
-    }
+    const tcuscan_status_t st = flag_kernel_params(P, n, (size_t)NT * W * 1024, d_ws, ws_bytes, s);
+    if (st != TCUSCAN_OK) return st;
     SplitArgs S;
     S.keys = (const uint32_t *)d_keys; S.vals = (const uint32_t *)d_vals;
     S.keys_out = (uint32_t *)d_keys_out; S.vals_out = (uint32_t *)d_vals_out;
     S.zeros_total = d_zeros_total; S.bit = bit;
     void *args[] = {&P, &S};
-    return hipLaunchKernel((const void *)split_kernel<NT, W>, dim3((unsigned)tiles), dim3(64 * W), args, 0, s) == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
+    const void *fn = d_vals ? (const void *)split_kernel<NT, W, true> : (const void *)split_kernel<NT, W, false>;
+    return hipLaunchKernel(fn, dim3(P.num_tiles), dim3(64 * W), args, 0, s) == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
 }
 
 // Used by tcuscan_compact_u32 (apps.hip) when the caller does not ask for the positions: one pass over the mask
@@ -1528,31 +1600,15 @@ extern "C" __attribute__((visibility("hidden")))
 tcuscan_status_t tcuscan_internal_compact_fused(const void *d_values, const void *d_mask, void *d_out, size_t n, unsigned *d_count,
                                                 void *d_ws, size_t ws_bytes, tcuscan_stream_t stream)
 {
-    const int dt = TCUSCAN_I8_I32;
-    const size_t need = tcuscan_workspace_bytes(1, n, (tcuscan_dtype_t)dt);
-    if (need && (!d_ws || ws_bytes < need || ((uintptr_t)d_ws % 8) != 0)) return TCUSCAN_ERR_WORKSPACE;
-    const int size = choose_tile(dt, 1, n);
-    const size_t tile = tile_elems(dt, size);
-    const size_t tpr = (n + tile - 1) / tile;
+    constexpr int NT = kFlagNT, W = kFlagW;
     hipStream_t s = (hipStream_t)stream;
     Params P;
-    P.in = d_mask; P.out = const_cast<void *>(d_values); P.rows = 1; P.cols = n;
-    P.tiles_per_row = (uint32_t)tpr; P.num_tiles = (uint32_t)tpr;
-    P.ws = need ? (WsHeader *)d_ws : nullptr;
-    P.reverse = 0; P.tile_desc = nullptr;
-    P.packed = (uint32_t *)d_out; P.count = d_count;
-    P.tag = g_calls.fetch_add(1u, std::memory_order_relaxed) % kTagMod + 1u;
-    if (P.ws && tpr > 1) {
-        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-        if (hipStreamIsCapturing(s, &cs) != hipSuccess) { (void)hipGetLastError(); cs = hipStreamCaptureStatusNone; }
-        if (cs == hipStreamCaptureStatusActive &&
-            launch_fill((char *)d_ws + sizeof(WsHeader), 8 * kStatusStride * tpr, s) != hipSuccess) return TCUSCAN_ERR_HIP;
-    }
-    using Ti = Tiles<TCUSCAN_I8_I32>;
-    hipError_t e = size == kTileHuge  ? launch_compact<Ti::kHuge, Ti::wHuge>(P, s)
-                 : size == kTileLarge ? launch_compact<Ti::kLarge, Ti::wLarge>(P, s)
-                                      : launch_compact<Ti::kSmall, Ti::wSmall>(P, s);
-    return e == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
+    const tcuscan_status_t st = flag_kernel_params(P, n, (size_t)NT * W * 1024, d_ws, ws_bytes, s);
+    if (st != TCUSCAN_OK) return st;
+    CompactArgs C;
+    C.mask = (const uint8_t *)d_mask; C.values = (const uint32_t *)d_values; C.out = (uint32_t *)d_out; C.count = d_count;
+    void *args[] = {&P, &C};
+    return hipLaunchKernel((const void *)compact_kernel<NT, W>, dim3(P.num_tiles), dim3(64 * W), args, 0, s) == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
 }
 
 extern "C" {
