@@ -887,7 +887,7 @@ __device__ __forceinline__ void split_store_range(int lane, const uint32_t *slot
         const u32x4 v = *(const u32x4 *)(slot + q0 + 4u * j);
         const uint32_t lo = 4u * j;
         if (lo >= a && lo + 4u <= end) {
-            *(u32x4 *)(gq + lo) = v;
+            __builtin_nontemporal_store(v, (u32x4 *)(gq + lo));
         } else {
             for (int i = 0; i < 4; ++i)
                 if (lo + i >= a && lo + i < end) gq[lo + i] = v[i];
@@ -995,7 +995,7 @@ __device__ __forceinline__ void load_run_words(int lane, const uint32_t *run, ui
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int p = 0; p < 4; ++p) x[t][p] = *(const u32x4 *)(run + (uint32_t)t * 1024u + 256u * p + in_blk);
+            for (int p = 0; p < 4; ++p) x[t][p] = __builtin_nontemporal_load((const u32x4 *)(run + (uint32_t)t * 1024u + 256u * p + in_blk));
     } else {
 #pragma unroll
         for (int t = 0; t < NT; ++t)
