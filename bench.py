@@ -8,8 +8,9 @@ carry chain between workgroups, down-sweep add, store) over one batch of seeded 
 input that is already resident in HBM.  Prints ONE JSON line.  `value` is G elements/s of the
 headline workload; `roofline` prices the scan kernel against the 8 TB/s HBM peak using
 algorithmic bytes (input read once + output written once); `cpu_baseline` is the sequential
-CPU oracle timed on this host in the same run; `others` holds the remaining benchmark
-configurations measured the same way.
+CPU oracle timed on this host in the same run, `cpu_all_cores` a chunked scan on one thread
+per available core (a second host figure, checked against the oracle here); `others` holds the
+remaining benchmark configurations measured the same way.
 """
 from __future__ import annotations
 
@@ -312,6 +313,31 @@ def cpu_baseline(name: str, x: np.ndarray, gpu_out):
             "ms": best * 1e3}, parity
 
 
+def cpu_all_cores(name: str, x: np.ndarray):
+    """The usual multi-thread host scan (rows dealt to threads, or chunk sums / offsets / chunk scans), one thread per
+    available core, on the same workload; its output is checked against the oracle."""
+    import oracle
+    from oracle import host_threads
+    cfg = inputs.CONFIGS[name]
+    kind, rows, cols = cfg["kind"], cfg["rows"], cfg["cols"]
+    excl = cfg["call"] == "exclusive"
+    n = rows * cols
+    is_int = kind in ("i32", "i8")
+    out = np.zeros(n, dtype=np.int32 if is_int else np.float32)      # pre-faulted
+    cores = host_threads.available()
+    best = float("inf")
+    for _ in range(3):
+        t0 = time.perf_counter()
+        host_threads.scan_into(x, kind, out, exclusive=excl, rows=rows, cols=cols, threads=cores)
+        best = min(best, time.perf_counter() - t0)
+    if is_int:
+        ok = oracle.compare_int(x, kind, out, exclusive=excl, rows=rows, cols=cols)[0] == 0
+    else:
+        ok = oracle.compare_float(x, kind, out, exclusive=excl, rows=rows, cols=cols).ok(cfg["tol"])
+    return {"value": n / best / 1e9, "unit": "G elements/s", "cores": cores, "kind": "chunked scan, one thread per core",
+            "sample": f"full workload ({n} elements), best of 3 passes, {best * 1e3:.0f} ms per pass", "matches_oracle": bool(ok)}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -338,6 +364,7 @@ def main() -> int:
 
     head, x, last = measure(args.workload, args.steps, args.warmup, keep_host=not args.no_cpu)
     cpu, parity = (None, None) if args.no_cpu else cpu_baseline(args.workload, x, last)
+    cpu_all = None if args.no_cpu else cpu_all_cores(args.workload, x)
     del x, last
     others = {}
     if not args.no_others:
@@ -365,6 +392,7 @@ def main() -> int:
                      "algorithmic_bytes_per_elem": head["bytes_per_elem"],
                      "frac_of_measured_copy": head["achieved_GBps"] / ceiling},
         "cpu_baseline": cpu,
+        "cpu_all_cores": cpu_all,
         "parity_of_timed_output": parity,
         "copy_ceiling_GBps": ceiling,
         "others": others,
