@@ -85,9 +85,18 @@ def measure(name: str, steps: int, warmup: int, keep_host: bool = False):
     kern_ms = ev0.elapsed_time(ev1) / steps
     if ws is not None and tcuscan.workspace_fault(ws) != 0:
         raise RuntimeError("carry chain fault flag set")
+    # launch by launch (an event between consecutive launches, outside the timed region above): median and minimum
+    m = min(steps, 30)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(m + 1)]
+    evs[0].record()
+    for i in range(m):
+        launch(cfg, d_ins[i % pairs], d_outs[i % pairs], ws)
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    each = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(m))
     res = {
         "workload": DESCR.get(name, name), "n": n, "dtype": kind, "bytes_per_elem": bytes_per_elem,
-        "ms_per_step": wall_ms, "kernel_ms": kern_ms,
+        "ms_per_step": wall_ms, "kernel_ms": kern_ms, "kernel_ms_median": each[m // 2], "kernel_ms_min": each[0],
         "gelems_per_s": n / (wall_ms * 1e-3) / 1e9,
         "achieved_GBps": n * bytes_per_elem / (kern_ms * 1e-3) / 1e9,
         "buffer_pairs": pairs,
@@ -372,7 +381,8 @@ def main() -> int:
             if name == args.workload:
                 continue
             r, _, _ = measure(name, max(10, args.steps // 2), args.warmup)
-            others[name] = {k: r[k] for k in ("workload", "kernel_ms", "gelems_per_s", "achieved_GBps", "frac_of_peak")}
+            others[name] = {k: r[k] for k in ("workload", "kernel_ms", "kernel_ms_median", "kernel_ms_min", "gelems_per_s",
+                                              "achieved_GBps", "frac_of_peak")}
         others["algorithm1_round_by_round"] = measure_levels(5)
         others.update(measure_apps(5))
         others.update(measure_variants(10))
@@ -389,6 +399,7 @@ def main() -> int:
         "roofline": {"bound": "hbm", "achieved": head["achieved_GBps"], "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                      "frac": head["frac_of_peak"], "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
                      "kernel": "scan_kernel", "kernel_ms": head["kernel_ms"],
+                     "kernel_ms_median": head["kernel_ms_median"], "kernel_ms_min": head["kernel_ms_min"],
                      "algorithmic_bytes_per_elem": head["bytes_per_elem"],
                      "frac_of_measured_copy": head["achieved_GBps"] / ceiling},
         "cpu_baseline": cpu,
