@@ -208,8 +208,16 @@ def measure_variants(steps: int):
     ws = tcuscan.new_segmented_workspace(nrows, m, "f32")
     ms = timed(lambda: tcuscan.segmented(xf, d_of, d_off, nrows, m, "f32", ws=ws))
     covered = int(off[-1])
-    res["segmented_short_rows"] = {"workload": f"{covered} fp32 elements in {nrows} rows, geometric lengths (mean 200), some empty, some of 8013",
+    res["segmented_short_rows"] = {"workload": f"{covered} fp32 elements in {nrows} rows, geometric lengths (mean 200), some empty, some of 8013; "
+                                               "the range scanned as one row with row-start bits",
                                    "ms": ms, "gelems_per_s": covered / ms / 1e6, "frac_of_peak": covered * 8 / ms / 1e6 / PEAK_HBM_GBPS}
+    tcuscan.set_segmented_form(False)
+    try:
+        ms = timed(lambda: tcuscan.segmented(xf, d_of, d_off, nrows, m, "f32", ws=ws))
+        res["segmented_short_rows_own_tiles"] = {"workload": "the same with tiles of its own for every row", "ms": ms,
+                                                 "gelems_per_s": covered / ms / 1e6, "frac_of_peak": covered * 8 / ms / 1e6 / PEAK_HBM_GBPS}
+    finally:
+        tcuscan.set_segmented_form(True)
     return res
 
 

@@ -1173,6 +1173,211 @@ __global__ __launch_bounds__(64 * kSegPack) void seg_short_kernel(Params P)
     }
 }
 
+// ------------------------------------------------------------- segmented scans, short rows of 32-bit elements
+//
+// Rows of a few hundred 32-bit elements do not get tiles of their own: the rows lie back to back, so the whole range
+// [offsets[0], offsets[rows]) is tiled like one long row -- every load and store instruction full, no descriptor per
+// tile -- and the row starts come in as one bit per element (set by seg_heads_kernel from the offsets).  The scan is
+// then the segmented one, sums restart at every set bit:
+//   level 0   a lane's granule (4 elements): the MFMA product with the triangular blocks as everywhere else; a granule
+//             with a row start at its element 1, 2 or 3 is redone by the lane in three dependent adds (the operand is
+//             the same for the 16 granules of a product, so it cannot know where one of them is cut -- and subtracting
+//             the part before the cut would not be exact in floating point);
+//   levels 1, 2   (sum since the last row start, "a row starts here") pairs scanned over the 64 lanes with DPP shifts:
+//             a pair that has a start keeps its sum, the others add the incoming one;
+//   beyond    the pair of the wavefront's run, of the workgroup, of the tile.  A tile that contains a row start knows
+//             what its successors need without asking anybody -- it publishes its pair as a finished prefix at once --
+//             so with short rows the carry chain is one hop long, and with long rows it is the usual one.
+// The results stay in the registers that held the inputs (one granule in, one granule out) while the tile waits for
+// what comes before it; that sum is then added to the elements that no row start precedes within the tile.
+// Forward scans only.
+
+__global__ void seg_heads_kernel(const long long *offsets, size_t rows, size_t total, uint32_t shift, uint32_t *heads, WsHeader *ws)
+{
+    const size_t r = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= rows) return;
+    const long long off = offsets[r], end = offsets[r + 1];
+    const bool bad = off < 0 || end < off || (unsigned long long)end > total;
+    if (bad) __hip_atomic_store(&ws->fault, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((end > off || bad) && off >= 0 && (unsigned long long)off < total) {   // (a bad row still ends the row before it)
+        const uint64_t b = (uint64_t)off + shift;                      // bit of element i: i + shift (granules start at multiples of 4)
+        atomicOr(&heads[b >> 5], 1u << (b & 31));
+    }
+}
+
+// (sum since the last row start, a row starts at or before here) of lanes 0 .. l, in lane l
+template <class A> __device__ __forceinline__ void seg_wave_inclusive(A &v, uint32_t &h)
+{
+#define TCUSCAN_SEG_STEP(CTRL)                                                        \
+    {                                                                                 \
+        const A vu = dpp_shr<A, CTRL>(v);                                             \
+        const uint32_t hu = dpp0<CTRL>(h);                                            \
+        v = h ? v : acc_add(vu, v);                                                   \
+        h |= hu;                                                                      \
+    }
+    TCUSCAN_SEG_STEP(kRowShr + 1)
+    TCUSCAN_SEG_STEP(kRowShr + 2)
+    TCUSCAN_SEG_STEP(kRowShr + 4)
+    TCUSCAN_SEG_STEP(kRowShr + 8)
+#undef TCUSCAN_SEG_STEP
+    {   // the row before, into rows 1 and 3
+        const A vu = acc_from_bits<A>((uint32_t)__builtin_amdgcn_update_dpp(0, (int)acc_bits(v), kRowBcast15, 0xa, 0xf, false));
+        const uint32_t hu = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)h, kRowBcast15, 0xa, 0xf, false);
+        v = h ? v : acc_add(vu, v);
+        h |= hu;
+    }
+    {   // rows 0 and 1, into rows 2 and 3
+        const A vu = acc_from_bits<A>((uint32_t)__builtin_amdgcn_update_dpp(0, (int)acc_bits(v), kRowBcast31, 0xc, 0xf, false));
+        const uint32_t hu = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)h, kRowBcast31, 0xc, 0xf, false);
+        v = h ? v : acc_add(vu, v);
+        h |= hu;
+    }
+}
+
+template <int DT, int NT, bool EXCL, int W>
+__global__ __launch_bounds__(64 * W) void seg_flat_kernel(Params P, const long long *offsets, const uint32_t *heads, uint32_t shift)
+{
+    using T = Tr<DT>;
+    using A = typename T::acc;
+    static_assert(T::kLinear && T::kG == 4 && NT <= 8, "32-bit elements: a lane keeps its granule; 4 flag bits per granule in one word");
+    constexpr uint32_t kEPW = NT * Geo<DT>::kTileElems;
+    constexpr uint32_t kWgElems = kEPW * W;
+    __shared__ uint32_t s_sum[W], s_head[W];
+    __shared__ uint32_t s_bcast;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const uint32_t tile = blockIdx.x, tag = P.tag;
+
+    // the range the rows cover, clamped to the arrays (offsets that leave them have raised the fault word already)
+    long long lo = offsets[0], hi = offsets[P.rows];
+    const long long total = (long long)P.cols;
+    lo = lo < 0 ? 0 : (lo > total ? total : lo);
+    hi = hi < lo ? lo : (hi > total ? total : hi);
+    const uint32_t lead = seg_lead<DT>(P, lo);
+    const uint64_t vlen = (uint64_t)(hi - lo) + lead;
+    if ((uint64_t)tile * kWgElems >= vlen) return;             // the grid is an upper bound
+    const uint64_t base = (uint64_t)tile * kWgElems + (uint64_t)wave * kEPW;
+    const Run R = make_seg_run<DT>(P, lo, (uint64_t)(hi - lo), lead, base);
+
+    u32x4 g[NT];
+    load_run<DT, NT, false, true>(R, lane, g);
+    // row starts among this lane's elements: 4 bits per granule, granule t in bits 4t .. 4t + 3
+    const uint64_t bit0 = (uint64_t)(lo - (long long)lead) + base + shift;     // bit of the run's first slot (a multiple of 4)
+    uint32_t starts = 0u;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const uint32_t e0 = (uint32_t)t * 256u + 4u * lane;
+        if (e0 < R.rem) {
+            const uint64_t b = bit0 + e0;
+            starts |= ((heads[b >> 5] >> (b & 31)) & 0xFu) << (4 * t);
+        }
+    }
+
+    // ---- the run by itself: segmented scan in place, (sum since the last row start, any row start) of the run
+    const typename T::AConst Aop = T::make(lane, false, false);
+    A carry = acc_from_bits<A>(0u);                            // sum since the last row start, up to the end of the tile before
+    bool run_open = true;                                      // no row start in the run so far
+    uint32_t open = 0u;                                        // per element: no row start at or before it in the run
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const uint32_t fb = (starts >> (4 * t)) & 0xFu;
+        typename T::acc4 d[1];
+        T::mma(Aop, g[t], lane, false, false, d);
+        A y[4];
+        for (int i = 0; i < 4; ++i) y[i] = acc_from_bits<A>(bits<u32x4>(d[0])[i]);
+        if (fb & 0xEu) {                                       // a row starts inside the granule
+            y[0] = acc_from_bits<A>(g[t][0]);
+            for (int i = 1; i < 4; ++i) {
+                const A x = acc_from_bits<A>(g[t][i]);
+                y[i] = ((fb >> i) & 1u) ? x : acc_add(y[i - 1], x);
+            }
+        }
+        A v = y[3];
+        uint32_t h = fb ? 1u : 0u;
+        seg_wave_inclusive(v, h);
+        const A vex = wave_shift_up(v);
+        const uint32_t hex = dpp0<kWaveShr1>(h);
+        const A in = hex ? vex : acc_add(carry, vex);          // what the open row brings into this granule
+        const bool in_open = run_open && !hex;
+        uint32_t clear = 0u;                                   // elements with no row start at or before them in the granule
+        for (int i = 0; i < 4; ++i) {
+            if ((fb & ((2u << i) - 1u)) == 0u) { y[i] = acc_add(in, y[i]); clear |= 1u << i; }
+            g[t][i] = acc_bits(y[i]);
+        }
+        if (in_open) open |= clear << (4 * t);
+        carry = uniform_from_lane(y[3], 63);
+        run_open = run_open && __ballot(fb != 0u) == 0ull;
+    }
+
+    // ---- the wavefronts of the workgroup, then the tiles before this one
+    if (lane == 0) { s_sum[wave] = acc_bits(carry); s_head[wave] = run_open ? 0u : 1u; }
+    __syncthreads();
+    A before = acc_from_bits<A>(0u), wg_sum = acc_from_bits<A>(0u);       // of the wavefronts before this one / of all of them
+    bool before_head = false, wg_head = false;
+#pragma unroll
+    for (int w = 0; w < W; ++w) {
+        const A v = acc_from_bits<A>(s_sum[w]);
+        const bool hd = s_head[w] != 0u;
+        if (w < wave) { before = hd ? v : acc_add(before, v); before_head = before_head || hd; }
+        wg_sum = hd ? v : acc_add(wg_sum, v);
+        wg_head = wg_head || hd;
+    }
+    A prefix = acc_from_bits<A>(0u);
+    if (P.num_tiles > 1) {
+        uint64_t *row_status = (uint64_t *)(P.ws + 1);
+        if (wave == 0) {
+            if (tile == 0 || wg_head) {                        // nothing before this tile matters to the tiles after it
+                if (lane == 0)
+                    __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStatePrefix, acc_bits(wg_sum)),
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (tile != 0) prefix = look_back<A>(row_status, (int)tile, tag, P.ws);
+            } else {
+                if (lane == 0)
+                    __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStateAggregate, acc_bits(wg_sum)),
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                prefix = look_back<A>(row_status, (int)tile, tag, P.ws);
+                if (lane == 0)
+                    __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStatePrefix, acc_bits(acc_add(prefix, wg_sum))),
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            if (lane == 0) s_bcast = acc_bits(prefix);
+        }
+        __syncthreads();
+        prefix = acc_from_bits<A>(s_bcast);
+    }
+    const A wave_in = before_head ? before : acc_add(prefix, before);     // the open row's sum at the start of this run
+
+    // ---- add it where no row start comes first, store
+    A last = wave_in;                                          // the inclusive result of the element before the granule (exclusive scans)
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const uint32_t fb = (starts >> (4 * t)) & 0xFu, ob = (open >> (4 * t)) & 0xFu;
+        A y[4];
+        for (int i = 0; i < 4; ++i) {
+            y[i] = acc_from_bits<A>(g[t][i]);
+            if ((ob >> i) & 1u) y[i] = acc_add(wave_in, y[i]);
+        }
+        u32x4 v;
+        if constexpr (EXCL) {
+            A prev = wave_shift_up(y[3]);
+            if (lane == 0) prev = last;
+            last = uniform_from_lane(y[3], 63);
+            v[0] = (fb & 1u) ? 0u : acc_bits(prev);
+            for (int i = 1; i < 4; ++i) v[i] = ((fb >> i) & 1u) ? 0u : acc_bits(y[i - 1]);
+        } else {
+            for (int i = 0; i < 4; ++i) v[i] = acc_bits(y[i]);
+        }
+        const uint32_t e0 = (uint32_t)t * 256u + 4u * lane;
+        if (R.out_vec && e0 + 4 <= R.rem && e0 >= R.lead) {
+            __builtin_nontemporal_store(v, (u32x4 *)(R.out + e0 * 4));
+        } else {
+            for (int i = 0; i < 4; ++i)
+                if (e0 + i < R.rem && e0 + i >= R.lead) ((uint32_t *)R.out)[e0 + i] = v[i];
+        }
+    }
+}
+
 // ---------------------------------------------------------------------- short-row kernel
 //
 // Rows no longer than one wavefront's run (NT tiles): every wavefront scans rows of its own -- no
@@ -1321,6 +1526,7 @@ int choose_tile(int dt, size_t rows, size_t cols)
 }
 
 std::atomic<uint32_t> g_calls{0};
+std::atomic<int> g_seg_flat{1};            // see tcuscan_set_segmented_form
 
 // Short rows: the smallest run length (1, 2, 4 or 8 MFMA tiles per wavefront) that holds a row.
 // The four (exclusive, reverse) instantiations of one kernel shape.
@@ -1440,6 +1646,7 @@ size_t seg_tile_elems(int dt, int cls)
 struct SegLayout {
     size_t max_tiles;        // upper bound on the number of tiles = grid size
     size_t counts_off, starts_off, rowmap_off, inner_off, inner_bytes, total_bytes;
+    size_t heads_off, heads_words;   // row-start bits (short 32-bit rows only, else 0 words): never where status words may lie
 };
 
 bool seg_layout(int dt, size_t rows, size_t total, SegLayout &L)
@@ -1453,7 +1660,9 @@ bool seg_layout(int dt, size_t rows, size_t total, SegLayout &L)
     L.rowmap_off = up(L.starts_off + 4 * (rows + 1));
     L.inner_off = up(L.rowmap_off + sizeof(TileDesc) * L.max_tiles);
     L.inner_bytes = tcuscan_workspace_bytes(1, rows + 1, TCUSCAN_I32_I32);
-    L.total_bytes = L.inner_off + L.inner_bytes;
+    L.heads_off = up(L.inner_off + L.inner_bytes);
+    L.heads_words = seg_tile_class(dt, rows, total) == kSegShort && in_size(dt) == 4 ? (total + 8) / 32 + 1 : 0;
+    L.total_bytes = L.heads_off + 4 * L.heads_words;
     return true;
 }
 
@@ -1479,6 +1688,46 @@ template <int DT> hipError_t launch_seg(Params P, bool excl, int cls, hipStream_
     return hipLaunchKernel(seg_short_kernel_for<DT>(excl, rev), dim3((P.num_tiles + per_wg - 1) / per_wg), dim3(64 * kSegPack), args, 0, s);
 }
 
+// Short rows of 32-bit elements, forward: the covered range as one row with row-start bits (seg_flat_kernel).  Three
+// launches: clear the bits, set them from the offsets, scan.  The status words are the first ones of the general
+// layout; the bits have a region of their own behind everything else (a word of bits where another call expects a
+// status word could pass for one).
+constexpr int kFlatNT = 8, kFlatW = 4;
+template <int DT> const void *seg_flat_kernel_for(bool excl)
+{
+    return excl ? (const void *)seg_flat_kernel<DT, kFlatNT, true, kFlatW> : (const void *)seg_flat_kernel<DT, kFlatNT, false, kFlatW>;
+}
+tcuscan_status_t run_segmented_flat(const void *d_in, void *d_out, const long long *d_offsets, size_t rows, size_t total, int dt,
+                                    int exclusive, void *d_ws, const SegLayout &L, hipStream_t s)
+{
+    const size_t tile = (size_t)kFlatNT * kFlatW * 256;
+    const size_t tiles = total / tile + 2;                       // the range is at most `total` long and starts less than a granule late
+    if (tiles > L.max_tiles) return TCUSCAN_ERR_UNSUPPORTED;     // (never: the general layout counts smaller tiles)
+    uint32_t *heads = (uint32_t *)((char *)d_ws + L.heads_off);
+    const uint32_t shift = (uint32_t)(((uintptr_t)d_in >> 2) & 3u);
+    if (launch_fill(heads, 4 * L.heads_words, s) != hipSuccess) return TCUSCAN_ERR_HIP;
+    {
+        const long long *off = d_offsets; size_t r = rows, t = total; uint32_t sh = shift; WsHeader *h = (WsHeader *)d_ws;
+        void *args[] = {&off, &r, &t, &sh, &heads, &h};
+        if (hipLaunchKernel((const void *)seg_heads_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), args, 0, s) != hipSuccess)
+            return TCUSCAN_ERR_HIP;
+    }
+    Params P;
+    P.in = d_in; P.out = d_out; P.rows = rows; P.cols = total;
+    P.tiles_per_row = 0; P.num_tiles = (uint32_t)tiles;
+    P.ws = (WsHeader *)d_ws;
+    P.reverse = 0; P.tile_desc = nullptr;
+    P.tag = g_calls.fetch_add(1u, std::memory_order_relaxed) % kTagMod + 1u;
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &cs) != hipSuccess) { (void)hipGetLastError(); cs = hipStreamCaptureStatusNone; }
+    if (cs == hipStreamCaptureStatusActive && launch_fill((char *)d_ws + sizeof(WsHeader), 8 * kStatusStride * tiles, s) != hipSuccess)
+        return TCUSCAN_ERR_HIP;
+    const long long *off = d_offsets; const uint32_t *hd = heads; uint32_t sh = shift;
+    void *args[] = {&P, &off, &hd, &sh};
+    const void *fn = dt == TCUSCAN_F32_F32 ? seg_flat_kernel_for<TCUSCAN_F32_F32>(exclusive != 0) : seg_flat_kernel_for<TCUSCAN_I32_I32>(exclusive != 0);
+    return hipLaunchKernel(fn, dim3(P.num_tiles), dim3(64 * kFlatW), args, 0, s) == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
+}
+
 tcuscan_status_t run_segmented(const void *d_in, void *d_out, const long long *d_offsets, size_t rows, size_t total, int dt,
                                int exclusive, int reverse, void *d_ws, size_t ws_bytes, tcuscan_stream_t stream)
 {
@@ -1492,6 +1741,8 @@ tcuscan_status_t run_segmented(const void *d_in, void *d_out, const long long *d
     if (!d_ws || ws_bytes < L.total_bytes || ((uintptr_t)d_ws % 8) != 0) return TCUSCAN_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     const int cls = seg_tile_class(dt, rows, total);
+    if (L.heads_words && !reverse && g_seg_flat.load(std::memory_order_relaxed))
+        return run_segmented_flat(d_in, d_out, d_offsets, rows, total, dt, exclusive, d_ws, L, s);
     const size_t tile = seg_tile_elems(dt, cls);
     int32_t *counts = (int32_t *)((char *)d_ws + L.counts_off);
     uint32_t *starts = (uint32_t *)((char *)d_ws + L.starts_off);
@@ -1618,6 +1869,12 @@ size_t tcuscan_tile_elems(tcuscan_dtype_t dt) { return valid_dtype((int)dt) ? kS
 size_t tcuscan_large_tile_elems(tcuscan_dtype_t dt) { return valid_dtype((int)dt) ? tile_elems((int)dt, kTileLarge) : 0; }
 
 size_t tcuscan_huge_tile_elems(tcuscan_dtype_t dt) { return valid_dtype((int)dt) ? tile_elems((int)dt, kTileHuge) : 0; }
+
+tcuscan_status_t tcuscan_set_segmented_form(int flat)
+{
+    g_seg_flat.store(flat != 0 ? 1 : 0, std::memory_order_relaxed);
+    return TCUSCAN_OK;
+}
 
 tcuscan_status_t tcuscan_set_tile_policy(int policy)
 {

@@ -18,7 +18,7 @@ DTYPES = {"i32": I32_I32, "f16": F16_F32, "i8": I8_I32, "f32": F32_F32, "bf16": 
 
 EXPORTS = ["tcuscan_workspace_bytes", "tcuscan_workspace_init", "tcuscan_inclusive", "tcuscan_exclusive",
            "tcuscan_batched", "tcuscan_scan", "tcuscan_segmented_workspace_bytes", "tcuscan_segmented", "tcuscan_tile_elems", "tcuscan_large_tile_elems", "tcuscan_huge_tile_elems",
-           "tcuscan_set_tile_policy",
+           "tcuscan_set_tile_policy", "tcuscan_set_segmented_form",
            "tcuscan_workspace_fault", "tcuscan_matmulscan_levels", "tcuscan_matmulscan_levels_radix", "tcuscan_compact_u32",
            "tcuscan_split_radix_sort_u32", "tcuscan_set_sort_fusion", "tcuscan_status_string"]
 
@@ -55,6 +55,8 @@ def load() -> ctypes.CDLL:
         L.tcuscan_set_tile_policy.restype = ci
         L.tcuscan_set_sort_fusion.argtypes = [ci]
         L.tcuscan_set_sort_fusion.restype = ci
+        L.tcuscan_set_segmented_form.argtypes = [ci]
+        L.tcuscan_set_segmented_form.restype = ci
         L.tcuscan_workspace_init.argtypes = [vp, sz, vp]
         L.tcuscan_inclusive.argtypes = [vp, vp, sz, ci, vp, sz, vp]
         L.tcuscan_exclusive.argtypes = [vp, vp, sz, ci, vp, sz, vp]
@@ -209,6 +211,10 @@ def compact_u32(values, mask, out, positions, count=None, ws=None, stream=None) 
                                     *_ws_args(ws), _stream(stream))
     if rc != OK:
         raise TcuscanError(rc, "tcuscan_compact_u32")
+
+
+def set_segmented_form(flat: bool) -> None:
+    load().tcuscan_set_segmented_form(int(bool(flat)))
 
 
 def set_sort_fusion(fused: bool) -> None:

@@ -37,6 +37,22 @@ def run_segmented(x, kind, off, total=None, flags=0, ws=None, inplace=False):
     return d_out.cpu().numpy().copy(), fault
 
 
+class forms:
+    """Both forms of the call where it has two (forward scans of short 32-bit rows: one range with row-start bits, or
+    tiles of their own for every row); the library's default is restored afterwards."""
+
+    def __init__(self, kind, flags=0):
+        self.which = [True, False] if kind in ("i32", "f32") and not flags & 2 else [True]
+
+    def __iter__(self):
+        try:
+            for flat in self.which:
+                tcuscan.set_segmented_form(flat)
+                yield flat
+        finally:
+            tcuscan.set_segmented_form(True)
+
+
 def check(x, kind, off, got, excl, rev, exact_float=False):
     if kind in INT_GEN or exact_float:
         nb, first = oracle.compare_segments(x, kind, off, got, exclusive=excl, reverse=rev, exact_float=kind not in INT_GEN)
@@ -69,14 +85,16 @@ def test_ragged_rows(kind, rows, mean, flags):
     excl, rev = bool(flags & 1), bool(flags & 2)
     gen = INT_GEN.get(kind) or TRI_GEN[kind]
     x = gen(n, 100 + rows)
-    got, fault = run_segmented(x, kind, off, flags=flags)
-    assert fault == 0
-    check(x, kind, off, got, excl, rev, exact_float=True)
-    if kind not in INT_GEN and flags in (0, 3):
-        x = RND_GEN[kind](n, 200 + rows)
+    for _ in forms(kind, flags):
         got, fault = run_segmented(x, kind, off, flags=flags)
         assert fault == 0
-        check(x, kind, off, got, excl, rev)
+        check(x, kind, off, got, excl, rev, exact_float=True)
+    if kind not in INT_GEN and flags in (0, 1, 3):
+        x = RND_GEN[kind](n, 200 + rows)
+        for _ in forms(kind, flags):
+            got, fault = run_segmented(x, kind, off, flags=flags)
+            assert fault == 0
+            check(x, kind, off, got, excl, rev)
 
 
 @pytest.mark.parametrize("kind", KINDS)
@@ -90,9 +108,10 @@ def test_every_start_alignment_and_length_around_the_tiles(kind):
     gen = INT_GEN.get(kind) or TRI_GEN[kind]
     x = gen(int(off[-1]) + 3, 31)
     for flags in (0, 1, 2, 3):
-        got, fault = run_segmented(x, kind, off, flags=flags)
-        assert fault == 0
-        check(x, kind, off, got, bool(flags & 1), bool(flags & 2), exact_float=True)
+        for _ in forms(kind, flags):
+            got, fault = run_segmented(x, kind, off, flags=flags)
+            assert fault == 0
+            check(x, kind, off, got, bool(flags & 1), bool(flags & 2), exact_float=True)
     # the same rows through the long-row tile (a large `total` raises the average row length)
     got, fault = run_segmented(x, kind, off[:4], total=x.size, flags=0)
     check(x, kind, off[:4], got, False, False, exact_float=True)
@@ -123,8 +142,11 @@ def test_many_rows_and_workspace_reuse():
         check(x, "i8", off, got, bool(flags & 1), bool(flags & 2))
     xf = inputs.f32_normal(n, 9)
     wsf = tcuscan.new_segmented_workspace(rows, n, "f32")
-    got, fault = run_segmented(xf, "f32", off, ws=wsf)
-    check(xf, "f32", off, got, False, False)
+    for _ in forms("f32"):
+        for flags in (0, 1):
+            got, fault = run_segmented(xf, "f32", off, flags=flags, ws=wsf)
+            assert fault == 0
+            check(xf, "f32", off, got, bool(flags), False)
 
 
 def test_long_rows_full_size():
@@ -146,11 +168,12 @@ def test_in_place_and_empty_calls():
     rng = np.random.default_rng(12)
     off = offsets_from(lengths_mix(rng, 500, 90), start=2)
     x = inputs.int32_full(int(off[-1]) + 1, 13)
-    got, fault = run_segmented(x, "i32", off, inplace=True)
     want = oracle.scan_segments(x, "i32", off)
     inside = slice(int(off[0]), int(off[-1]))
-    assert fault == 0 and np.array_equal(got[inside], want[inside])
-    assert got[0] == x[0] and got[1] == x[1] and got[-1] == x[-1]          # outside the rows: untouched
+    for _ in forms("i32"):
+        got, fault = run_segmented(x, "i32", off, inplace=True)
+        assert fault == 0 and np.array_equal(got[inside], want[inside])
+        assert got[0] == x[0] and got[1] == x[1] and got[-1] == x[-1]      # outside the rows: untouched
     t = torch.zeros(16, dtype=torch.int32, device="cuda")
     o = torch.zeros(3, dtype=torch.int64, device="cuda")
     tcuscan.segmented(t, t, o, 0, 16, "i32")                                # no rows: nothing enqueued
@@ -161,14 +184,16 @@ def test_in_place_and_empty_calls():
 def test_bad_offsets_are_not_followed_and_raise_the_fault_word():
     x = inputs.int32_full(1000, 14)
     off = np.array([0, 100, 100, 400, 5000], np.int64)                     # the last row leaves [0, total]
-    got, fault = run_segmented(x, "i32", off)
-    assert fault == 2
     want = oracle.scan_segments(x, "i32", off[:4])
-    assert np.array_equal(got[:400], want[:400])                            # the valid rows are scanned
-    assert np.all(got[400:] == GUARD)                                       # the bad one is skipped
-    for bad in ([0, 300, 200, 250, 1000], [-5, 10, 20, 30, 40], [0, 10, 20, 30, 1001]):
-        got, fault = run_segmented(x, "i32", np.array(bad, np.int64))
-        assert fault == 2                                                   # results unspecified, but flagged and in bounds
+    for flat in forms("i32"):
+        got, fault = run_segmented(x, "i32", off)
+        assert fault == 2
+        assert np.array_equal(got[:400], want[:400])                        # the valid rows before it are scanned
+        if not flat:
+            assert np.all(got[400:] == GUARD)                               # rows with tiles of their own: the bad one gets none
+        for bad in ([0, 300, 200, 250, 1000], [-5, 10, 20, 30, 40], [0, 10, 20, 30, 1001]):
+            got, fault = run_segmented(x, "i32", np.array(bad, np.int64))
+            assert fault == 2                                               # results unspecified, but flagged and in bounds
 
 
 def test_refusals():
