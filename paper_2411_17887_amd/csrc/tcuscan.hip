@@ -1190,7 +1190,7 @@ __global__ __launch_bounds__(64 * kSegPack) void seg_short_kernel(Params P)
 //             so with short rows the carry chain is one hop long, and with long rows it is the usual one.
 // The results stay in the registers that held the inputs (one granule in, one granule out) while the tile waits for
 // what comes before it; that sum is then added to the elements that no row start precedes within the tile.
-// Forward scans only.
+// A reverse scan is the same in mirrored order, restarting at row ends.
 
 __global__ void seg_heads_kernel(const long long *offsets, size_t rows, size_t total, uint32_t shift, uint32_t *heads, WsHeader *ws)
 {
@@ -1201,6 +1201,10 @@ __global__ void seg_heads_kernel(const long long *offsets, size_t rows, size_t t
     if (bad) __hip_atomic_store(&ws->fault, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if ((end > off || bad) && off >= 0 && (unsigned long long)off < total) {   // (a bad row still ends the row before it)
         const uint64_t b = (uint64_t)off + shift;                      // bit of element i: i + shift (granules start at multiples of 4)
+        atomicOr(&heads[b >> 5], 1u << (b & 31));
+    }
+    if (r == rows - 1 && !bad) {                                       // behind the last row: its last element ends a row (reverse scans)
+        const uint64_t b = (uint64_t)end + shift;
         atomicOr(&heads[b >> 5], 1u << (b & 31));
     }
 }
@@ -1234,7 +1238,7 @@ template <class A> __device__ __forceinline__ void seg_wave_inclusive(A &v, uint
     }
 }
 
-template <int DT, int NT, bool EXCL, int W>
+template <int DT, int NT, bool EXCL, bool REV, int W>
 __global__ __launch_bounds__(64 * W) void seg_flat_kernel(Params P, const long long *offsets, const uint32_t *heads, uint32_t shift)
 {
     using T = Tr<DT>;
@@ -1256,13 +1260,20 @@ __global__ __launch_bounds__(64 * W) void seg_flat_kernel(Params P, const long l
     hi = hi < lo ? lo : (hi > total ? total : hi);
     const uint32_t lead = seg_lead<DT>(P, lo);
     const uint64_t vlen = (uint64_t)(hi - lo) + lead;
-    if ((uint64_t)tile * kWgElems >= vlen) return;             // the grid is an upper bound
-    const uint64_t base = (uint64_t)tile * kWgElems + (uint64_t)wave * kEPW;
+    const uint64_t tiles = (vlen + kWgElems - 1) / kWgElems;
+    if (tile >= tiles) return;                                 // the grid is an upper bound
+    const uint64_t pos = REV ? tiles - 1 - tile : tile;        // a reverse scan starts at the end of the range
+    const uint64_t base = pos * kWgElems + (uint64_t)wave * kEPW;
     const Run R = make_seg_run<DT>(P, lo, (uint64_t)(hi - lo), lead, base);
+    // Everything below works in processing order: element i of a granule is its memory element mem(i); a reverse scan
+    // mirrors the granules of the run (slot_offset), the elements inside a granule, the wavefronts and the tiles, and
+    // restarts at row ENDS -- element j ends a row when a row starts at j + 1 (the kernel that sets the bits also sets
+    // the one behind the last row).
+    auto mem = [](int i) { return REV ? 3 - i : i; };
 
     // a run that lies inside the range as a whole (all but the first and the last few) takes straight-line loads and stores
-    const bool whole_in = __builtin_amdgcn_readfirstlane((int)(R.in_vec && R.lead == 0u && R.rem >= kEPW)) != 0;
-    const bool whole_out = __builtin_amdgcn_readfirstlane((int)(R.out_vec && R.lead == 0u && R.rem >= kEPW)) != 0;
+    const bool whole_in = !REV && __builtin_amdgcn_readfirstlane((int)(R.in_vec && R.lead == 0u && R.rem >= kEPW)) != 0;
+    const bool whole_out = __builtin_amdgcn_readfirstlane((int)(R.out_vec && R.lead == 0u && R.rem >= kEPW)) != 0;   // (either direction)
     u32x4 g[NT];
     // row starts among this lane's elements: 4 bits per granule, granule t in bits 4t .. 4t + 3
     const uint64_t bit0 = (uint64_t)(lo - (long long)lead) + base + shift;     // bit of the run's first slot (a multiple of 4)
@@ -1276,19 +1287,25 @@ __global__ __launch_bounds__(64 * W) void seg_flat_kernel(Params P, const long l
             starts |= ((heads[b >> 5] >> (b & 31)) & 0xFu) << (4 * t);
         }
     } else {
-        load_run<DT, NT, false, true>(R, lane, g);
+        load_run<DT, NT, REV, true>(R, lane, g);
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            const uint32_t e0 = (uint32_t)t * 256u + 4u * lane;
+            const uint32_t e0 = slot_offset<DT, NT, REV>(t, lane);
             if (e0 < R.rem) {
                 const uint64_t b = bit0 + e0;
-                starts |= ((heads[b >> 5] >> (b & 31)) & 0xFu) << (4 * t);
+                if constexpr (REV) {
+                    const uint64_t w = (uint64_t)heads[b >> 5] | ((uint64_t)heads[(b >> 5) + 1] << 32);
+                    const uint32_t ends = (uint32_t)(w >> ((b & 31) + 1)) & 0xFu;                     // memory order
+                    starts |= (((ends & 1u) << 3) | ((ends & 2u) << 1) | ((ends & 4u) >> 1) | ((ends & 8u) >> 3)) << (4 * t);
+                } else {
+                    starts |= ((heads[b >> 5] >> (b & 31)) & 0xFu) << (4 * t);
+                }
             }
         }
     }
 
     // ---- the run by itself: segmented scan in place, (sum since the last row start, any row start) of the run
-    const typename T::AConst Aop = T::make(lane, false, false);
+    const typename T::AConst Aop = T::make(lane, false, REV);
     A carry = acc_from_bits<A>(0u);                            // sum since the last row start, up to the end of the tile before
     bool run_open = true;                                      // no row start in the run so far
     uint32_t open = 0u;                                        // bit t: no row start in the run before this lane's granule of tile t
@@ -1299,16 +1316,16 @@ __global__ __launch_bounds__(64 * W) void seg_flat_kernel(Params P, const long l
         A y[4];
         if (__ballot((fb & 0xEu) != 0u) == 0ull) {             // no granule of this tile is cut: the product is the scan
             typename T::acc4 d[1];
-            T::mma(Aop, g[t], lane, false, false, d);
-            for (int i = 0; i < 4; ++i) y[i] = acc_from_bits<A>(bits<u32x4>(d[0])[i]);
+            T::mma(Aop, g[t], lane, false, REV, d);
+            for (int i = 0; i < 4; ++i) y[i] = acc_from_bits<A>(bits<u32x4>(d[0])[mem(i)]);
         } else {                                               // three dependent adds; a row start drops what came before
-            y[0] = acc_from_bits<A>(g[t][0]);
+            y[0] = acc_from_bits<A>(g[t][mem(0)]);
             for (int i = 1; i < 4; ++i) {
                 const uint32_t keep = (uint32_t)(((int32_t)(~fb << (31 - i))) >> 31);       // all ones unless a row starts at i
-                y[i] = acc_add(acc_from_bits<A>(acc_bits(y[i - 1]) & keep), acc_from_bits<A>(g[t][i]));
+                y[i] = acc_add(acc_from_bits<A>(acc_bits(y[i - 1]) & keep), acc_from_bits<A>(g[t][mem(i)]));
             }
         }
-        for (int i = 0; i < 4; ++i) g[t][i] = acc_bits(y[i]);
+        for (int i = 0; i < 4; ++i) g[t][mem(i)] = acc_bits(y[i]);
         A v = y[3];
         uint32_t h = fb ? 1u : 0u;
         seg_wave_inclusive(v, h);
@@ -1332,6 +1349,18 @@ __global__ __launch_bounds__(64 * W) void seg_flat_kernel(Params P, const long l
         if (w < wave) { before = hd ? v : acc_add(before, v); before_head = before_head || hd; }
         wg_sum = hd ? v : acc_add(wg_sum, v);
         wg_head = wg_head || hd;
+    }
+    if constexpr (REV) {                                       // the wavefronts behind this one come first
+        before = acc_from_bits<A>(0u); wg_sum = acc_from_bits<A>(0u);
+        before_head = false; wg_head = false;
+#pragma unroll
+        for (int w = W - 1; w >= 0; --w) {
+            const A v = acc_from_bits<A>(s_sum[w]);
+            const bool hd = s_head[w] != 0u;
+            if (w > wave) { before = hd ? v : acc_add(before, v); before_head = before_head || hd; }
+            wg_sum = hd ? v : acc_add(wg_sum, v);
+            wg_head = wg_head || hd;
+        }
     }
     A prefix = acc_from_bits<A>(0u);
     if (P.num_tiles > 1) {
@@ -1367,7 +1396,7 @@ __global__ __launch_bounds__(64 * W) void seg_flat_kernel(Params P, const long l
         const uint32_t first = fb ? (uint32_t)__builtin_ctz(fb) : 4u;     // elements before the granule's first row start
         A y[4];
         for (int i = 0; i < 4; ++i) {
-            y[i] = acc_from_bits<A>(g[t][i]);
+            y[i] = acc_from_bits<A>(g[t][mem(i)]);
             if ((uint32_t)i < first) y[i] = acc_add(add, y[i]);
         }
         u32x4 v;
@@ -1375,12 +1404,12 @@ __global__ __launch_bounds__(64 * W) void seg_flat_kernel(Params P, const long l
             A prev = wave_shift_up(y[3]);
             if (lane == 0) prev = last;
             last = uniform_from_lane(y[3], 63);
-            v[0] = (fb & 1u) ? 0u : acc_bits(prev);
-            for (int i = 1; i < 4; ++i) v[i] = ((fb >> i) & 1u) ? 0u : acc_bits(y[i - 1]);
+            v[mem(0)] = (fb & 1u) ? 0u : acc_bits(prev);
+            for (int i = 1; i < 4; ++i) v[mem(i)] = ((fb >> i) & 1u) ? 0u : acc_bits(y[i - 1]);
         } else {
-            for (int i = 0; i < 4; ++i) v[i] = acc_bits(y[i]);
+            for (int i = 0; i < 4; ++i) v[mem(i)] = acc_bits(y[i]);
         }
-        const uint32_t e0 = (uint32_t)t * 256u + 4u * lane;
+        const uint32_t e0 = slot_offset<DT, NT, REV>(t, lane);
         if (whole_out) {
             __builtin_nontemporal_store(v, (u32x4 *)(R.out + e0 * 4));
         } else if (R.out_vec && e0 + 4 <= R.rem && e0 >= R.lead) {
@@ -1675,7 +1704,7 @@ bool seg_layout(int dt, size_t rows, size_t total, SegLayout &L)
     L.inner_off = up(L.rowmap_off + sizeof(TileDesc) * L.max_tiles);
     L.inner_bytes = tcuscan_workspace_bytes(1, rows + 1, TCUSCAN_I32_I32);
     L.heads_off = up(L.inner_off + L.inner_bytes);
-    L.heads_words = seg_tile_class(dt, rows, total) == kSegShort && in_size(dt) == 4 ? (total + 8) / 32 + 1 : 0;
+    L.heads_words = seg_tile_class(dt, rows, total) == kSegShort && in_size(dt) == 4 ? (total + 8) / 32 + 2 : 0;
     L.total_bytes = L.heads_off + 4 * L.heads_words;
     return true;
 }
@@ -1702,19 +1731,20 @@ template <int DT> hipError_t launch_seg(Params P, bool excl, int cls, hipStream_
     return hipLaunchKernel(seg_short_kernel_for<DT>(excl, rev), dim3((P.num_tiles + per_wg - 1) / per_wg), dim3(64 * kSegPack), args, 0, s);
 }
 
-// Short rows of 32-bit elements, forward: the covered range as one row with row-start bits (seg_flat_kernel).  Three
+// Short rows of 32-bit elements: the covered range as one row with row-start bits (seg_flat_kernel).  Three
 // launches: clear the bits, set them from the offsets, scan.  Measured on 2^26 fp32 elements cut at random into rows of
 // mean length 20 / 200 / 1500 / 5000 / 20000: 172 / 107 / 108 / 110 / 114 us against 1436 / 213 / 137 / 102 / 97 us with
 // tiles of their own for every row -- hence for the short class only (average below 2048 elements).  The status words are the first ones of the general
 // layout; the bits have a region of their own behind everything else (a word of bits where another call expects a
 // status word could pass for one).
 constexpr int kFlatNT = 8, kFlatW = 8;
-template <int DT> const void *seg_flat_kernel_for(bool excl)
+template <int DT> const void *seg_flat_kernel_for(bool excl, bool rev)
 {
-    return excl ? (const void *)seg_flat_kernel<DT, kFlatNT, true, kFlatW> : (const void *)seg_flat_kernel<DT, kFlatNT, false, kFlatW>;
+    if (rev) return excl ? (const void *)seg_flat_kernel<DT, kFlatNT, true, true, kFlatW> : (const void *)seg_flat_kernel<DT, kFlatNT, false, true, kFlatW>;
+    return excl ? (const void *)seg_flat_kernel<DT, kFlatNT, true, false, kFlatW> : (const void *)seg_flat_kernel<DT, kFlatNT, false, false, kFlatW>;
 }
 tcuscan_status_t run_segmented_flat(const void *d_in, void *d_out, const long long *d_offsets, size_t rows, size_t total, int dt,
-                                    int exclusive, void *d_ws, const SegLayout &L, hipStream_t s)
+                                    int exclusive, int reverse, void *d_ws, const SegLayout &L, hipStream_t s)
 {
     const size_t tile = (size_t)kFlatNT * kFlatW * 256;
     const size_t tiles = total / tile + 2;                       // the range is at most `total` long and starts less than a granule late
@@ -1732,7 +1762,7 @@ tcuscan_status_t run_segmented_flat(const void *d_in, void *d_out, const long lo
     P.in = d_in; P.out = d_out; P.rows = rows; P.cols = total;
     P.tiles_per_row = 0; P.num_tiles = (uint32_t)tiles;
     P.ws = (WsHeader *)d_ws;
-    P.reverse = 0; P.tile_desc = nullptr;
+    P.reverse = reverse ? 1u : 0u; P.tile_desc = nullptr;
     P.tag = g_calls.fetch_add(1u, std::memory_order_relaxed) % kTagMod + 1u;
     hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
     if (hipStreamIsCapturing(s, &cs) != hipSuccess) { (void)hipGetLastError(); cs = hipStreamCaptureStatusNone; }
@@ -1740,7 +1770,8 @@ tcuscan_status_t run_segmented_flat(const void *d_in, void *d_out, const long lo
         return TCUSCAN_ERR_HIP;
     const long long *off = d_offsets; const uint32_t *hd = heads; uint32_t sh = shift;
     void *args[] = {&P, &off, &hd, &sh};
-    const void *fn = dt == TCUSCAN_F32_F32 ? seg_flat_kernel_for<TCUSCAN_F32_F32>(exclusive != 0) : seg_flat_kernel_for<TCUSCAN_I32_I32>(exclusive != 0);
+    const void *fn = dt == TCUSCAN_F32_F32 ? seg_flat_kernel_for<TCUSCAN_F32_F32>(exclusive != 0, reverse != 0)
+                                           : seg_flat_kernel_for<TCUSCAN_I32_I32>(exclusive != 0, reverse != 0);
     return hipLaunchKernel(fn, dim3(P.num_tiles), dim3(64 * kFlatW), args, 0, s) == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
 }
 
@@ -1757,8 +1788,8 @@ tcuscan_status_t run_segmented(const void *d_in, void *d_out, const long long *d
     if (!d_ws || ws_bytes < L.total_bytes || ((uintptr_t)d_ws % 8) != 0) return TCUSCAN_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     const int cls = seg_tile_class(dt, rows, total);
-    if (L.heads_words && !reverse && g_seg_flat.load(std::memory_order_relaxed))
-        return run_segmented_flat(d_in, d_out, d_offsets, rows, total, dt, exclusive, d_ws, L, s);
+    if (L.heads_words && g_seg_flat.load(std::memory_order_relaxed))
+        return run_segmented_flat(d_in, d_out, d_offsets, rows, total, dt, exclusive, reverse, d_ws, L, s);
     const size_t tile = seg_tile_elems(dt, cls);
     int32_t *counts = (int32_t *)((char *)d_ws + L.counts_off);
     uint32_t *starts = (uint32_t *)((char *)d_ws + L.starts_off);
