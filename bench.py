@@ -270,16 +270,20 @@ def measure_apps(steps: int):
         return bool((k[1:] >= k[:-1]).all().item())
 
     ms2 = timed(sort_once, max(2, steps // 2))
-    res["split_radix_sort"] = {"workload": "n=2^26 random 32-bit keys, 32 fused split passes (mask from the keys, MFMA scan, scatter: one "
-                                           "kernel each), includes one 256 MiB copy per run",
+    res["split_radix_sort"] = {"workload": "n=2^26 random 32-bit keys, 16 fused split passes on two bits each (flags from the keys, MFMA "
+                                           "scans, scatter: one kernel per pass), includes one 256 MiB copy per run",
                                "ms": ms2, "mkeys_per_s": m / (ms2 * 1e-3) / 1e6, "sorted": is_sorted()}
-    tcuscan.set_sort_fusion(False)
     try:
+        tcuscan.set_sort_fusion(2)
+        ms1 = timed(sort_once, max(2, steps // 2))
+        res["split_radix_sort_one_bit"] = {"workload": "the same with 32 fused split passes on one bit each",
+                                           "ms": ms1, "mkeys_per_s": m / (ms1 * 1e-3) / 1e6, "sorted": is_sorted()}
+        tcuscan.set_sort_fusion(0)
         ms3 = timed(sort_once, max(2, steps // 2))
-        res["split_radix_sort_three_kernels"] = {"workload": "the same with mask kernel + tcuscan_exclusive + scatter kernel per pass",
+        res["split_radix_sort_three_kernels"] = {"workload": "the same with mask kernel + tcuscan_exclusive + scatter kernel per bit",
                                                  "ms": ms3, "mkeys_per_s": m / (ms3 * 1e-3) / 1e6, "sorted": is_sorted()}
     finally:
-        tcuscan.set_sort_fusion(True)
+        tcuscan.set_sort_fusion(1)
     return res
 
 

@@ -224,17 +224,20 @@ tcuscan_status_t tcuscan_compact_u32(const void *d_values, const void *d_mask, v
  *   d_keys_tmp, d_vals_tmp   scratch, n words each (d_vals_tmp only with d_vals); keys buffers 16-byte aligned
  *   d_flags                  scratch, n bytes, 16-byte aligned
  *   d_positions              scratch, n int32
- * One scan per bit: this answers "can the matrix unit sort?", it is not a tuned sort.  By default every pass is one
- * fused kernel (mask built from the keys, scanned on the MFMA unit, keys scattered; d_flags is not used and
- * d_positions only holds 32 counters); tcuscan_set_sort_fusion(0) selects the three-kernel form of the reduction
- * (mask kernel, tcuscan_exclusive, scatter kernel), which is also what n < 32 takes.
+ * This answers "can the matrix unit sort?".  By default a pass is one fused kernel (flags built from the keys, scanned
+ * on the MFMA unit, keys scattered; d_flags is not used and d_positions only holds 96 counters) and splits on two bits
+ * at once -- four buckets, the flags of two digits sharing a byte of the scanned operand -- so a full sort is 16
+ * passes; an odd `bits` ends with one pass on a single bit.  tcuscan_set_sort_fusion(2) keeps the fused kernel to one
+ * bit per pass, tcuscan_set_sort_fusion(0) selects the three-kernel form of the reduction (mask kernel,
+ * tcuscan_exclusive, scatter kernel per bit), which is also what n < 96 takes.
  */
 tcuscan_status_t tcuscan_split_radix_sort_u32(void *d_keys, void *d_vals, size_t n, int bits,
                                               void *d_keys_tmp, void *d_vals_tmp, void *d_flags, void *d_positions,
                                               void *d_ws, size_t ws_bytes, tcuscan_stream_t stream);
 
-/* 1 (default): fused split passes; 0: mask kernel + tcuscan_exclusive + scatter kernel per pass.  Process-wide; a
- * measurement and test knob, the sorted result is the same. */
+/* 1 (default): fused split passes on two bits; 2: fused passes on one bit; 0: mask kernel + tcuscan_exclusive + scatter
+ * kernel per bit; anything else TCUSCAN_ERR_INVALID_ARG.  Process-wide; a measurement and test knob, the sorted result
+ * is the same. */
 tcuscan_status_t tcuscan_set_sort_fusion(int fused);
 
 /* Static, human-readable name of a status code. */

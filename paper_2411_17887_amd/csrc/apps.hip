@@ -24,6 +24,11 @@ extern "C" tcuscan_status_t tcuscan_internal_split_pass(const void *d_keys, cons
                                                         int bit, const unsigned *d_zeros_total, void *d_ws, size_t ws_bytes,
                                                         tcuscan_stream_t stream);
 
+extern "C" tcuscan_status_t tcuscan_internal_digit_counts(const void *d_keys, size_t n, unsigned *d_counts64, tcuscan_stream_t stream);
+extern "C" tcuscan_status_t tcuscan_internal_split4_pass(const void *d_keys, const void *d_vals, void *d_keys_out, void *d_vals_out, size_t n,
+                                                         int bit, const unsigned *d_hist4, void *d_ws, size_t ws_bytes,
+                                                         tcuscan_stream_t stream);
+
 namespace {
 
 constexpr int kThreads = 256;
@@ -93,6 +98,7 @@ __global__ __launch_bounds__(kThreads) void copy_u32_kernel(const uint32_t *__re
 unsigned blocks_for(size_t items) { return (unsigned)((items + kThreads - 1) / kThreads); }
 
 bool g_force_unfused_sort = false;      // measurement / test knob, see tcuscan_set_sort_fusion
+int g_sort_digit_bits = 2;              // fused passes: bits per pass (2 or 1), same knob
 
 }  // namespace
 
@@ -137,20 +143,26 @@ tcuscan_status_t tcuscan_split_radix_sort_u32(void *d_keys, void *d_vals, size_t
     uint32_t *src_v = (uint32_t *)d_vals, *dst_v = (uint32_t *)d_vals_tmp;
     int8_t *flags = (int8_t *)d_flags;
     int32_t *pos = (int32_t *)d_positions;
-    // Fused passes (the default): the mask and the positions are never written; the split kernel builds the mask from
-    // the keys, scans it and scatters in one go.  The number of keys with a 0 in each bit is taken once, up front (it
-    // does not change when the keys are permuted), into the first 32 words of d_positions.  The unfused form below
-    // (mask kernel, tcuscan_exclusive, scatter kernel) remains for n < 32 and as the plain statement of the reduction.
-    const bool fused = n >= 32 && !g_force_unfused_sort;
+    // Fused passes (the default): the mask and the positions are never written; the split kernel builds the flags from
+    // the keys, scans them and scatters in one go -- two bits (four buckets) per pass, and one more pass on a single bit
+    // when `bits` is odd.  How many keys have which digit at each position does not change when the keys are permuted:
+    // it is counted once, up front, into the first 96 words of d_positions (64 digit counts, 32 zero-bit counts).  The
+    // unfused form below (mask kernel, tcuscan_exclusive, scatter kernel, one bit per pass) remains for n < 96 and as
+    // the plain statement of the reduction.
+    const bool fused = n >= 96 && !g_force_unfused_sort;
     if (fused) {
-        unsigned *counts = (unsigned *)d_positions;
-        tcuscan_status_t st = tcuscan_internal_bit_zero_counts(d_keys, n, counts, stream);
+        unsigned *hist = (unsigned *)d_positions, *zeros = hist + 64;
+        tcuscan_status_t st = g_sort_digit_bits == 2 ? tcuscan_internal_digit_counts(d_keys, n, hist, stream) : TCUSCAN_OK;
+        if (st == TCUSCAN_OK && (g_sort_digit_bits != 2 || (bits & 1))) st = tcuscan_internal_bit_zero_counts(d_keys, n, zeros, stream);
         if (st != TCUSCAN_OK) return st;
-        for (int bit = 0; bit < bits; ++bit) {
-            st = tcuscan_internal_split_pass(src_k, src_v, dst_k, dst_v, n, bit, counts + bit, d_ws, ws_bytes, stream);
+        for (int bit = 0; bit < bits;) {
+            const int step = g_sort_digit_bits == 2 && bits - bit >= 2 ? 2 : 1;
+            st = step == 2 ? tcuscan_internal_split4_pass(src_k, src_v, dst_k, dst_v, n, bit, hist + 4 * (bit / 2), d_ws, ws_bytes, stream)
+                           : tcuscan_internal_split_pass(src_k, src_v, dst_k, dst_v, n, bit, zeros + bit, d_ws, ws_bytes, stream);
             if (st != TCUSCAN_OK) return st;
             uint32_t *t = src_k; src_k = dst_k; dst_k = t;
             t = src_v; src_v = dst_v; dst_v = t;
+            bit += step;
         }
     }
     for (int bit = 0; !fused && bit < bits; ++bit) {
@@ -187,6 +199,8 @@ tcuscan_status_t tcuscan_split_radix_sort_u32(void *d_keys, void *d_vals, size_t
 
 extern "C" tcuscan_status_t tcuscan_set_sort_fusion(int fused)
 {
+    if (fused < 0 || fused > 2) return TCUSCAN_ERR_INVALID_ARG;
     g_force_unfused_sort = fused == 0;
+    g_sort_digit_bits = fused == 2 ? 1 : 2;
     return TCUSCAN_OK;
 }

@@ -1048,6 +1048,245 @@ __global__ __launch_bounds__(64 * W) void split_kernel(Params P, SplitArgs S)
     if constexpr (VALS) split_scatter<NT, kSlot, true>(lane, Aop, g, val, S.vals_out, zero_at, one_at, zeros_run, rem, n, s_pack[wave]);
 }
 
+// ---- the split on two bits at once: four buckets per pass, half the passes
+//
+// The same reduction with a digit of two bits: keys go to four consecutive ranges by digit, old order kept inside
+// each.  Four flag vectors ("digit is d") would be four scans; they are one-hot, so two of them share a byte -- flag
+// of digit 0 (2) as 1, of digit 1 (3) as 64 -- and one product with the strict triangular blocks returns both counts
+// of earlier keys inside the granule (each below 16) in separate bit fields.  Granule totals come from the totals
+// operand the same way; from there on (16-lane scans, blocks, runs, workgroup) two counts travel in the halves of one
+// 32-bit word.  The carry chain has four values per tile: the four words share the tile's status slot, and the first
+// four wavefronts of a workgroup publish and look back for one digit each, at the same time.
+
+struct Split4Args {
+    const uint32_t *keys, *vals;       // vals may be null
+    uint32_t *keys_out, *vals_out;
+    const uint32_t *hist;              // number of keys with digit 0, 1, 2, 3 at this position (whole array)
+    int bit;                           // position of the digit's low bit
+};
+
+// 16 digit positions x 4 digits: counts[4 j + d] = keys whose bits 2j+1, 2j are d.  Digits 1, 2 and 3 are counted
+// (digit 0 is the rest): a key becomes three words with one bit per digit position ("the digit here is d", at the even
+// bits), and the bits of such a word are added up in byte-wide counters -- bits s, s + 8, s + 16, s + 24 in the four
+// bytes of one word, for s = 0, 2, 4, 6 -- which are emptied before a byte can overflow.
+__global__ __launch_bounds__(256) void digit_counts_kernel(const uint32_t *__restrict__ keys, size_t n, uint32_t *counts)
+{
+    __shared__ uint32_t s_cnt[64];
+    if (threadIdx.x < 64) s_cnt[threadIdx.x] = 0u;
+    __syncthreads();
+    uint32_t cnt[3][16];                                      // [digit - 1][position]
+#pragma unroll
+    for (int d = 0; d < 3; ++d)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) cnt[d][j] = 0u;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i0 < n; i0 += 255u * stride) {
+        uint32_t packed[3][4];                                // [digit - 1][s / 2]: byte b counts position s / 2 + 4 b
+#pragma unroll
+        for (int d = 0; d < 3; ++d)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) packed[d][k] = 0u;
+        size_t i = i0;
+#pragma unroll 4
+        for (int k = 0; k < 255 && i < n; ++k, i += stride) {
+            const uint32_t key = keys[i];
+            const uint32_t lo = key & 0x55555555u, hi = (key >> 1) & 0x55555555u;
+            const uint32_t is[3] = {lo & ~hi, hi & ~lo, lo & hi};
+#pragma unroll
+            for (int d = 0; d < 3; ++d)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) packed[d][q] += (is[d] >> (2 * q)) & 0x01010101u;
+        }
+#pragma unroll
+        for (int d = 0; d < 3; ++d)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) cnt[d][q + 4 * b] += (packed[d][q] >> (8 * b)) & 0xFFu;
+    }
+#pragma unroll
+    for (int d = 0; d < 3; ++d)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const uint32_t w = wave_sum(cnt[d][j]);
+            if ((threadIdx.x & 63) == 0 && w) atomicAdd(&s_cnt[4 * j + d + 1], w);
+        }
+    __syncthreads();
+    if (threadIdx.x < 64 && (threadIdx.x & 3) && s_cnt[threadIdx.x]) atomicAdd(&counts[threadIdx.x], s_cnt[threadIdx.x]);
+}
+
+// counts[4 j] = n - counts[4 j + 1] - counts[4 j + 2] - counts[4 j + 3]
+__global__ void digit_zero_counts_kernel(uint32_t *counts, size_t n)
+{
+    const int j = threadIdx.x;
+    if (j < 16) counts[4 * j] = (uint32_t)n - counts[4 * j + 1] - counts[4 * j + 2] - counts[4 * j + 3];
+}
+
+// The words x of one wavefront's run to the four ranges: digit d's from dst[at0[d]] on, cnt[d] of them.
+template <int NT, uint32_t SLOT>
+__device__ __forceinline__ void split4_scatter(int lane, const typename Tr<TCUSCAN_I8_I32>::AConst &Aex, const u32x4 (&gA)[NT],
+                                               const u32x4 (&gB)[NT], const u32x4 (&key)[NT][4], int bit, const u32x4 (&x)[NT][4],
+                                               uint32_t *dst, const uint64_t (&at0)[4], const uint32_t (&cnt)[4], uint32_t rem, uint64_t n,
+                                               uint32_t *slot)
+{
+    using T = Tr<TCUSCAN_I8_I32>;
+    const bool ragged = rem < NT * 1024u;
+    // the four ranges in the slot, each at the offset it has inside a 16-byte group of the destination
+    uint32_t a[4], q0[4], next = 0u;
+    uint32_t *gp[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        gp[d] = dst + at0[d];
+        a[d] = (uint32_t)((uintptr_t)gp[d] >> 2) & 3u;
+        q0[d] = next;
+        next = (next + a[d] + cnt[d] + 3u) & ~3u;
+    }
+    uint32_t runA = (q0[0] + a[0]) | ((q0[1] + a[1]) << 16);          // where the next key of digit 0 / 1 goes (two halves)
+    uint32_t runB = (q0[2] + a[2]) | ((q0[3] + a[3]) << 16);          // ... of digit 2 / 3
+    const uint32_t in_blk = 16u * (lane & 15) + 4u * (lane >> 4);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const u32x4 ttA = bits<u32x4>(T::totals(Aex, gA[t])), ttB = bits<u32x4>(T::totals(Aex, gB[t]));
+#pragma unroll
+        for (int p = 0; p < T::kBlocks; ++p) {
+            const i32x4 z = {0, 0, 0, 0};                            // same-digit keys before this one in its granule:
+            const i32x4 dA = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aex.a[p], bits<i32x4>(gA[t]), z, 0, 0, 0);   // result block p
+            const i32x4 dB = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aex.a[p], bits<i32x4>(gB[t]), z, 0, 0, 0);
+            const uint32_t pairA = (ttA[p] & 63u) | ((ttA[p] >> 6) << 16), pairB = (ttB[p] & 63u) | ((ttB[p] >> 6) << 16);
+            const uint32_t exA = row_exclusive_scan(pairA), exB = row_exclusive_scan(pairB);
+            const uint32_t blkA = uniform_from_lane(exA + pairA, 15), blkB = uniform_from_lane(exB + pairB, 15);
+            const uint32_t baseA = runA + exA, baseB = runB + exB;
+            const uint32_t idx0 = (uint32_t)t * 1024u + 256u * p + in_blk;
+            for (int r = 0; r < 4; ++r) {
+                const uint32_t d = (key[t][p][r] >> bit) & 3u;
+                const uint32_t w = (d & 2u) ? (uint32_t)dB[r] : (uint32_t)dA[r];
+                const uint32_t bs = (d & 2u) ? baseB : baseA;
+                uint32_t at = ((bs >> (16u * (d & 1u))) & 0xFFFFu) + ((w >> (6u * (d & 1u))) & 63u);
+                if (ragged && idx0 + r >= rem) at = SLOT - 1u;       // keys past the end go to the slot's spare last word,
+                at = at < SLOT - 1u ? at : SLOT - 1u;                // and so would a position beyond the ranges (never)
+                slot[at] = x[t][p][r];
+            }
+            runA += blkA; runB += blkB;
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const uint64_t room = at0[d] < n ? n - at0[d] : 0u;
+        split_store_range(lane, slot, q0[d], a[d], cnt[d], gp[d] - a[d], a[d] + (uint32_t)(room < 0x40000000ull ? room : 0x40000000ull));
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int NT, int W, bool VALS>
+__global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(VALS ? 1 : 4))) void split4_kernel(Params P, Split4Args S)
+{
+    constexpr int DT = TCUSCAN_I8_I32;
+    using T = Tr<DT>;
+    static_assert(T::kBlocks == 4 && W >= 4, "four result blocks of 256 per MFMA tile; one wavefront per digit for the carry chain");
+    constexpr uint32_t kEPW = NT * Geo<DT>::kTileElems;
+    constexpr uint32_t kSlot = kEPW + 32u;                      // four ranges, each shifted by up to 3 words and rounded up
+    static_assert(kSlot < 65536u, "slot positions travel in 16-bit halves");
+    __shared__ uint32_t s_cnt[W][2];
+    __shared__ uint32_t s_prefix[4];
+    __shared__ __attribute__((aligned(16))) uint32_t s_pack[W][kSlot];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const uint32_t tile = blockIdx.x, tag = P.tag;
+    const uint64_t n = P.cols;
+    const uint64_t base = ((uint64_t)tile * W + wave) * kEPW;                       // first key of this wavefront's run
+    const uint32_t rem = base < n ? (n - base < 0x40000000ull ? (uint32_t)(n - base) : 0x40000000u) : 0u;
+    const int bit = S.bit;
+    const uint32_t in_blk = 16u * (lane & 15) + 4u * (lane >> 4);
+    const bool ragged = rem < kEPW;
+
+    // ---- the keys; their digit flags as bytes for the two products; this lane's keys per digit
+    u32x4 key[NT][4], gA[NT], gB[NT];
+    load_run_words<NT>(lane, S.keys + base, rem, ~0u, key);
+    uint32_t c01 = 0u, c23 = 0u;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        uint32_t wA[4], wB[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            // the four digits in the four bytes of one word, then all four flag bytes at once: 1 or 64 by the digit's
+            // low bit, to stream B where its high bit is set and to stream A where it is not
+            uint32_t dig = 0u;
+            for (int i = 0; i < 4; ++i) dig |= ((key[t][p][i] >> bit) & 3u) << (8 * i);
+            uint32_t one = 0x01010101u + 63u * (dig & 0x01010101u);
+            if (ragged) {
+                const uint32_t idx0 = (uint32_t)t * 1024u + 256u * p + in_blk;            // keys past the end: no flag
+                const uint32_t have = idx0 >= rem ? 0u : (rem - idx0 >= 4u ? 4u : rem - idx0);
+                one &= have == 4u ? ~0u : ((1u << (8u * have)) - 1u);
+            }
+            const uint32_t high = ((dig >> 1) & 0x01010101u) * 255u;
+            wB[p] = one & high;
+            wA[p] = one ^ wB[p];
+            c01 += (uint32_t)__builtin_popcount(wA[p] & 0x01010101u) | ((uint32_t)__builtin_popcount(wA[p] & 0x40404040u) << 16);
+            c23 += (uint32_t)__builtin_popcount(wB[p] & 0x01010101u) | ((uint32_t)__builtin_popcount(wB[p] & 0x40404040u) << 16);
+        }
+        gA[t] = rows_transpose(wA);
+        gB[t] = rows_transpose(wB);
+    }
+    const uint32_t run01 = wave_sum(c01), run23 = wave_sum(c23);                    // at most 2048 per half
+    if (lane == 0) { s_cnt[wave][0] = run01; s_cnt[wave][1] = run23; }
+    __syncthreads();
+    uint32_t off01 = 0u, off23 = 0u, wg01 = 0u, wg23 = 0u;
+#pragma unroll
+    for (int w = 0; w < W; ++w) {
+        const uint32_t v01 = s_cnt[w][0], v23 = s_cnt[w][1];
+        if (w < wave) { off01 += v01; off23 += v23; }
+        wg01 += v01; wg23 += v23;
+    }
+    uint32_t prefix[4] = {0u, 0u, 0u, 0u};
+    if (P.num_tiles > 1) {
+        if (wave < 4) {                                          // digit `wave`: its word of the tile's status slot
+            uint64_t *row_status = (uint64_t *)(P.ws + 1) + wave;
+            const uint32_t mine = ((wave & 2 ? wg23 : wg01) >> (16 * (wave & 1))) & 0xFFFFu;
+            uint32_t pre = 0u;
+            if (tile == 0) {
+                if (lane == 0)
+                    __hip_atomic_store(row_status, status_word(tag, kStatePrefix, mine), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+                if (lane == 0)
+                    __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStateAggregate, mine),
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                pre = look_back<uint32_t>(row_status, (int)tile, tag, P.ws);
+                if (lane == 0)
+                    __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStatePrefix, pre + mine),
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            if (lane == 0) s_prefix[wave] = pre;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int d = 0; d < 4; ++d) prefix[d] = s_prefix[d];
+    }
+
+    // ---- where this run's keys of each digit go: behind the smaller digits of the whole array, the same digit of the
+    // tiles before, of the wavefronts before
+    uint64_t at0[4];
+    uint32_t cnt[4];
+    uint64_t bucket = 0u;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const uint32_t off = ((d & 2 ? off23 : off01) >> (16 * (d & 1))) & 0xFFFFu;
+        cnt[d] = (uint32_t)__builtin_amdgcn_readfirstlane((int)(((d & 2 ? run23 : run01) >> (16 * (d & 1))) & 0xFFFFu));
+        at0[d] = bucket + prefix[d] + off;
+        bucket += S.hist[d];
+    }
+    u32x4 val[VALS ? NT : 1][4];
+    if constexpr (VALS) load_run_words<NT>(lane, S.vals + base, rem, 0u, val);
+    const typename T::AConst Aex = T::make(lane, true, false);
+    split4_scatter<NT, kSlot>(lane, Aex, gA, gB, key, bit, key, S.keys_out, at0, cnt, rem, n, s_pack[wave]);
+    if constexpr (VALS) split4_scatter<NT, kSlot>(lane, Aex, gA, gB, key, bit, val, S.vals_out, at0, cnt, rem, n, s_pack[wave]);
+}
+
 struct CompactArgs {
     const uint8_t *mask;               // 0 / 1 bytes
     const uint32_t *values;
@@ -1889,6 +2128,41 @@ tcuscan_status_t tcuscan_internal_split_pass(const void *d_keys, const void *d_v
     S.zeros_total = d_zeros_total; S.bit = bit;
     void *args[] = {&P, &S};
     const void *fn = d_vals ? (const void *)split_kernel<NT, W, true> : (const void *)split_kernel<NT, W, false>;
+    return hipLaunchKernel(fn, dim3(P.num_tiles), dim3(64 * W), args, 0, s) == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
+}
+
+extern "C" __attribute__((visibility("hidden")))
+tcuscan_status_t tcuscan_internal_digit_counts(const void *d_keys, size_t n, unsigned *d_counts64, tcuscan_stream_t stream)
+{
+    hipStream_t s = (hipStream_t)stream;
+    if (launch_fill(d_counts64, 64 * sizeof(unsigned), s) != hipSuccess) return TCUSCAN_ERR_HIP;
+    const uint32_t *k = (const uint32_t *)d_keys; uint32_t *c = d_counts64;
+    void *args[] = {&k, &n, &c};
+    const unsigned grid = (unsigned)((n + 255) / 256 < 2048 ? (n + 255) / 256 : 2048);
+    if (hipLaunchKernel((const void *)digit_counts_kernel, dim3(grid), dim3(256), args, 0, s) != hipSuccess) return TCUSCAN_ERR_HIP;
+    void *args2[] = {&c, &n};
+    return hipLaunchKernel((const void *)digit_zero_counts_kernel, dim3(1), dim3(64), args2, 0, s) == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
+}
+
+extern "C" __attribute__((visibility("hidden")))
+tcuscan_status_t tcuscan_internal_split4_pass(const void *d_keys, const void *d_vals, void *d_keys_out, void *d_vals_out, size_t n, int bit,
+                                              const unsigned *d_hist4, void *d_ws, size_t ws_bytes, tcuscan_stream_t stream)
+{
+    // Keys alone: 8 wavefronts per workgroup, and the register allocator is held to 128 registers so that two workgroups
+    // (64.5 KiB of LDS each) share a compute unit (a dozen spilled registers; without the limit one workgroup: 208 us
+    // per pass of 2^26 keys against 177).  With payloads, which cost 32 registers more, 4 wavefronts per workgroup.
+    constexpr int NT = kFlagNT;
+    const int W = d_vals ? 4 : kFlagW;
+    hipStream_t s = (hipStream_t)stream;
+    Params P;
+    const tcuscan_status_t st = flag_kernel_params(P, n, (size_t)NT * W * 1024, d_ws, ws_bytes, s);
+    if (st != TCUSCAN_OK) return st;
+    Split4Args S;
+    S.keys = (const uint32_t *)d_keys; S.vals = (const uint32_t *)d_vals;
+    S.keys_out = (uint32_t *)d_keys_out; S.vals_out = (uint32_t *)d_vals_out;
+    S.hist = d_hist4; S.bit = bit;
+    void *args[] = {&P, &S};
+    const void *fn = d_vals ? (const void *)split4_kernel<NT, 4, true> : (const void *)split4_kernel<NT, kFlagW, false>;
     return hipLaunchKernel(fn, dim3(P.num_tiles), dim3(64 * W), args, 0, s) == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
 }
 

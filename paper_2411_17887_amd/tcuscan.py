@@ -217,8 +217,11 @@ def set_segmented_form(flat: bool) -> None:
     load().tcuscan_set_segmented_form(int(bool(flat)))
 
 
-def set_sort_fusion(fused: bool) -> None:
-    load().tcuscan_set_sort_fusion(int(bool(fused)))
+def set_sort_fusion(form: int) -> None:
+    """1: fused split passes on two bits (default); 2: fused passes on one bit; 0: mask kernel + scan + scatter kernel."""
+    rc = load().tcuscan_set_sort_fusion(int(form))
+    if rc != OK:
+        raise TcuscanError(rc, "tcuscan_set_sort_fusion")
 
 
 def split_radix_sort_u32(keys, keys_tmp, flags, positions, vals=None, vals_tmp=None, bits: int = 32, ws=None, stream=None) -> None:

@@ -90,12 +90,13 @@ def gpu_sort(k, vals=None, bits=32):
     return d_k.cpu().numpy().view(np.uint32), (d_v.cpu().numpy().view(np.uint32) if vals is not None else None)
 
 
-@pytest.fixture(params=[True, False], ids=["fused", "three_kernels"])
+@pytest.fixture(params=[1, 2, 0], ids=["fused_two_bits", "fused_one_bit", "three_kernels"])
 def sort_form(request):
-    """Both forms of a split pass: the fused kernel (default) and mask kernel + scan + scatter kernel."""
+    """The forms of a split pass: the fused kernels (two bits per pass, the default; one bit per pass) and mask kernel +
+    scan + scatter kernel."""
     tcuscan.set_sort_fusion(request.param)
     yield request.param
-    tcuscan.set_sort_fusion(True)
+    tcuscan.set_sort_fusion(1)
 
 
 @pytest.mark.parametrize("n", [1, 2, 17, 31, 32, 33, 255, 257, 1000, 8192 * 5 + 3, 32768, 32769, 5 * 32768 - 1, (1 << 20) + 1])
