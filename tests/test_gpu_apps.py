@@ -99,7 +99,7 @@ def sort_form(request):
     tcuscan.set_sort_fusion(1)
 
 
-@pytest.mark.parametrize("n", [1, 2, 17, 31, 32, 33, 255, 257, 1000, 8192 * 5 + 3, 32768, 32769, 5 * 32768 - 1, (1 << 20) + 1])
+@pytest.mark.parametrize("n", [1, 2, 17, 31, 32, 33, 95, 96, 97, 255, 257, 1000, 8192 * 5 + 3, 32768, 32769, 5 * 32768 - 1, (1 << 20) + 1])
 def test_sort_full_keys(n, sort_form):
     k = keys_u32(n, 2 * n + 1)
     got, _ = gpu_sort(k)
