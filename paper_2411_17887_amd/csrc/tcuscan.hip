@@ -2096,7 +2096,8 @@ tcuscan_status_t flag_kernel_params(Params &P, size_t n, size_t tile, void *d_ws
 }
 
 // 2048 elements per wavefront (their words stay in registers from the load to the scatter), 8 wavefronts: 16384 per
-// workgroup, 64.5 KiB of LDS, two workgroups per compute unit.
+// workgroup, 64.5 KiB of LDS, two workgroups per compute unit.  (1024 per wavefront, four workgroups and twice the
+// wavefronts per compute unit: compaction 407 us against 367, sort 3.76 ms against 3.11 -- more tiles, no better overlap.)
 constexpr int kFlagNT = 2, kFlagW = 8;
 
 }  // namespace
