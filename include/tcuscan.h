@@ -129,9 +129,10 @@ tcuscan_status_t tcuscan_scan(const void *d_in, void *d_out, size_t rows, size_t
  *   d_ws       tcuscan_segmented_workspace_bytes(rows, total, dt) bytes, zero-filled once like every workspace here
  * Four launches are enqueued: tiles per row, their exclusive scan (this library's int32 scan), one descriptor per
  * tile (its row's extent and its place in the row), the scan itself.  The tile size follows the average row length
- * total / rows.  Short rows (average below 2048 elements) of the two 32-bit types take another form, three
- * launches: the row starts become one bit per element, and the range the rows cover is scanned like one row whose
- * sums restart at every set bit (tcuscan_set_segmented_form(0) switches that form off).
+ * total / rows.  Short rows (average below 2048 / 4096 / 8192 elements for 32- / 16- / 8-bit inputs) take another
+ * form, three launches: the row starts become one bit per element, and the range the rows cover is scanned like one
+ * row whose sums restart at every set bit (reverse scans of 8- and 16-bit inputs excepted;
+ * tcuscan_set_segmented_form(0) switches that form off).
  * Rows may start at any element: a row is tiled from the 16-byte boundary at or below its start, the few elements in
  * front of it are read as zero and not written.  Offsets that decrease or leave [0, total] are not followed: the
  * workspace's fault word is set to 2 (see tcuscan_workspace_fault) and the results of the call are unspecified (such
@@ -158,7 +159,7 @@ size_t tcuscan_huge_tile_elems(tcuscan_dtype_t dt);
  */
 tcuscan_status_t tcuscan_set_tile_policy(int policy);
 
-/* 1 (default): short 32-bit rows of a segmented scan are scanned as one range with row-start bits; 0: every
+/* 1 (default): short rows of a segmented scan are scanned as one range with row-start bits; 0: every
  * row gets tiles of its own, as for all other segmented calls.  Process-wide; a measurement and test knob, results do
  * not depend on it beyond floating-point summation order. */
 tcuscan_status_t tcuscan_set_segmented_form(int flat);

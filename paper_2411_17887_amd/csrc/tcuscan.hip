@@ -1660,6 +1660,198 @@ __global__ __launch_bounds__(64 * W) void seg_flat_kernel(Params P, const long l
     }
 }
 
+// ---- the same for 8- and 16-bit inputs
+//
+// A lane's granule is 16 or 8 elements, and the matrix unit would hand its results to four or two other lanes (the
+// result layout that makes the plain scan's stores contiguous).  Here level 0 stays in the lane: the granule is
+// unpacked and scanned by dependent adds that drop what came before a row start, so the lane that knows a granule's
+// row starts also holds all of its results; everything above level 0 is the 32-bit kernel's.  The results -- four or two
+// 16-byte groups per lane -- change lanes just before the store (lane swaps: a 4 x 4 or 2 x 2 transpose between
+// registers and lane rows), so that every store instruction still writes 1 KiB of consecutive outputs.  Forward only.
+
+template <int DT> __device__ __forceinline__ typename Tr<DT>::acc narrow_elem(const u32x4 &g, int i);
+template <> __device__ __forceinline__ uint32_t narrow_elem<TCUSCAN_I8_I32>(const u32x4 &g, int i)
+{
+    return (uint32_t)(int32_t)(int8_t)(uint8_t)(g[i >> 2] >> (8 * (i & 3)));
+}
+template <> __device__ __forceinline__ float narrow_elem<TCUSCAN_BF16_F32>(const u32x4 &g, int i)
+{
+    return bits<float>((i & 1) ? (g[i >> 1] & 0xFFFF0000u) : (g[i >> 1] << 16));
+}
+template <> __device__ __forceinline__ float narrow_elem<TCUSCAN_F16_F32>(const u32x4 &g, int i)
+{
+    return (float)bits<_Float16>((uint16_t)(g[i >> 1] >> (16 * (i & 1))));
+}
+
+template <int DT, bool EXCL, int W>
+__global__ __launch_bounds__(64 * W) void seg_flat_narrow_kernel(Params P, const long long *offsets, const uint32_t *heads, uint32_t shift)
+{
+    using T = Tr<DT>;
+    using A = typename T::acc;
+    constexpr int G = T::kG, NT = 32 / G, Q = G / 4;           // elements per granule, granules per lane, 16-byte result groups per granule
+    static_assert(G == 8 || G == 16, "8- and 16-bit inputs");
+    constexpr uint32_t kTile = 64u * G;                        // elements one load instruction of the wavefront covers
+    constexpr uint32_t kEPW = NT * kTile;                      // 2048
+    constexpr uint32_t kWgElems = kEPW * W;
+    constexpr uint32_t kMask = (1u << G) - 1u;
+    __shared__ uint32_t s_sum[W], s_head[W];
+    __shared__ uint32_t s_bcast;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const uint32_t tile = blockIdx.x, tag = P.tag;
+
+    long long lo = offsets[0], hi = offsets[P.rows];
+    const long long total = (long long)P.cols;
+    lo = lo < 0 ? 0 : (lo > total ? total : lo);
+    hi = hi < lo ? lo : (hi > total ? total : hi);
+    const uint32_t lead = seg_lead<DT>(P, lo);
+    const uint64_t vlen = (uint64_t)(hi - lo) + lead;
+    if ((uint64_t)tile * kWgElems >= vlen) return;             // the grid is an upper bound
+    const uint64_t base = (uint64_t)tile * kWgElems + (uint64_t)wave * kEPW;
+    const Run R = make_seg_run<DT>(P, lo, (uint64_t)(hi - lo), lead, base);
+    const bool whole_in = __builtin_amdgcn_readfirstlane((int)(R.in_vec && R.lead == 0u && R.rem >= kEPW)) != 0;
+    const bool whole_out = __builtin_amdgcn_readfirstlane((int)(R.out_vec && R.lead == 0u && R.rem >= kEPW)) != 0;
+
+    u32x4 g[NT];
+    const uint64_t bit0 = (uint64_t)(lo - (long long)lead) + base + shift;     // bit of the run's first slot (a multiple of G)
+    uint32_t starts = 0u;                                      // G bits per granule, granule t in bits G t ..
+    if (whole_in) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) g[t] = *(const u32x4 *)(R.in + ((uint32_t)t * kTile + (uint32_t)G * lane) * T::kEsz);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const uint64_t b = bit0 + (uint32_t)t * kTile + (uint32_t)G * lane;
+            starts |= ((heads[b >> 5] >> (b & 31)) & kMask) << (G * t);
+        }
+    } else {
+        load_run<DT, NT, false, true>(R, lane, g);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const uint32_t e0 = (uint32_t)t * kTile + (uint32_t)G * lane;
+            if (e0 < R.rem) {
+                const uint64_t b = bit0 + e0;
+                starts |= ((heads[b >> 5] >> (b & 31)) & kMask) << (G * t);
+            }
+        }
+    }
+
+    // ---- the run by itself
+    A y[NT][G];
+    A carry = acc_from_bits<A>(0u);
+    bool run_open = true;
+    uint32_t open = 0u;
+    A in[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const uint32_t fb = (starts >> (G * t)) & kMask;
+        y[t][0] = narrow_elem<DT>(g[t], 0);
+#pragma unroll
+        for (int i = 1; i < G; ++i) {
+            const uint32_t keep = (uint32_t)(((int32_t)(~fb << (31 - i))) >> 31);           // all ones unless a row starts at i
+            y[t][i] = acc_add(acc_from_bits<A>(acc_bits(y[t][i - 1]) & keep), narrow_elem<DT>(g[t], i));
+        }
+        A v = y[t][G - 1];
+        uint32_t h = fb ? 1u : 0u;
+        seg_wave_inclusive(v, h);
+        const A vex = wave_shift_up(v);
+        const uint32_t hex = dpp0<kWaveShr1>(h);
+        in[t] = hex ? vex : acc_add(carry, vex);
+        if (run_open && !hex) open |= 1u << t;
+        carry = uniform_from_lane(fb ? y[t][G - 1] : acc_add(in[t], y[t][G - 1]), 63);
+        run_open = run_open && __ballot(fb != 0u) == 0ull;
+    }
+
+    // ---- the wavefronts of the workgroup, then the tiles before this one
+    if (lane == 0) { s_sum[wave] = acc_bits(carry); s_head[wave] = run_open ? 0u : 1u; }
+    __syncthreads();
+    A before = acc_from_bits<A>(0u), wg_sum = acc_from_bits<A>(0u);
+    bool before_head = false, wg_head = false;
+#pragma unroll
+    for (int w = 0; w < W; ++w) {
+        const A v = acc_from_bits<A>(s_sum[w]);
+        const bool hd = s_head[w] != 0u;
+        if (w < wave) { before = hd ? v : acc_add(before, v); before_head = before_head || hd; }
+        wg_sum = hd ? v : acc_add(wg_sum, v);
+        wg_head = wg_head || hd;
+    }
+    A prefix = acc_from_bits<A>(0u);
+    if (P.num_tiles > 1) {
+        uint64_t *row_status = (uint64_t *)(P.ws + 1);
+        if (wave == 0) {
+            if (tile == 0 || wg_head) {
+                if (lane == 0)
+                    __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStatePrefix, acc_bits(wg_sum)),
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (tile != 0) prefix = look_back<A>(row_status, (int)tile, tag, P.ws);
+            } else {
+                if (lane == 0)
+                    __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStateAggregate, acc_bits(wg_sum)),
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                prefix = look_back<A>(row_status, (int)tile, tag, P.ws);
+                if (lane == 0)
+                    __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStatePrefix, acc_bits(acc_add(prefix, wg_sum))),
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            if (lane == 0) s_bcast = acc_bits(prefix);
+        }
+        __syncthreads();
+        prefix = acc_from_bits<A>(s_bcast);
+    }
+    const A wave_in = before_head ? before : acc_add(prefix, before);
+
+    // ---- the open row's sum to the elements that no row start of their granule precedes; results change lanes; store
+    A last = wave_in;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const uint32_t fb = (starts >> (G * t)) & kMask;
+        const A add = ((open >> t) & 1u) ? acc_add(wave_in, in[t]) : in[t];
+        const uint32_t first = fb ? (uint32_t)__builtin_ctz(fb) : (uint32_t)G;
+#pragma unroll
+        for (int i = 0; i < G; ++i)
+            if ((uint32_t)i < first) y[t][i] = acc_add(add, y[t][i]);
+        u32x4 v[Q];
+        if constexpr (EXCL) {
+            A prev = wave_shift_up(y[t][G - 1]);
+            if (lane == 0) prev = last;
+            last = uniform_from_lane(y[t][G - 1], 63);
+            v[0][0] = (fb & 1u) ? 0u : acc_bits(prev);
+#pragma unroll
+            for (int i = 1; i < G; ++i) v[i >> 2][i & 3] = ((fb >> i) & 1u) ? 0u : acc_bits(y[t][i - 1]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < G; ++i) v[i >> 2][i & 3] = acc_bits(y[t][i]);
+        }
+        // group k of the lane in row P (16 lanes) / half P (32 lanes) <- group P of the lane in row / half k, same column
+        uint32_t e[Q];                                         // where the group this lane now holds in register k belongs
+        if constexpr (Q == 4) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const uint32_t col[4] = {v[0][w], v[1][w], v[2][w], v[3][w]};
+                const u32x4 tr = rows_transpose(col);
+                for (int k = 0; k < 4; ++k) v[k][w] = tr[k];
+            }
+            for (int k = 0; k < 4; ++k) e[k] = (uint32_t)t * kTile + 256u * k + 16u * (lane & 15) + 4u * (lane >> 4);
+        } else {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const auto sw = __builtin_amdgcn_permlane32_swap(v[0][w], v[1][w], false, false);
+                v[0][w] = sw[0]; v[1][w] = sw[1];
+            }
+            for (int k = 0; k < 2; ++k) e[k] = (uint32_t)t * kTile + 256u * k + 8u * (lane & 31) + 4u * (lane >> 5);
+        }
+#pragma unroll
+        for (int k = 0; k < Q; ++k) {
+            if (whole_out || (R.out_vec && e[k] + 4 <= R.rem && e[k] >= R.lead)) {
+                __builtin_nontemporal_store(v[k], (u32x4 *)(R.out + e[k] * 4));
+            } else {
+                for (int i = 0; i < 4; ++i)
+                    if (e[k] + i < R.rem && e[k] + i >= R.lead) ((uint32_t *)R.out)[e[k] + i] = v[k][i];
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------------- short-row kernel
 //
 // Rows no longer than one wavefront's run (NT tiles): every wavefront scans rows of its own -- no
@@ -1943,7 +2135,7 @@ bool seg_layout(int dt, size_t rows, size_t total, SegLayout &L)
     L.inner_off = up(L.rowmap_off + sizeof(TileDesc) * L.max_tiles);
     L.inner_bytes = tcuscan_workspace_bytes(1, rows + 1, TCUSCAN_I32_I32);
     L.heads_off = up(L.inner_off + L.inner_bytes);
-    L.heads_words = seg_tile_class(dt, rows, total) == kSegShort && in_size(dt) == 4 ? (total + 8) / 32 + 2 : 0;
+    L.heads_words = seg_tile_class(dt, rows, total) == kSegShort ? (total + 32) / 32 + 2 : 0;
     L.total_bytes = L.heads_off + 4 * L.heads_words;
     return true;
 }
@@ -1989,7 +2181,7 @@ tcuscan_status_t run_segmented_flat(const void *d_in, void *d_out, const long lo
     const size_t tiles = total / tile + 2;                       // the range is at most `total` long and starts less than a granule late
     if (tiles > L.max_tiles) return TCUSCAN_ERR_UNSUPPORTED;     // (never: the general layout counts smaller tiles)
     uint32_t *heads = (uint32_t *)((char *)d_ws + L.heads_off);
-    const uint32_t shift = (uint32_t)(((uintptr_t)d_in >> 2) & 3u);
+    const uint32_t shift = (uint32_t)(((uintptr_t)d_in / in_size(dt)) & (16 / in_size(dt) - 1));    // granules start at bit multiples of their length
     if (launch_fill(heads, 4 * L.heads_words, s) != hipSuccess) return TCUSCAN_ERR_HIP;
     {
         const long long *off = d_offsets; size_t r = rows, t = total; uint32_t sh = shift; WsHeader *h = (WsHeader *)d_ws;
@@ -2009,8 +2201,15 @@ tcuscan_status_t run_segmented_flat(const void *d_in, void *d_out, const long lo
         return TCUSCAN_ERR_HIP;
     const long long *off = d_offsets; const uint32_t *hd = heads; uint32_t sh = shift;
     void *args[] = {&P, &off, &hd, &sh};
-    const void *fn = dt == TCUSCAN_F32_F32 ? seg_flat_kernel_for<TCUSCAN_F32_F32>(exclusive != 0, reverse != 0)
-                                           : seg_flat_kernel_for<TCUSCAN_I32_I32>(exclusive != 0, reverse != 0);
+    const bool ex = exclusive != 0;
+    const void *fn;
+    switch (dt) {
+    case TCUSCAN_F32_F32:  fn = seg_flat_kernel_for<TCUSCAN_F32_F32>(ex, reverse != 0); break;
+    case TCUSCAN_I32_I32:  fn = seg_flat_kernel_for<TCUSCAN_I32_I32>(ex, reverse != 0); break;
+    case TCUSCAN_I8_I32:   fn = ex ? (const void *)seg_flat_narrow_kernel<TCUSCAN_I8_I32, true, kFlatW> : (const void *)seg_flat_narrow_kernel<TCUSCAN_I8_I32, false, kFlatW>; break;
+    case TCUSCAN_F16_F32:  fn = ex ? (const void *)seg_flat_narrow_kernel<TCUSCAN_F16_F32, true, kFlatW> : (const void *)seg_flat_narrow_kernel<TCUSCAN_F16_F32, false, kFlatW>; break;
+    default:               fn = ex ? (const void *)seg_flat_narrow_kernel<TCUSCAN_BF16_F32, true, kFlatW> : (const void *)seg_flat_narrow_kernel<TCUSCAN_BF16_F32, false, kFlatW>; break;
+    }
     return hipLaunchKernel(fn, dim3(P.num_tiles), dim3(64 * kFlatW), args, 0, s) == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
 }
 
@@ -2027,7 +2226,7 @@ tcuscan_status_t run_segmented(const void *d_in, void *d_out, const long long *d
     if (!d_ws || ws_bytes < L.total_bytes || ((uintptr_t)d_ws % 8) != 0) return TCUSCAN_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     const int cls = seg_tile_class(dt, rows, total);
-    if (L.heads_words && g_seg_flat.load(std::memory_order_relaxed))
+    if (L.heads_words && (in_size(dt) == 4 || !reverse) && g_seg_flat.load(std::memory_order_relaxed))
         return run_segmented_flat(d_in, d_out, d_offsets, rows, total, dt, exclusive, reverse, d_ws, L, s);
     const size_t tile = seg_tile_elems(dt, cls);
     int32_t *counts = (int32_t *)((char *)d_ws + L.counts_off);
