@@ -131,8 +131,7 @@ tcuscan_status_t tcuscan_scan(const void *d_in, void *d_out, size_t rows, size_t
  * tile (its row's extent and its place in the row), the scan itself.  The tile size follows the average row length
  * total / rows.  Short rows (average below 2048 / 4096 / 8192 elements for 32- / 16- / 8-bit inputs) take another
  * form, three launches: the row starts become one bit per element, and the range the rows cover is scanned like one
- * row whose sums restart at every set bit (reverse scans of 8- and 16-bit inputs excepted;
- * tcuscan_set_segmented_form(0) switches that form off).
+ * row whose sums restart at every set bit (tcuscan_set_segmented_form(0) switches that form off).
  * Rows may start at any element: a row is tiled from the 16-byte boundary at or below its start, the few elements in
  * front of it are read as zero and not written.  Offsets that decrease or leave [0, total] are not followed: the
  * workspace's fault word is set to 2 (see tcuscan_workspace_fault) and the results of the call are unspecified (such

@@ -1667,7 +1667,7 @@ __global__ __launch_bounds__(64 * W) void seg_flat_kernel(Params P, const long l
 // unpacked and scanned by dependent adds that drop what came before a row start, so the lane that knows a granule's
 // row starts also holds all of its results; everything above level 0 is the 32-bit kernel's.  The results -- four or two
 // 16-byte groups per lane -- change lanes just before the store (lane swaps: a 4 x 4 or 2 x 2 transpose between
-// registers and lane rows), so that every store instruction still writes 1 KiB of consecutive outputs.  Forward only.
+// registers and lane rows), so that every store instruction still writes 1 KiB of consecutive outputs.
 
 template <int DT> __device__ __forceinline__ typename Tr<DT>::acc narrow_elem(const u32x4 &g, int i);
 template <> __device__ __forceinline__ uint32_t narrow_elem<TCUSCAN_I8_I32>(const u32x4 &g, int i)
@@ -1683,7 +1683,7 @@ template <> __device__ __forceinline__ float narrow_elem<TCUSCAN_F16_F32>(const 
     return (float)bits<_Float16>((uint16_t)(g[i >> 1] >> (16 * (i & 1))));
 }
 
-template <int DT, bool EXCL, int W>
+template <int DT, bool EXCL, bool REV, int W>
 __global__ __launch_bounds__(64 * W) void seg_flat_narrow_kernel(Params P, const long long *offsets, const uint32_t *heads, uint32_t shift)
 {
     using T = Tr<DT>;
@@ -1707,10 +1707,13 @@ __global__ __launch_bounds__(64 * W) void seg_flat_narrow_kernel(Params P, const
     hi = hi < lo ? lo : (hi > total ? total : hi);
     const uint32_t lead = seg_lead<DT>(P, lo);
     const uint64_t vlen = (uint64_t)(hi - lo) + lead;
-    if ((uint64_t)tile * kWgElems >= vlen) return;             // the grid is an upper bound
-    const uint64_t base = (uint64_t)tile * kWgElems + (uint64_t)wave * kEPW;
+    const uint64_t tiles = (vlen + kWgElems - 1) / kWgElems;
+    if (tile >= tiles) return;                                 // the grid is an upper bound
+    const uint64_t pos = REV ? tiles - 1 - tile : tile;        // a reverse scan starts at the end of the range
+    const uint64_t base = pos * kWgElems + (uint64_t)wave * kEPW;
     const Run R = make_seg_run<DT>(P, lo, (uint64_t)(hi - lo), lead, base);
-    const bool whole_in = __builtin_amdgcn_readfirstlane((int)(R.in_vec && R.lead == 0u && R.rem >= kEPW)) != 0;
+    auto mem = [](int i) { return REV ? G - 1 - i : i; };      // processing order -> element of the granule (as in seg_flat_kernel)
+    const bool whole_in = !REV && __builtin_amdgcn_readfirstlane((int)(R.in_vec && R.lead == 0u && R.rem >= kEPW)) != 0;
     const bool whole_out = __builtin_amdgcn_readfirstlane((int)(R.out_vec && R.lead == 0u && R.rem >= kEPW)) != 0;
 
     u32x4 g[NT];
@@ -1725,13 +1728,19 @@ __global__ __launch_bounds__(64 * W) void seg_flat_narrow_kernel(Params P, const
             starts |= ((heads[b >> 5] >> (b & 31)) & kMask) << (G * t);
         }
     } else {
-        load_run<DT, NT, false, true>(R, lane, g);
+        load_run<DT, NT, REV, true>(R, lane, g);
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            const uint32_t e0 = (uint32_t)t * kTile + (uint32_t)G * lane;
+            const uint32_t e0 = slot_offset<DT, NT, REV>(t, lane);
             if (e0 < R.rem) {
                 const uint64_t b = bit0 + e0;
-                starts |= ((heads[b >> 5] >> (b & 31)) & kMask) << (G * t);
+                if constexpr (REV) {                           // row ends: a row starts one element further on; mirrored
+                    const uint64_t w = (uint64_t)heads[b >> 5] | ((uint64_t)heads[(b >> 5) + 1] << 32);
+                    const uint32_t ends = (uint32_t)(w >> ((b & 31) + 1)) & kMask;
+                    starts |= (__builtin_bitreverse32(ends) >> (32 - G)) << (G * t);
+                } else {
+                    starts |= ((heads[b >> 5] >> (b & 31)) & kMask) << (G * t);
+                }
             }
         }
     }
@@ -1745,11 +1754,11 @@ __global__ __launch_bounds__(64 * W) void seg_flat_narrow_kernel(Params P, const
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         const uint32_t fb = (starts >> (G * t)) & kMask;
-        y[t][0] = narrow_elem<DT>(g[t], 0);
+        y[t][0] = narrow_elem<DT>(g[t], mem(0));
 #pragma unroll
         for (int i = 1; i < G; ++i) {
             const uint32_t keep = (uint32_t)(((int32_t)(~fb << (31 - i))) >> 31);           // all ones unless a row starts at i
-            y[t][i] = acc_add(acc_from_bits<A>(acc_bits(y[t][i - 1]) & keep), narrow_elem<DT>(g[t], i));
+            y[t][i] = acc_add(acc_from_bits<A>(acc_bits(y[t][i - 1]) & keep), narrow_elem<DT>(g[t], mem(i)));
         }
         A v = y[t][G - 1];
         uint32_t h = fb ? 1u : 0u;
@@ -1774,6 +1783,18 @@ __global__ __launch_bounds__(64 * W) void seg_flat_narrow_kernel(Params P, const
         if (w < wave) { before = hd ? v : acc_add(before, v); before_head = before_head || hd; }
         wg_sum = hd ? v : acc_add(wg_sum, v);
         wg_head = wg_head || hd;
+    }
+    if constexpr (REV) {                                       // the wavefronts behind this one come first
+        before = acc_from_bits<A>(0u); wg_sum = acc_from_bits<A>(0u);
+        before_head = false; wg_head = false;
+#pragma unroll
+        for (int w = W - 1; w >= 0; --w) {
+            const A v = acc_from_bits<A>(s_sum[w]);
+            const bool hd = s_head[w] != 0u;
+            if (w > wave) { before = hd ? v : acc_add(before, v); before_head = before_head || hd; }
+            wg_sum = hd ? v : acc_add(wg_sum, v);
+            wg_head = wg_head || hd;
+        }
     }
     A prefix = acc_from_bits<A>(0u);
     if (P.num_tiles > 1) {
@@ -1815,12 +1836,12 @@ __global__ __launch_bounds__(64 * W) void seg_flat_narrow_kernel(Params P, const
             A prev = wave_shift_up(y[t][G - 1]);
             if (lane == 0) prev = last;
             last = uniform_from_lane(y[t][G - 1], 63);
-            v[0][0] = (fb & 1u) ? 0u : acc_bits(prev);
+            v[mem(0) >> 2][mem(0) & 3] = (fb & 1u) ? 0u : acc_bits(prev);
 #pragma unroll
-            for (int i = 1; i < G; ++i) v[i >> 2][i & 3] = ((fb >> i) & 1u) ? 0u : acc_bits(y[t][i - 1]);
+            for (int i = 1; i < G; ++i) v[mem(i) >> 2][mem(i) & 3] = ((fb >> i) & 1u) ? 0u : acc_bits(y[t][i - 1]);
         } else {
 #pragma unroll
-            for (int i = 0; i < G; ++i) v[i >> 2][i & 3] = acc_bits(y[t][i]);
+            for (int i = 0; i < G; ++i) v[mem(i) >> 2][mem(i) & 3] = acc_bits(y[t][i]);
         }
         // group k of the lane in row P (16 lanes) / half P (32 lanes) <- group P of the lane in row / half k, same column
         uint32_t e[Q];                                         // where the group this lane now holds in register k belongs
@@ -1831,14 +1852,14 @@ __global__ __launch_bounds__(64 * W) void seg_flat_narrow_kernel(Params P, const
                 const u32x4 tr = rows_transpose(col);
                 for (int k = 0; k < 4; ++k) v[k][w] = tr[k];
             }
-            for (int k = 0; k < 4; ++k) e[k] = (uint32_t)t * kTile + 256u * k + 16u * (lane & 15) + 4u * (lane >> 4);
+            for (int k = 0; k < 4; ++k) e[k] = slot_offset<DT, NT, REV>(t, 16 * k + (lane & 15)) + 4u * (lane >> 4);
         } else {
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
                 const auto sw = __builtin_amdgcn_permlane32_swap(v[0][w], v[1][w], false, false);
                 v[0][w] = sw[0]; v[1][w] = sw[1];
             }
-            for (int k = 0; k < 2; ++k) e[k] = (uint32_t)t * kTile + 256u * k + 8u * (lane & 31) + 4u * (lane >> 5);
+            for (int k = 0; k < 2; ++k) e[k] = slot_offset<DT, NT, REV>(t, 32 * k + (lane & 31)) + 4u * (lane >> 5);
         }
 #pragma unroll
         for (int k = 0; k < Q; ++k) {
@@ -2174,6 +2195,11 @@ template <int DT> const void *seg_flat_kernel_for(bool excl, bool rev)
     if (rev) return excl ? (const void *)seg_flat_kernel<DT, kFlatNT, true, true, kFlatW> : (const void *)seg_flat_kernel<DT, kFlatNT, false, true, kFlatW>;
     return excl ? (const void *)seg_flat_kernel<DT, kFlatNT, true, false, kFlatW> : (const void *)seg_flat_kernel<DT, kFlatNT, false, false, kFlatW>;
 }
+template <int DT> const void *seg_flat_narrow_kernel_for(bool excl, bool rev)
+{
+    if (rev) return excl ? (const void *)seg_flat_narrow_kernel<DT, true, true, kFlatW> : (const void *)seg_flat_narrow_kernel<DT, false, true, kFlatW>;
+    return excl ? (const void *)seg_flat_narrow_kernel<DT, true, false, kFlatW> : (const void *)seg_flat_narrow_kernel<DT, false, false, kFlatW>;
+}
 tcuscan_status_t run_segmented_flat(const void *d_in, void *d_out, const long long *d_offsets, size_t rows, size_t total, int dt,
                                     int exclusive, int reverse, void *d_ws, const SegLayout &L, hipStream_t s)
 {
@@ -2206,9 +2232,9 @@ tcuscan_status_t run_segmented_flat(const void *d_in, void *d_out, const long lo
     switch (dt) {
     case TCUSCAN_F32_F32:  fn = seg_flat_kernel_for<TCUSCAN_F32_F32>(ex, reverse != 0); break;
     case TCUSCAN_I32_I32:  fn = seg_flat_kernel_for<TCUSCAN_I32_I32>(ex, reverse != 0); break;
-    case TCUSCAN_I8_I32:   fn = ex ? (const void *)seg_flat_narrow_kernel<TCUSCAN_I8_I32, true, kFlatW> : (const void *)seg_flat_narrow_kernel<TCUSCAN_I8_I32, false, kFlatW>; break;
-    case TCUSCAN_F16_F32:  fn = ex ? (const void *)seg_flat_narrow_kernel<TCUSCAN_F16_F32, true, kFlatW> : (const void *)seg_flat_narrow_kernel<TCUSCAN_F16_F32, false, kFlatW>; break;
-    default:               fn = ex ? (const void *)seg_flat_narrow_kernel<TCUSCAN_BF16_F32, true, kFlatW> : (const void *)seg_flat_narrow_kernel<TCUSCAN_BF16_F32, false, kFlatW>; break;
+    case TCUSCAN_I8_I32:   fn = seg_flat_narrow_kernel_for<TCUSCAN_I8_I32>(ex, reverse != 0); break;
+    case TCUSCAN_F16_F32:  fn = seg_flat_narrow_kernel_for<TCUSCAN_F16_F32>(ex, reverse != 0); break;
+    default:               fn = seg_flat_narrow_kernel_for<TCUSCAN_BF16_F32>(ex, reverse != 0); break;
     }
     return hipLaunchKernel(fn, dim3(P.num_tiles), dim3(64 * kFlatW), args, 0, s) == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
 }
@@ -2226,7 +2252,7 @@ tcuscan_status_t run_segmented(const void *d_in, void *d_out, const long long *d
     if (!d_ws || ws_bytes < L.total_bytes || ((uintptr_t)d_ws % 8) != 0) return TCUSCAN_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     const int cls = seg_tile_class(dt, rows, total);
-    if (L.heads_words && (in_size(dt) == 4 || !reverse) && g_seg_flat.load(std::memory_order_relaxed))
+    if (L.heads_words && g_seg_flat.load(std::memory_order_relaxed))
         return run_segmented_flat(d_in, d_out, d_offsets, rows, total, dt, exclusive, reverse, d_ws, L, s);
     const size_t tile = seg_tile_elems(dt, cls);
     int32_t *counts = (int32_t *)((char *)d_ws + L.counts_off);

@@ -38,12 +38,11 @@ def run_segmented(x, kind, off, total=None, flags=0, ws=None, inplace=False):
 
 
 class forms:
-    """Both forms of the call where it has two (short rows: one range with row-start bits, or tiles of their own for
-    every row; 8- and 16-bit inputs have the first form for forward scans only); the library's default is restored
-    afterwards."""
+    """Both forms of the call (short rows: one range with row-start bits, or tiles of their own for every row); the
+    library's default is restored afterwards."""
 
-    def __init__(self, kind, flags=0):
-        self.which = [True, False] if kind in ("i32", "f32") or not flags & 2 else [True]
+    def __init__(self, kind=None, flags=0):
+        self.which = [True, False]
 
     def __iter__(self):
         try:
