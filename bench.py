@@ -218,6 +218,28 @@ def measure_variants(steps: int):
                                                  "gelems_per_s": covered / ms / 1e6, "frac_of_peak": covered * 8 / ms / 1e6 / PEAK_HBM_GBPS}
     finally:
         tcuscan.set_segmented_form(True)
+    # the same length mix on 2^27 bf16 elements (level 0 of the row-start-bits form runs in the lane for 8/16-bit inputs)
+    del xf, ws
+    m = 1 << 27
+    lens = rng.geometric(1.0 / 200, size=int(m / 199)) - 1
+    lens[:: 97] = 0
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    off = off[off <= m]
+    nrows = off.size - 1
+    covered = int(off[-1])
+    xb = torch.from_numpy(inputs.bf16_uniform_pm1(m, 7).view(np.int16)).cuda()
+    d_ob = torch.empty(m, dtype=torch.float32, device="cuda")
+    d_off = torch.from_numpy(off).cuda()
+    ws = tcuscan.new_segmented_workspace(nrows, m, "bf16")
+    for name, flat in (("segmented_short_rows_bf16", True), ("segmented_short_rows_bf16_own_tiles", False)):
+        tcuscan.set_segmented_form(flat)
+        try:
+            ms = timed(lambda: tcuscan.segmented(xb, d_ob, d_off, nrows, m, "bf16", ws=ws))
+        finally:
+            tcuscan.set_segmented_form(True)
+        res[name] = {"workload": f"{covered} bf16 -> fp32 elements in {nrows} rows, geometric lengths (mean 200), "
+                                 + ("one range with row-start bits" if flat else "tiles of its own for every row"),
+                     "ms": ms, "gelems_per_s": covered / ms / 1e6, "frac_of_peak": covered * 6 / ms / 1e6 / PEAK_HBM_GBPS}
     return res
 
 

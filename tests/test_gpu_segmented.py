@@ -287,3 +287,32 @@ def test_offsets_beyond_32_bits():
             got = d_out[start:stop].cpu().numpy().astype(np.int64)
             want = oracle.scan_int64(x, "i8") + ones_between(a, start)
             assert np.array_equal(got, want), f"row {r}, window at {start}"
+
+
+def test_short_rows_beyond_32_bits():
+    """2^32 + 100000 int8 elements in rows of 3000 (the form with row-start bits; element, bit and tile indices pass
+    2^31 and 2^32).  Checked against the oracle on windows that start at a row start: around 2^31, around 2^32, and the
+    end of the array; forward inclusive and reverse exclusive."""
+    import torch
+    n = (1 << 32) + 100_000
+    length = 3000
+    off = np.append(np.arange(0, n, length, dtype=np.int64), n)
+    rows = off.size - 1
+    g = torch.Generator(device="cuda").manual_seed(987)
+    d_in = torch.randint(0, 2, (n,), dtype=torch.int8, device="cuda", generator=g)
+    d_out = torch.empty(n, dtype=torch.int32, device="cuda")
+    d_off = torch.from_numpy(off).cuda()
+    ws = tcuscan.new_segmented_workspace(rows, n, "i8")
+    for flags in (0, 3):
+        d_out.fill_(GUARD)
+        tcuscan.segmented(d_in, d_out, d_off, rows, n, "i8", flags=flags, ws=ws)
+        torch.cuda.synchronize()
+        assert tcuscan.workspace_fault(ws) == 0
+        for centre in (1 << 31, 1 << 32, n):
+            r0 = max(0, min(rows, centre // length) - 300)
+            r1 = min(rows, r0 + 600)
+            a, b = int(off[r0]), int(off[r1])
+            x = d_in[a:b].cpu().numpy()
+            got = d_out[a:b].cpu().numpy()
+            assert oracle.compare_segments(x, "i8", off[r0:r1 + 1] - a, got, exclusive=bool(flags & 1), reverse=bool(flags & 2)) == (0, -1), \
+                f"flags {flags}, rows {r0}..{r1}"
