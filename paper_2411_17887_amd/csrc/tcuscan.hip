@@ -1477,6 +1477,55 @@ template <class A> __device__ __forceinline__ void seg_wave_inclusive(A &v, uint
     }
 }
 
+// From the pair of a wavefront's run -- (sum since the last row start, "there is a row start") -- to the sum the open row
+// brings to the start of that run: the pairs of the workgroup's wavefronts through LDS, combined in processing order
+// (a reverse scan takes the wavefronts from the last to the first), then the carry chain between tiles.  A tile that
+// contains a row start publishes its pair as a finished prefix at once: nothing before it matters to the tiles after
+// it; the others publish a total, look back, and publish their prefix.
+template <class A, int W, bool REV>
+__device__ __forceinline__ A seg_open_sum_before_run(const Params &P, uint32_t tile, int lane, int wave, A carry, bool run_open,
+                                                     uint32_t *s_sum, uint32_t *s_head, uint32_t *s_bcast)
+{
+    const uint32_t tag = P.tag;
+    if (lane == 0) { s_sum[wave] = acc_bits(carry); s_head[wave] = run_open ? 0u : 1u; }
+    __syncthreads();
+    A before = acc_from_bits<A>(0u), wg_sum = acc_from_bits<A>(0u);       // of the wavefronts before this one / of all of them
+    bool before_head = false, wg_head = false;
+#pragma unroll
+    for (int k = 0; k < W; ++k) {
+        const int w = REV ? W - 1 - k : k;
+        const A v = acc_from_bits<A>(s_sum[w]);
+        const bool hd = s_head[w] != 0u;
+        if (REV ? w > wave : w < wave) { before = hd ? v : acc_add(before, v); before_head = before_head || hd; }
+        wg_sum = hd ? v : acc_add(wg_sum, v);
+        wg_head = wg_head || hd;
+    }
+    A prefix = acc_from_bits<A>(0u);
+    if (P.num_tiles > 1) {
+        uint64_t *row_status = (uint64_t *)(P.ws + 1);
+        if (wave == 0) {
+            if (tile == 0 || wg_head) {
+                if (lane == 0)
+                    __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStatePrefix, acc_bits(wg_sum)),
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (tile != 0) prefix = look_back<A>(row_status, (int)tile, tag, P.ws);
+            } else {
+                if (lane == 0)
+                    __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStateAggregate, acc_bits(wg_sum)),
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                prefix = look_back<A>(row_status, (int)tile, tag, P.ws);
+                if (lane == 0)
+                    __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStatePrefix, acc_bits(acc_add(prefix, wg_sum))),
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            if (lane == 0) *s_bcast = acc_bits(prefix);
+        }
+        __syncthreads();
+        prefix = acc_from_bits<A>(*s_bcast);
+    }
+    return before_head ? before : acc_add(prefix, before);
+}
+
 template <int DT, int NT, bool EXCL, bool REV, int W>
 __global__ __launch_bounds__(64 * W) void seg_flat_kernel(Params P, const long long *offsets, const uint32_t *heads, uint32_t shift)
 {
@@ -1490,7 +1539,7 @@ __global__ __launch_bounds__(64 * W) void seg_flat_kernel(Params P, const long l
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const uint32_t tile = blockIdx.x, tag = P.tag;
+    const uint32_t tile = blockIdx.x;
 
     // the range the rows cover, clamped to the arrays (offsets that leave them have raised the fault word already)
     long long lo = offsets[0], hi = offsets[P.rows];
@@ -1576,55 +1625,8 @@ __global__ __launch_bounds__(64 * W) void seg_flat_kernel(Params P, const long l
         run_open = run_open && __ballot(fb != 0u) == 0ull;
     }
 
-    // ---- the wavefronts of the workgroup, then the tiles before this one
-    if (lane == 0) { s_sum[wave] = acc_bits(carry); s_head[wave] = run_open ? 0u : 1u; }
-    __syncthreads();
-    A before = acc_from_bits<A>(0u), wg_sum = acc_from_bits<A>(0u);       // of the wavefronts before this one / of all of them
-    bool before_head = false, wg_head = false;
-#pragma unroll
-    for (int w = 0; w < W; ++w) {
-        const A v = acc_from_bits<A>(s_sum[w]);
-        const bool hd = s_head[w] != 0u;
-        if (w < wave) { before = hd ? v : acc_add(before, v); before_head = before_head || hd; }
-        wg_sum = hd ? v : acc_add(wg_sum, v);
-        wg_head = wg_head || hd;
-    }
-    if constexpr (REV) {                                       // the wavefronts behind this one come first
-        before = acc_from_bits<A>(0u); wg_sum = acc_from_bits<A>(0u);
-        before_head = false; wg_head = false;
-#pragma unroll
-        for (int w = W - 1; w >= 0; --w) {
-            const A v = acc_from_bits<A>(s_sum[w]);
-            const bool hd = s_head[w] != 0u;
-            if (w > wave) { before = hd ? v : acc_add(before, v); before_head = before_head || hd; }
-            wg_sum = hd ? v : acc_add(wg_sum, v);
-            wg_head = wg_head || hd;
-        }
-    }
-    A prefix = acc_from_bits<A>(0u);
-    if (P.num_tiles > 1) {
-        uint64_t *row_status = (uint64_t *)(P.ws + 1);
-        if (wave == 0) {
-            if (tile == 0 || wg_head) {                        // nothing before this tile matters to the tiles after it
-                if (lane == 0)
-                    __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStatePrefix, acc_bits(wg_sum)),
-                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (tile != 0) prefix = look_back<A>(row_status, (int)tile, tag, P.ws);
-            } else {
-                if (lane == 0)
-                    __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStateAggregate, acc_bits(wg_sum)),
-                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                prefix = look_back<A>(row_status, (int)tile, tag, P.ws);
-                if (lane == 0)
-                    __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStatePrefix, acc_bits(acc_add(prefix, wg_sum))),
-                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-            if (lane == 0) s_bcast = acc_bits(prefix);
-        }
-        __syncthreads();
-        prefix = acc_from_bits<A>(s_bcast);
-    }
-    const A wave_in = before_head ? before : acc_add(prefix, before);     // the open row's sum at the start of this run
+    // ---- the wavefronts of the workgroup, then the tiles before this one: the open row's sum at the start of this run
+    const A wave_in = seg_open_sum_before_run<A, W, REV>(P, tile, lane, wave, carry, run_open, s_sum, s_head, &s_bcast);
 
     // ---- what the open row brings, to the elements that no row start of their granule precedes; store
     A last = wave_in;                                          // the inclusive result of the element before the granule (exclusive scans)
@@ -1699,7 +1701,7 @@ __global__ __launch_bounds__(64 * W) void seg_flat_narrow_kernel(Params P, const
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const uint32_t tile = blockIdx.x, tag = P.tag;
+    const uint32_t tile = blockIdx.x;
 
     long long lo = offsets[0], hi = offsets[P.rows];
     const long long total = (long long)P.cols;
@@ -1771,55 +1773,8 @@ __global__ __launch_bounds__(64 * W) void seg_flat_narrow_kernel(Params P, const
         run_open = run_open && __ballot(fb != 0u) == 0ull;
     }
 
-    // ---- the wavefronts of the workgroup, then the tiles before this one
-    if (lane == 0) { s_sum[wave] = acc_bits(carry); s_head[wave] = run_open ? 0u : 1u; }
-    __syncthreads();
-    A before = acc_from_bits<A>(0u), wg_sum = acc_from_bits<A>(0u);
-    bool before_head = false, wg_head = false;
-#pragma unroll
-    for (int w = 0; w < W; ++w) {
-        const A v = acc_from_bits<A>(s_sum[w]);
-        const bool hd = s_head[w] != 0u;
-        if (w < wave) { before = hd ? v : acc_add(before, v); before_head = before_head || hd; }
-        wg_sum = hd ? v : acc_add(wg_sum, v);
-        wg_head = wg_head || hd;
-    }
-    if constexpr (REV) {                                       // the wavefronts behind this one come first
-        before = acc_from_bits<A>(0u); wg_sum = acc_from_bits<A>(0u);
-        before_head = false; wg_head = false;
-#pragma unroll
-        for (int w = W - 1; w >= 0; --w) {
-            const A v = acc_from_bits<A>(s_sum[w]);
-            const bool hd = s_head[w] != 0u;
-            if (w > wave) { before = hd ? v : acc_add(before, v); before_head = before_head || hd; }
-            wg_sum = hd ? v : acc_add(wg_sum, v);
-            wg_head = wg_head || hd;
-        }
-    }
-    A prefix = acc_from_bits<A>(0u);
-    if (P.num_tiles > 1) {
-        uint64_t *row_status = (uint64_t *)(P.ws + 1);
-        if (wave == 0) {
-            if (tile == 0 || wg_head) {
-                if (lane == 0)
-                    __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStatePrefix, acc_bits(wg_sum)),
-                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (tile != 0) prefix = look_back<A>(row_status, (int)tile, tag, P.ws);
-            } else {
-                if (lane == 0)
-                    __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStateAggregate, acc_bits(wg_sum)),
-                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                prefix = look_back<A>(row_status, (int)tile, tag, P.ws);
-                if (lane == 0)
-                    __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStatePrefix, acc_bits(acc_add(prefix, wg_sum))),
-                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-            if (lane == 0) s_bcast = acc_bits(prefix);
-        }
-        __syncthreads();
-        prefix = acc_from_bits<A>(s_bcast);
-    }
-    const A wave_in = before_head ? before : acc_add(prefix, before);
+    // ---- the wavefronts of the workgroup, then the tiles before this one: the open row's sum at the start of this run
+    const A wave_in = seg_open_sum_before_run<A, W, REV>(P, tile, lane, wave, carry, run_open, s_sum, s_head, &s_bcast);
 
     // ---- the open row's sum to the elements that no row start of their granule precedes; results change lanes; store
     A last = wave_in;
