@@ -1079,23 +1079,33 @@ __global__ __launch_bounds__(256) void digit_counts_kernel(const uint32_t *__res
     for (int d = 0; d < 3; ++d)
 #pragma unroll
         for (int j = 0; j < 16; ++j) cnt[d][j] = 0u;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i0 < n; i0 += 255u * stride) {
+    // four keys per step (one 16-byte load per lane; the array is 16-byte aligned), the last n mod 4 keys by one thread
+    const size_t stride = (size_t)gridDim.x * blockDim.x, quads = n / 4;
+    const u32x4 *keys4 = (const u32x4 *)keys;
+    for (size_t i0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i0 < quads + 1; i0 += 63u * stride) {
         uint32_t packed[3][4];                                // [digit - 1][s / 2]: byte b counts position s / 2 + 4 b
 #pragma unroll
         for (int d = 0; d < 3; ++d)
 #pragma unroll
             for (int k = 0; k < 4; ++k) packed[d][k] = 0u;
         size_t i = i0;
-#pragma unroll 4
-        for (int k = 0; k < 255 && i < n; ++k, i += stride) {
-            const uint32_t key = keys[i];
-            const uint32_t lo = key & 0x55555555u, hi = (key >> 1) & 0x55555555u;
-            const uint32_t is[3] = {lo & ~hi, hi & ~lo, lo & hi};
+#pragma unroll 2
+        for (int k = 0; k < 63 && i < quads + 1; ++k, i += stride) {          // 63 x 4 keys: a byte counter stays below 256
+            u32x4 kq = {0u, 0u, 0u, 0u};
+            uint32_t have = 4u;
+            if (i < quads) kq = keys4[i];
+            else { have = (uint32_t)(n - 4 * quads); for (uint32_t j = 0; j < have; ++j) kq[j] = keys[4 * quads + j]; }
 #pragma unroll
-            for (int d = 0; d < 3; ++d)
+            for (int j = 0; j < 4; ++j) {
+                if ((uint32_t)j >= have) break;
+                const uint32_t key = kq[j];
+                const uint32_t lo = key & 0x55555555u, hi = (key >> 1) & 0x55555555u;
+                const uint32_t is[3] = {lo & ~hi, hi & ~lo, lo & hi};
 #pragma unroll
-                for (int q = 0; q < 4; ++q) packed[d][q] += (is[d] >> (2 * q)) & 0x01010101u;
+                for (int d = 0; d < 3; ++d)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) packed[d][q] += (is[d] >> (2 * q)) & 0x01010101u;
+            }
         }
 #pragma unroll
         for (int d = 0; d < 3; ++d)
