@@ -126,3 +126,24 @@ def test_new_entry_points_reject_bad_arguments_on_the_host():
     for s, n in [(2, 16), (8, 64), (4, 5), (32, 1000), (16, 0)]:
         assert call("tcuscan_matmulscan_levels_radix", FAKE, FAKE + (1 << 30), n, tcuscan.I32_I32, s, -1, 0, 0) == tcuscan.ERR_UNSUPPORTED
     assert call("tcuscan_matmulscan_levels_radix", 0, FAKE, 16, tcuscan.I32_I32, 4, -1, 0, 0) == tcuscan.ERR_INVALID_ARG
+
+
+def test_process_wide_knobs():
+    """The measurement / test knobs are host-side settings: valid values are accepted, anything else is refused, and
+    the defaults are put back."""
+    try:
+        for form in (0, 1, 2):
+            assert call("tcuscan_set_sort_fusion", form) == tcuscan.OK
+        for form in (-1, 3, 100):
+            assert call("tcuscan_set_sort_fusion", form) == tcuscan.ERR_INVALID_ARG
+        with pytest.raises(tcuscan.TcuscanError):
+            tcuscan.set_sort_fusion(7)
+        for flat in (0, 1, 5):                                   # any non-zero value means "on"
+            assert call("tcuscan_set_segmented_form", flat) == tcuscan.OK
+        for policy in (0, 1, 2, 3):
+            assert call("tcuscan_set_tile_policy", policy) == tcuscan.OK
+        assert call("tcuscan_set_tile_policy", 4) == tcuscan.ERR_INVALID_ARG
+    finally:
+        tcuscan.set_sort_fusion(1)
+        tcuscan.set_segmented_form(True)
+        call("tcuscan_set_tile_policy", 0)
