@@ -882,16 +882,15 @@ __device__ __forceinline__ u32x4 load_block_words(const uint32_t *run, bool vec,
 __device__ __forceinline__ void split_store_range(int lane, const uint32_t *slot, uint32_t q0, uint32_t a, uint32_t cnt,
                                                   uint32_t *gq, uint32_t lim)
 {
-    const uint32_t end = (a + cnt < lim ? a + cnt : lim), groups = (end + 3u) >> 2;
-    for (uint32_t j = (uint32_t)lane; j < groups; j += 64u) {
-        const u32x4 v = *(const u32x4 *)(slot + q0 + 4u * j);
-        const uint32_t lo = 4u * j;
-        if (lo >= a && lo + 4u <= end) {
-            __builtin_nontemporal_store(v, (u32x4 *)(gq + lo));
-        } else {
-            for (int i = 0; i < 4; ++i)
-                if (lo + i >= a && lo + i < end) gq[lo + i] = v[i];
-        }
+    const uint32_t end = (a + cnt < lim ? a + cnt : lim);
+    const uint32_t first = (a + 3u) >> 2, past = end >> 2;               // whole groups: first .. past - 1
+    for (uint32_t j = first + (uint32_t)lane; j < past; j += 64u)
+        __builtin_nontemporal_store(*(const u32x4 *)(slot + q0 + 4u * j), (u32x4 *)(gq + 4u * j));
+    // the ragged group in front (words a .. 3) and the one behind (words 4 past ..): lanes 0 .. 3 and 4 .. 7, a word each
+    if (lane < 8) {
+        const uint32_t i = lane < 4 ? (uint32_t)lane : 4u * past + (uint32_t)(lane - 4);
+        const bool mine = lane < 4 ? (i >= a && i < end && first == 1u) : (i < end && past >= first);
+        if (mine) gq[i] = slot[q0 + i];
     }
 }
 
@@ -907,6 +906,7 @@ __device__ __forceinline__ void split_scatter(int lane, const typename Tr<TCUSCA
     using T = Tr<TCUSCAN_I8_I32>;
     constexpr uint32_t kEPW = NT * 1024u;
     const uint32_t valid = rem < kEPW ? rem : kEPW;
+    const bool ragged = rem < kEPW;
     uint32_t *dz = dst + zero_at, *d1 = dst + one_at;
     const uint32_t a0 = (uint32_t)((uintptr_t)dz >> 2) & 3u, a1 = (uint32_t)((uintptr_t)d1 >> 2) & 3u;
     const uint32_t base1 = ((a0 + zeros_run + 3u) & ~3u) + a1;              // where the ones start in the slot
@@ -925,8 +925,14 @@ __device__ __forceinline__ void split_scatter(int lane, const typename Tr<TCUSCA
             const uint32_t idx0 = (uint32_t)t * 1024u + 256u * p + in_blk;
             for (int r = 0; r < 4; ++r) {
                 const uint32_t w = (uint32_t)d[p][r], zb = before + ex + (w >> 1), idx = idx0 + r;
-                const uint32_t at = (w & 1u) ? a0 + zb : base1 + (idx - zb);
-                if (idx < rem && at < SLOT && (ONES || (w & 1u))) slot[at] = x[t][p][r];
+                uint32_t at = (w & 1u) ? a0 + zb : base1 + (idx - zb);
+                if constexpr (ONES) {                          // every key has a place: no branch around the write;
+                    if (ragged && idx >= rem) at = SLOT - 1u;  // keys past the end go to the slot's spare last word,
+                    at = at < SLOT - 1u ? at : SLOT - 1u;      // and so would a position beyond the ranges (never)
+                    slot[at] = x[t][p][r];
+                } else {
+                    if (idx < rem && at < SLOT && (w & 1u)) slot[at] = x[t][p][r];
+                }
             }
             before += zeros;
         }
@@ -1218,7 +1224,7 @@ __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(VALS ? 1
     // ---- the keys; their digit flags as bytes for the two products; this lane's keys per digit
     u32x4 key[NT][4], gA[NT], gB[NT];
     load_run_words<NT>(lane, S.keys + base, rem, ~0u, key);
-    uint32_t c01 = 0u, c23 = 0u;
+    uint32_t sumA = 0u, sumB = 0u;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         uint32_t wA[4], wB[4];
@@ -1237,12 +1243,14 @@ __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(VALS ? 1
             const uint32_t high = ((dig >> 1) & 0x01010101u) * 255u;
             wB[p] = one & high;
             wA[p] = one ^ wB[p];
-            c01 += (uint32_t)__builtin_popcount(wA[p] & 0x01010101u) | ((uint32_t)__builtin_popcount(wA[p] & 0x40404040u) << 16);
-            c23 += (uint32_t)__builtin_popcount(wB[p] & 0x01010101u) | ((uint32_t)__builtin_popcount(wB[p] & 0x40404040u) << 16);
+            sumA = __builtin_amdgcn_udot4(wA[p], 0x01010101u, sumA, false);    // bytes added up: digit 0 (2) counts 1, digit 1 (3) counts 64
+            sumB = __builtin_amdgcn_udot4(wB[p], 0x01010101u, sumB, false);
         }
         gA[t] = rows_transpose(wA);
         gB[t] = rows_transpose(wB);
     }
+    static_assert(NT * 16 < 64, "a lane's keys per digit stay below 64: the two counts of a byte sum do not mix");
+    const uint32_t c01 = (sumA & 63u) | ((sumA >> 6) << 16), c23 = (sumB & 63u) | ((sumB >> 6) << 16);
     const uint32_t run01 = wave_sum(c01), run23 = wave_sum(c23);                    // at most 2048 per half
     if (lane == 0) { s_cnt[wave][0] = run01; s_cnt[wave][1] = run23; }
     __syncthreads();
