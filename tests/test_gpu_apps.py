@@ -134,3 +134,25 @@ def test_sort_special_inputs(sort_form):
         assert np.array_equal(got, np.sort(k))
     g, _ = gpu_sort(keys_u32(1000, 1), bits=0)
     assert np.array_equal(g, keys_u32(1000, 1))              # zero passes: untouched
+
+
+def test_sort_random_sizes_bits_and_forms():
+    """Seeded random cases: sizes around the tile sizes, 1 .. 32 bits (odd counts end with a one-bit pass), keys with few
+    distinct values, with and without payloads, both fused forms; against numpy's stable sort."""
+    rng = np.random.default_rng(1711)
+    try:
+        for case in range(40):
+            n = int(rng.choice([97, 1000, 16383, 16384, 16385, 100000, (1 << 20) + 7])) + int(rng.integers(0, 50))
+            bits = int(rng.integers(1, 33))
+            k = keys_u32(n, 3000 + case)
+            if rng.random() < 0.3:
+                k = k & np.uint32(rng.integers(1, 1 << 16))
+            payload = np.arange(n, dtype=np.uint32) if rng.random() < 0.5 else None
+            tcuscan.set_sort_fusion(1 + case % 2)
+            gk, gv = gpu_sort(k, payload, bits=bits)
+            mask = np.uint32((1 << bits) - 1) if bits < 32 else np.uint32(0xFFFFFFFF)
+            order = np.argsort(k & mask, kind="stable")
+            assert np.array_equal(gk, k[order]), f"case {case}: n {n}, {bits} bits"
+            assert payload is None or np.array_equal(gv, payload[order]), f"case {case}: payloads"
+    finally:
+        tcuscan.set_sort_fusion(1)

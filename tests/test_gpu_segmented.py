@@ -316,3 +316,40 @@ def test_short_rows_beyond_32_bits():
             got = d_out[a:b].cpu().numpy()
             assert oracle.compare_segments(x, "i8", off[r0:r1 + 1] - a, got, exclusive=bool(flags & 1), reverse=bool(flags & 2)) == (0, -1), \
                 f"flags {flags}, rows {r0}..{r1}"
+
+
+def test_random_layouts_and_misaligned_pointers():
+    """Seeded random cases: dtype, number of rows, length mix (with empty rows and a long one now and then), first
+    offset, flags, and base pointers of input and output that are not 16-byte aligned; both forms; bit-exact (integer
+    inputs and integer-valued floats); nothing outside the rows is written, in front of the output buffer included."""
+    import torch
+    rng = np.random.default_rng(2411)
+    gen = {"i32": inputs.int32_full, "i8": inputs.int8_full, "f32": inputs.tri_f32, "f16": inputs.tri_f16, "bf16": inputs.tri_bf16_bits}
+    for case in range(120):
+        kind = KINDS[case % 5]
+        rows = int(rng.integers(1, 3000))
+        mean = int(rng.choice([1, 3, 10, 40, 200, 900, 3000]))
+        lens = rng.geometric(1.0 / mean, size=rows) - 1
+        if rng.random() < 0.3:
+            lens[rng.integers(0, rows)] = int(rng.integers(0, 60000))
+        start = int(rng.integers(0, 40))
+        off = offsets_from(lens, start=start)
+        pad_in, pad_out = int(rng.integers(0, 8)), int(rng.integers(0, 8))
+        n = int(off[-1]) + int(rng.integers(0, 20))
+        if n == 0:
+            continue
+        flags = int(rng.integers(0, 4))
+        x = gen[kind](n + pad_in, 1000 + case)
+        d_in = to_device(x, kind)[pad_in:]
+        d_full = torch.full((n + pad_out,), GUARD, dtype=out_dtype(kind), device="cuda")
+        d_out = d_full[pad_out:]
+        d_off = torch.from_numpy(off).cuda()
+        ws = tcuscan.new_segmented_workspace(rows, n, kind)
+        for flat in forms():
+            d_full.fill_(GUARD)
+            tcuscan.segmented(d_in, d_out, d_off, rows, n, kind, flags=flags, ws=ws)
+            torch.cuda.synchronize()
+            assert tcuscan.workspace_fault(ws) == 0
+            what = f"case {case}: {kind}, {rows} rows of mean {mean}, flags {flags}, pads {pad_in}/{pad_out}, flat {flat}"
+            check(x[pad_in:], kind, off, d_out.cpu().numpy(), bool(flags & 1), bool(flags & 2), exact_float=True)
+            assert np.all(d_full[:pad_out].cpu().numpy() == GUARD), what
