@@ -62,7 +62,7 @@ def test_fused_compaction_without_a_positions_buffer(n):
             assert c == int(mm.sum()) and np.array_equal(g, v[mm != 0])
 
 
-def test_fused_compaction_every_tile_size():
+def test_fused_compaction_whatever_the_tile_policy():
     try:
         for policy in (1, 2, 3):
             tcuscan.set_tile_policy(policy)
