@@ -519,7 +519,9 @@ __device__ __forceinline__ void load_run(const Run &R, int lane, u32x4 (&g)[NT])
     for (int t = 0; t < NT; ++t) {
         const uint32_t e0 = slot_offset<DT, NT, REV>(t, lane);                            // element offset inside the run
         if (R.in_vec && e0 + kG <= R.rem && (!SEG || e0 >= R.lead)) {
-            g[t] = *(const u32x4 *)(R.in + e0 * T::kEsz);
+            // (measured: non-temporal loads gain 3 % on the 32-bit chains and cost 10 % on the 8- and 16-bit ones)
+            if constexpr (T::kEsz == 4) g[t] = __builtin_nontemporal_load((const u32x4 *)(R.in + e0 * T::kEsz));
+            else g[t] = *(const u32x4 *)(R.in + e0 * T::kEsz);
         } else if (SEG && R.in_vec && e0 + kG <= R.cap) {
             // Segmented scans: a granule that straddles a row boundary still lies inside the caller's array; it is
             // loaded whole and the neighbouring row's elements are masked out (rows are short there, and an element-wise
