@@ -37,7 +37,7 @@ DESCR = {
 }
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the same
 # counters on a plain 1 GiB device copy (fetch x2.000, write x1.000); profiles/scan_kernel_bench_default.md.
-MEASURED_TRAFFIC_BYTES = {"C5": 1626876316, "C3": 1350951745, "C4": 805484577, "C2": 101643438}
+MEASURED_TRAFFIC_BYTES = {"C5": 1627055368, "C3": 1350949057, "C4": 805459263, "C2": 101638485}
 
 
 def device_input(x: np.ndarray, kind: str):
