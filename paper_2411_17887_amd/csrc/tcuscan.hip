@@ -1916,10 +1916,21 @@ __global__ void seg_desc_kernel(const uint32_t *tile_start, const long long *off
     desc[t] = d;
 }
 
+// One 16-byte store per thread where the address allows it (p is 4-byte aligned; the words in front of the first
+// 16-byte boundary and behind the last go one by one).
 __global__ void fill_zero_kernel(uint32_t *p, size_t words)
 {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < words) p[i] = 0u;
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;      // group of four words, counted from the boundary
+    const size_t head = ((16u - ((uintptr_t)p & 15u)) & 15u) / 4u;         // words before the first boundary
+    const size_t h = head < words ? head : words;
+    const size_t first = h + 4 * i;
+    if (first + 4 <= words) {
+        *(u32x4 *)(p + first) = u32x4{0u, 0u, 0u, 0u};
+    } else {
+        for (size_t k = first; k < words; ++k) p[k] = 0u;
+    }
+    if (i == 0)
+        for (size_t k = 0; k < h; ++k) p[k] = 0u;
 }
 
 // ------------------------------------------------------------------------ host side
@@ -2048,7 +2059,7 @@ hipError_t launch_fill(void *d, size_t bytes, hipStream_t s)
     size_t words = bytes / 4;
     uint32_t *p = (uint32_t *)d;
     void *args[] = {&p, &words};
-    return hipLaunchKernel((const void *)fill_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), args, 0, s);
+    return hipLaunchKernel((const void *)fill_zero_kernel, dim3((unsigned)((words / 4 + 1 + 255) / 256)), dim3(256), args, 0, s);
 }
 
 tcuscan_status_t run(const void *d_in, void *d_out, size_t rows, size_t cols, int dt, int exclusive, int reverse,
