@@ -1937,6 +1937,7 @@ __global__ void fill_zero_kernel(uint32_t *p, size_t words)
 
 constexpr size_t kSmallTile = 8192;                      // elements per workgroup tile, small variant (all dtypes)
 constexpr size_t kShortRowMax = 2048;                    // rows up to this length can be scanned one per wavefront
+constexpr size_t kShortRowMax32 = 2816;                  // ... 32-bit inputs: up to 11 of their 256-element MFMA tiles
 constexpr size_t kShortRowMinRows = 8;                   // ... when there are enough of them to fill wavefronts
 
 bool valid_dtype(int dt) { return dt >= 0 && dt <= 4; }
@@ -2035,12 +2036,18 @@ template <int DT> hipError_t launch_rows(Params P, bool excl, hipStream_t s)
     if (tiles <= 1) return launch_rows_nt<DT, 1>(P, excl, s);
     if (tiles <= 2) return launch_rows_nt<DT, 2>(P, excl, s);
     if (tiles <= 4) return launch_rows_nt<DT, 4>(P, excl, s);
-    return launch_rows_nt<DT, 8>(P, excl, s);
+    if (tiles <= 8) return launch_rows_nt<DT, 8>(P, excl, s);
+    return launch_rows_nt<DT, 12>(P, excl, s);
 }
 
 template <int DT> hipError_t launch_dt(Params P, bool excl, int size, hipStream_t s)
 {
-    if (P.rows >= kShortRowMinRows && P.cols <= kShortRowMax) return launch_rows<DT>(P, excl, s);
+    // 32-bit rows a little longer than 2048 still do better one per wavefront (12 MFMA tiles, partly masked) than in a
+    // workgroup tile of 8192 that is a quarter full: measured 2100 / 2304 / 2560 columns 70 / 76 / 76 % of peak against
+    // 50 / 61 / 69 %, equal at 2816, and the workgroup tile ahead from there (3000: 73.5 % against 70 %); for 8- and
+    // 16-bit inputs the workgroup tile is ahead everywhere above 2048.
+    const size_t row_max = Tr<DT>::kEsz == 4 ? kShortRowMax32 : kShortRowMax;
+    if (P.rows >= kShortRowMinRows && P.cols <= row_max) return launch_rows<DT>(P, excl, s);
     // hipLaunchKernel reports this launch's own status (hipGetLastError could return a stale,
     // unrelated code left behind by another library's polling calls).
     void *args[] = {&P};
