@@ -1855,7 +1855,11 @@ __global__ __launch_bounds__(64 * W) void seg_flat_narrow_kernel(Params P, const
 // the histogram prefix sums in gradient-boosted-tree split finding, one of the paper's two
 // motivating applications.
 
-template <int DT, int NT, bool EXCL, bool REV>
+// LEAD: the rows do not start at 16-byte boundaries (odd row lengths, or an unaligned array): every row is then tiled
+// from the boundary at or below its start, the elements in front of it read as zero and not written -- what the
+// segmented scans do -- so that all full granules still take the 128-bit path (element by element, the same rows
+// run at a third of the speed).
+template <int DT, int NT, bool EXCL, bool REV, bool LEAD = false>
 __global__ __launch_bounds__(kThreads) void scan_rows_kernel(Params P)
 {
     using T = Tr<DT>;
@@ -1864,11 +1868,20 @@ __global__ __launch_bounds__(kThreads) void scan_rows_kernel(Params P)
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const uint64_t row = (uint64_t)blockIdx.x * kWaves + wave;
     if (row >= P.rows) return;
-    const Run R = make_run<DT>(P, row, 0);
     u32x4 g[NT];
-    load_run<DT, NT, REV>(R, lane, g);
     const typename T::AConst Aop = T::make(lane, EXCL, REV);
-    scan_and_store<DT, NT, EXCL, REV>(lane, Aop, R, g, acc_from_bits<A>(0u));
+    if constexpr (!LEAD) {
+        const Run R = make_run<DT>(P, row, 0);
+        load_run<DT, NT, REV>(R, lane, g);
+        scan_and_store<DT, NT, EXCL, REV>(lane, Aop, R, g, acc_from_bits<A>(0u));
+    } else {
+        Params Q = P;
+        Q.cols = P.rows * P.cols;                              // make_seg_run: the length of the arrays (no access beyond it)
+        const long long off = (long long)(row * P.cols);
+        const Run R = make_seg_run<DT>(Q, off, P.cols, seg_lead<DT>(P, off), 0);
+        load_run<DT, NT, REV, true>(R, lane, g);
+        scan_and_store<DT, NT, EXCL, REV, true>(lane, Aop, R, g, acc_from_bits<A>(0u));
+    }
 }
 
 // Segmented scans, step 1: tiles per row.  A row [off, off + len) is tiled from the 16-byte boundary at or below its
@@ -2012,10 +2025,10 @@ std::atomic<int> g_seg_flat{1};            // see tcuscan_set_segmented_form
 
 // Short rows: the smallest run length (1, 2, 4 or 8 MFMA tiles per wavefront) that holds a row.
 // The four (exclusive, reverse) instantiations of one kernel shape.
-template <int DT, int NT> const void *rows_kernel_for(bool excl, bool rev)
+template <int DT, int NT, bool LEAD> const void *rows_kernel_for(bool excl, bool rev)
 {
-    if (rev) return excl ? (const void *)scan_rows_kernel<DT, NT, true, true> : (const void *)scan_rows_kernel<DT, NT, false, true>;
-    return excl ? (const void *)scan_rows_kernel<DT, NT, true, false> : (const void *)scan_rows_kernel<DT, NT, false, false>;
+    if (rev) return excl ? (const void *)scan_rows_kernel<DT, NT, true, true, LEAD> : (const void *)scan_rows_kernel<DT, NT, false, true, LEAD>;
+    return excl ? (const void *)scan_rows_kernel<DT, NT, true, false, LEAD> : (const void *)scan_rows_kernel<DT, NT, false, false, LEAD>;
 }
 template <int DT, int NT, int W> const void *scan_kernel_for(bool excl, bool rev)
 {
@@ -2023,21 +2036,24 @@ template <int DT, int NT, int W> const void *scan_kernel_for(bool excl, bool rev
     return excl ? (const void *)scan_kernel<DT, NT, true, false, W> : (const void *)scan_kernel<DT, NT, false, false, W>;
 }
 
-template <int DT, int NT> hipError_t launch_rows_nt(Params P, bool excl, hipStream_t s)
+template <int DT, int NT> hipError_t launch_rows_nt(Params P, bool excl, bool lead, hipStream_t s)
 {
     void *args[] = {&P};
-    return hipLaunchKernel(rows_kernel_for<DT, NT>(excl, P.reverse != 0), dim3((unsigned)((P.rows + kWaves - 1) / kWaves)),
-                           dim3(kThreads), args, 0, s);
+    const void *fn = lead ? rows_kernel_for<DT, NT, true>(excl, P.reverse != 0) : rows_kernel_for<DT, NT, false>(excl, P.reverse != 0);
+    return hipLaunchKernel(fn, dim3((unsigned)((P.rows + kWaves - 1) / kWaves)), dim3(kThreads), args, 0, s);
 }
 
 template <int DT> hipError_t launch_rows(Params P, bool excl, hipStream_t s)
 {
-    const size_t tiles = (P.cols + Geo<DT>::kTileElems - 1) / Geo<DT>::kTileElems;
-    if (tiles <= 1) return launch_rows_nt<DT, 1>(P, excl, s);
-    if (tiles <= 2) return launch_rows_nt<DT, 2>(P, excl, s);
-    if (tiles <= 4) return launch_rows_nt<DT, 4>(P, excl, s);
-    if (tiles <= 8) return launch_rows_nt<DT, 8>(P, excl, s);
-    return launch_rows_nt<DT, 12>(P, excl, s);
+    // rows that start at 16-byte boundaries take the plain form; the others are tiled from the boundary below their
+    // start, which can cost one more MFMA tile
+    const bool lead = ((uintptr_t)P.in & 15) != 0 || (P.cols * Tr<DT>::kEsz) % 16 != 0;
+    const size_t tiles = (P.cols + (lead ? Tr<DT>::kG - 1 : 0) + Geo<DT>::kTileElems - 1) / Geo<DT>::kTileElems;
+    if (tiles <= 1) return launch_rows_nt<DT, 1>(P, excl, lead, s);
+    if (tiles <= 2) return launch_rows_nt<DT, 2>(P, excl, lead, s);
+    if (tiles <= 4) return launch_rows_nt<DT, 4>(P, excl, lead, s);
+    if (tiles <= 8) return launch_rows_nt<DT, 8>(P, excl, lead, s);
+    return launch_rows_nt<DT, 12>(P, excl, lead, s);
 }
 
 template <int DT> hipError_t launch_dt(Params P, bool excl, int size, hipStream_t s)

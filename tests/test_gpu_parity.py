@@ -153,7 +153,7 @@ def test_batched_shapes(kind, rows, cols):
 
 @pytest.mark.parametrize("kind", KINDS)
 @pytest.mark.parametrize("rows,cols", [(4096, 256), (1000, 1024), (513, 2048), (77, 2047), (9, 1), (100, 300), (8, 2048),
-                                       (4099, 64), (33, 513), (65537, 16)])
+                                       (4099, 64), (33, 513), (65537, 16), (50, 2815), (31, 2600), (12, 2816), (9, 2817)])
 def test_short_rows_one_per_wavefront(kind, rows, cols):
     """Many short rows (histogram-like shapes): each wavefront scans whole rows; includes row lengths that
     leave rows unaligned, a ragged last workgroup and exclusive scans."""
@@ -205,6 +205,19 @@ def test_in_place(kind):
     x = (inputs.int32_full if kind == "i32" else inputs.tri_f32)(n, 3)
     got = run_scan(x, kind, "inclusive", inplace=True)
     check(x, kind, got, exact_float=(kind == "f32"))
+
+
+@pytest.mark.parametrize("kind", ["i32", "f32"])
+def test_in_place_rows_that_share_granules(kind):
+    """Short rows of odd lengths, in place: a 16-byte granule at a row boundary belongs to two rows, which two
+    wavefronts scan at the same time; each must write its own elements only."""
+    for rows, cols, call in [(3001, 333, "batched"), (257, 2815, "batched_exclusive"), (1000, 7, "reverse")]:
+        x = (inputs.int32_full if kind == "i32" else inputs.tri_f32)(rows * cols, rows + cols)
+        got = run_scan(x, kind, call, rows=rows, cols=cols, inplace=True)
+        if "reverse" in call:
+            assert (oracle.compare_int_reverse if kind == "i32" else oracle.compare_float_exact_reverse)(x, kind, got, rows=rows, cols=cols) == (0, -1)
+        else:
+            check(x, kind, got, exclusive=call.endswith("exclusive"), rows=rows, cols=cols, exact_float=(kind == "f32"))
 
 
 def test_workspace_is_reusable_across_calls_shapes_and_dtypes():
