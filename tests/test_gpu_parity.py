@@ -188,7 +188,7 @@ def test_batched_row_equals_unbatched_scan_of_that_row():
 # ------------------------------------------------------------------ pointers and buffers
 
 @pytest.mark.parametrize("kind", KINDS)
-def test_unaligned_pointers_take_the_elementwise_path(kind):
+def test_unaligned_pointers(kind):
     n = 3 * 8192 + 77
     for in_off, out_off in [(1, 0), (0, 1), (3, 2), (5, 3)]:
         if kind in INT_GEN:
@@ -218,6 +218,24 @@ def test_in_place_rows_that_share_granules(kind):
             assert (oracle.compare_int_reverse if kind == "i32" else oracle.compare_float_exact_reverse)(x, kind, got, rows=rows, cols=cols) == (0, -1)
         else:
             check(x, kind, got, exclusive=call.endswith("exclusive"), rows=rows, cols=cols, exact_float=(kind == "f32"))
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_long_rows_that_do_not_start_at_16_byte_boundaries(kind):
+    """Odd row lengths and shifted base pointers with rows too long for one wavefront: tiled from the boundary below the
+    row start (the descriptor-free form of the segmented kernel), forward and reverse; lengths that fill their last
+    tile to the end need one tile more than the workspace promises and take the element-wise path -- same results."""
+    cases = [(7, 8191, 0), (3, 3 * 8192 - 1, 0), (5, 2 * 8192 - 2, 0), (9, 65537, 0), (1, 300001, 1), (2, 600001, 3), (3, 40000, 2)]
+    for rows, cols, shift in cases:
+        for call in ("batched", "batched_exclusive", "reverse", "reverse_exclusive"):
+            ex, rev = call.endswith("exclusive"), call.startswith("reverse")
+            x = (INT_GEN.get(kind) or TRI_GEN[kind])(rows * cols, rows + cols + shift)
+            got = run_scan(x, kind, call, rows=rows, cols=cols, in_offset=shift, out_offset=shift)
+            if rev:
+                cmp = oracle.compare_int_reverse if kind in INT_GEN else oracle.compare_float_exact_reverse
+                assert cmp(x, kind, got, exclusive=ex, rows=rows, cols=cols) == (0, -1), (rows, cols, shift, call)
+            else:
+                check(x, kind, got, exclusive=ex, rows=rows, cols=cols, exact_float=kind not in INT_GEN)
 
 
 def test_workspace_is_reusable_across_calls_shapes_and_dtypes():
