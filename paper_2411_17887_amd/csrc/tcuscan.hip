@@ -2280,12 +2280,16 @@ tcuscan_status_t run_segmented_flat(const void *d_in, void *d_out, const long lo
 bool run_unaligned_rows(const void *d_in, void *d_out, size_t rows, size_t cols, int dt, int exclusive, int reverse, void *d_ws,
                         size_t ws_bytes, hipStream_t s, tcuscan_status_t &st)
 {
-    const int cls = cols < ((size_t)1 << 19) ? kSegSmall : kSegLarge;
-    const size_t tile = seg_tile_elems(dt, cls), granule = 16 / in_size(dt);
-    const size_t tpr = (cols + granule - 1 + tile - 1) / tile;
-    const size_t need = tpr > 1 ? sizeof(WsHeader) + 8 * kStatusStride * rows * tpr : 0;
-    if (rows * tpr > 0x7FFFFFFFull || rows > 0x7FFFFFFFull) return false;
-    if (need && (!d_ws || ws_bytes < need || ((uintptr_t)d_ws % 8) != 0)) return false;
+    // the tile the average-length rule picks, or the other one if the workspace only has the status words for that
+    int cls = cols < ((size_t)1 << 19) ? kSegSmall : kSegLarge;
+    size_t tpr = 0, need = 0;
+    for (int attempt = 0; attempt < 2; ++attempt, cls = cls == kSegSmall ? kSegLarge : kSegSmall) {
+        const size_t tile = seg_tile_elems(dt, cls), granule = 16 / in_size(dt);
+        tpr = (cols + granule - 1 + tile - 1) / tile;
+        need = tpr > 1 ? sizeof(WsHeader) + 8 * kStatusStride * rows * tpr : 0;
+        if (rows * tpr <= 0x7FFFFFFFull && rows <= 0x7FFFFFFFull && (!need || (d_ws && ws_bytes >= need && ((uintptr_t)d_ws % 8) == 0))) break;
+        if (attempt == 1) return false;
+    }
     Params P;
     P.in = d_in; P.out = d_out; P.rows = rows; P.cols = rows * cols;     // cols: the length of the arrays, as for segmented calls
     P.tiles_per_row = (uint32_t)tpr; P.num_tiles = (uint32_t)(rows * tpr);
