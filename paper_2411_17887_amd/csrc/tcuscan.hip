@@ -2118,7 +2118,7 @@ tcuscan_status_t run(const void *d_in, void *d_out, size_t rows, size_t cols, in
         const size_t row_max = in_size(dt) == 4 ? kShortRowMax32 : kShortRowMax;
         const bool one_per_wavefront = rows >= kShortRowMinRows && cols <= row_max;
         tcuscan_status_t st;
-        if ((((uintptr_t)d_in & 15) != 0 || (cols * in_size(dt)) % 16 != 0) && !one_per_wavefront &&
+        if ((((uintptr_t)d_in & 15) != 0 || (rows > 1 && (cols * in_size(dt)) % 16 != 0)) && !one_per_wavefront &&
             run_unaligned_rows(d_in, d_out, rows, cols, dt, exclusive, reverse, d_ws, ws_bytes, s, st))
             return st;
     }
