@@ -387,6 +387,44 @@ def test_graph_capture_replays_match_eager():
     assert tcuscan.workspace_fault(ws) == 0
 
 
+def test_graph_capture_of_rows_that_are_not_aligned():
+    """The two forms for rows that do not start at 16-byte boundaries (one per wavefront; chained tiles without
+    descriptors), recorded into one graph and replayed with new data, eager calls on the same workspace in between."""
+    import torch
+    kind = "f32"
+    rows_a, cols_a = 300, 1001                       # one row per wavefront, tiled from the boundary below the row start
+    rows_b, cols_b = 5, 50001                        # chained tiles, status words cleared by a recorded fill kernel
+    ws = tcuscan.new_workspace(rows_b, cols_b, kind)
+    a_in = torch.zeros(rows_a * cols_a, dtype=torch.float32, device="cuda")
+    b_in = torch.zeros(rows_b * cols_b, dtype=torch.float32, device="cuda")
+    a_out, b_out = torch.empty_like(a_in), torch.empty_like(b_in)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                     # warm-up outside capture
+        tcuscan.batched(a_in, a_out, rows_a, cols_a, kind, stream=side)
+        tcuscan.batched(b_in, b_out, rows_b, cols_b, kind, ws=ws, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        tcuscan.batched(a_in, a_out, rows_a, cols_a, kind, stream=side)
+        tcuscan.batched(b_in, b_out, rows_b, cols_b, kind, exclusive_scan=True, ws=ws, stream=side)
+    eager = torch.empty_like(b_out)
+    for rep in range(4):
+        xa, xb = inputs.tri_f32(rows_a * cols_a, 70 + rep), inputs.tri_f32(rows_b * cols_b, 80 + rep)
+        a_in.copy_(torch.from_numpy(xa).cuda()); b_in.copy_(torch.from_numpy(xb).cuda())
+        a_out.fill_(-1); b_out.fill_(-1)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        check(xa, kind, a_out.cpu().numpy(), rows=rows_a, cols=cols_a, exact_float=True)
+        check(xb, kind, b_out.cpu().numpy(), exclusive=True, rows=rows_b, cols=cols_b, exact_float=True)
+        tcuscan.scan(b_in, eager, rows_b, cols_b, kind, flags=tcuscan.REVERSE, ws=ws)      # eager, same workspace
+        torch.cuda.synchronize()
+        assert oracle.compare_float_exact_reverse(xb, kind, eager.cpu().numpy(), rows=rows_b, cols=cols_b) == (0, -1)
+    assert tcuscan.workspace_fault(ws) == 0
+
+
 # ------------------------------------------------------------------ seeded random shapes
 
 def test_random_shapes_dtypes_and_offsets(tile_policy):
