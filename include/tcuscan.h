@@ -79,8 +79,11 @@ tcuscan_status_t tcuscan_workspace_init(void *d_ws, size_t ws_bytes, tcuscan_str
  *   n      element count; n == 0 returns TCUSCAN_OK and enqueues nothing.
  *   d_ws, ws_bytes   workspace, see tcuscan_workspace_bytes(1, n, dt); may be NULL/0
  *          when that is 0.
- * 16-byte aligned d_in and d_out take the 128-bit load/store path; other alignments
- * are accepted and run an element-wise path.
+ * 16-byte aligned d_in and d_out take the 128-bit load/store path.  Other alignments are
+ * accepted: an input that does not start at a 16-byte boundary (and, in the row-wise calls,
+ * rows whose length in bytes is not a multiple of 16) is tiled from the boundary below, the
+ * elements in front read as zero and never written; an output whose alignment differs from
+ * the input's is written element by element.
  * Floating-point results are any valid fp32 summation order (MFMA accumulation order
  * and the carry chain's grouping are not fixed), so they may differ in the last bits
  * from run to run; integer results are unique.
