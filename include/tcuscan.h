@@ -20,7 +20,14 @@
  * Plain C ABI.  Every pointer named d_* is a DEVICE pointer owned by the caller; the
  * library allocates nothing and frees nothing.  Calls are asynchronous: they enqueue
  * on `stream` (a hipStream_t passed as void*) and return; outputs are valid once the
- * stream reaches that point.  No call blocks, prints, throws or exits.
+ * stream reaches that point.  No call prints, throws or exits, and none blocks except
+ * tcuscan_workspace_fault, which waits for the stream and copies one word to the host
+ * (so it cannot be used while the stream is being captured).
+ *
+ * Inputs must be finite.  The local scans are products with 0/1 matrices, and 0 x Inf
+ * and 0 x NaN are NaN: one non-finite input turns every output computed by the same
+ * matrix instruction into NaN -- including outputs in front of it, up to 128 elements
+ * away for 16-bit inputs -- where a sequential sum would only spoil what follows.
  */
 #ifndef TCUSCAN_H
 #define TCUSCAN_H
@@ -56,13 +63,21 @@ typedef void *tcuscan_stream_t; /* a hipStream_t; NULL is the default stream */
  * workgroups (Algorithm 1's up-sweep rounds t >= 3 and Section 2.2 steps 2-3): one
  * 8-byte status word per tile, kept in a 64-byte slot of its own, plus a 256-byte header.
  *
+ * The count is taken for a row together with the fewer-than-16 bytes in front of it down
+ * to a 16-byte boundary, which is how rows that do not start at such a boundary are
+ * tiled; for row lengths within 16 bytes of a multiple of the tile this is one word per
+ * row more than the rows alone would need.  (Workspaces sized without that word are
+ * still accepted; such rows then take the other tile size, a few per cent slower.)
+ *
  * The caller zero-fills it ONCE after allocation (hipMemset, or tcuscan_workspace_init)
  * and may then reuse it for any number of calls whose requirement is not larger: every
  * call tags its status words with a fresh per-process call number, so older words read
- * as "not published".  A call recorded by stream capture is replayed with the tag it
- * was recorded with and therefore clears its status words first (one extra fill kernel
- * in the graph).  Two calls that are in flight at the same time must not share a
- * workspace.  After 2^30 - 2 library calls in one process, zero-fill workspaces again.
+ * as "not published".  The tags repeat after 2^30 - 2 calls; the library keeps track of
+ * which workspaces it has seen since the last repeat and clears the status words of the
+ * others itself (a fill kernel in front of the call), so the caller never has to.  A
+ * call recorded by stream capture is replayed with the tag it was recorded with and
+ * therefore clears its status words first (one extra fill kernel in the graph).  Two
+ * calls that are in flight at the same time must not share a workspace.
  */
 size_t tcuscan_workspace_bytes(size_t rows, size_t cols, tcuscan_dtype_t dt);
 
@@ -139,6 +154,10 @@ tcuscan_status_t tcuscan_scan(const void *d_in, void *d_out, size_t rows, size_t
  * front of it are read as zero and not written.  Offsets that decrease or leave [0, total] are not followed: the
  * workspace's fault word is set to 2 (see tcuscan_workspace_fault) and the results of the call are unspecified (such
  * rows are skipped or clipped, rows may overlap); no access outside the n = total elements is made.
+ * A segmented call keeps row maps in its workspace besides status words, at places that depend on its shape, so it
+ * clears its status words in front of every run, and the library clears them again before another kind of call uses the
+ * same workspace.  It cannot see a segmented call being REPLAYED from a graph: give such a graph a workspace that no
+ * call outside the graph uses.
  */
 size_t tcuscan_segmented_workspace_bytes(size_t rows, size_t total, tcuscan_dtype_t dt);
 tcuscan_status_t tcuscan_segmented(const void *d_in, void *d_out, const long long *d_offsets, size_t rows, size_t total,
@@ -161,6 +180,18 @@ size_t tcuscan_huge_tile_elems(tcuscan_dtype_t dt);
  */
 tcuscan_status_t tcuscan_set_tile_policy(int policy);
 
+/*
+ * How tiles are handed to workgroups, process-wide.  0 (default): a workgroup scans the tile with its own index in the
+ * grid; a tile waits only for tiles with smaller indices, so the carry chain makes progress as long as the hardware
+ * starts workgroups in index order (never a workgroup while one with a smaller index is still waiting for a place),
+ * which is how the dispatcher of this device family behaves and what every run of this library has shown.  1: a
+ * workgroup draws its tile from a counter in the workspace when it starts running, so every tile it can wait for
+ * belongs to a workgroup that is running or done whatever the dispatch order is; one atomic on one address per tile
+ * makes long chains several times slower.  For callers who cannot rely on dispatch order (another dispatcher, a
+ * simulator, a partitioned device).  Results are the same up to floating-point summation order.
+ */
+tcuscan_status_t tcuscan_set_chain_policy(int policy);
+
 /* 1 (default): short rows of a segmented scan are scanned as one range with row-start bits; 0: every
  * row gets tiles of its own, as for all other segmented calls.  Process-wide; a measurement and test knob, results do
  * not depend on it beyond floating-point summation order. */
@@ -174,6 +205,49 @@ tcuscan_status_t tcuscan_set_segmented_form(int flat);
  * segmented scan was given offsets that decrease or leave [0, total].
  */
 tcuscan_status_t tcuscan_workspace_fault(const void *d_ws, tcuscan_stream_t stream, unsigned *h_fault);
+
+/*
+ * Which way tcuscan_scan takes for this input pointer, shape and workspace size (a host-side query, nothing is
+ * enqueued; d_in is only looked at for its alignment).  Rows that start at 16-byte boundaries take ROWS or TILES; other
+ * rows are tiled from the boundary below (Section 2.2's segments, with BatchMatMul's zero-pad in front), unless the
+ * workspace has status words for neither tile size that takes -- then ELEMENTWISE, the plain tiles read element by
+ * element, several times slower.  A workspace of tcuscan_workspace_bytes() never gets ELEMENTWISE.  Returns -1 for an
+ * unknown dtype or an empty shape.
+ */
+#define TCUSCAN_PATH_ROWS                0 /* one row per wavefront, no carry chain */
+#define TCUSCAN_PATH_TILES               1 /* workgroup tiles and the carry chain */
+#define TCUSCAN_PATH_TILES_FROM_BOUNDARY 2 /* the same for rows that do not start at 16-byte boundaries */
+#define TCUSCAN_PATH_ELEMENTWISE         3
+int tcuscan_path_for(const void *d_in, size_t rows, size_t cols, tcuscan_dtype_t dt, size_t ws_bytes);
+
+/*
+ * Measurement only: a streaming kernel with a scan's memory traffic and none of its work, the yardstick the benchmark
+ * prices the scans against (a scan reads every input once and writes every output once; Section 2.3's cost model
+ * counts the matrix products, the device counts the bytes).  Writes out_bytes (a multiple of 64) to d_out and reads
+ * in_bytes_per_out_word (0: nothing, 1, 2 or 4) bytes from d_in for every 4 bytes written -- the mix of 8-, 16- and
+ * 32-bit inputs with 32-bit outputs.  Both pointers 16-byte aligned.  variant: bits 0-1 = log2 of the 16-byte loads
+ * (write-only: stores) each lane has in flight (1, 2, 4, 8), bit 8 = non-temporal loads, bit 9 = every wavefront reads
+ * a run of consecutive KiB (a scan tile's shape) instead of interleaving with its workgroup's other wavefronts, bit 10 =
+ * a grid of 2048 workgroups that walk over the data instead of one workgroup per chunk; a caller takes the best of them.
+ * 128-bit loads, non-temporal 128-bit stores, 1 KiB per wavefront and instruction, no dependencies.  The output is a
+ * function of the input that nobody needs.
+ */
+tcuscan_status_t tcuscan_measure_stream(const void *d_in, void *d_out, size_t out_bytes, int in_bytes_per_out_word,
+                                        unsigned variant, tcuscan_stream_t stream);
+
+/*
+ * Test hooks, process-wide; not for production use.
+ *   tcuscan_test_advance_calls   adds `calls` to the process's call counter, as if that many calls had drawn status-word
+ *                                tags (tcuscan_test_tag_period() of them bring the same tag round again).
+ *   tcuscan_test_chain_fault     spin_limit: polls of one status word before a carry-chain wait gives up and raises
+ *                                fault word 1 (0: back to the default, 2^24); mute_tile: the workgroup tile with this
+ *                                index does not publish its status word (negative: none; plain scans only).  With a
+ *                                muted tile and a small limit every later tile of the row gives up, all kernels end
+ *                                normally, the results are wrong and the fault word says so.
+ */
+tcuscan_status_t tcuscan_test_advance_calls(unsigned long long calls);
+unsigned long long tcuscan_test_tag_period(void);
+tcuscan_status_t tcuscan_test_chain_fault(unsigned spin_limit, long long mute_tile);
 
 /*
  * Algorithm 1 (MatMulScan) executed literally with s = 16: one kernel launch per round, k = log_s n

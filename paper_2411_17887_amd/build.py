@@ -4,23 +4,37 @@ from __future__ import annotations
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SOURCES = [os.path.join(HERE, "csrc", "tcuscan.hip"), os.path.join(HERE, "csrc", "levels.hip"),
-           os.path.join(HERE, "csrc", "apps.hip")]
+SOURCES = [os.path.join(HERE, "csrc", name) for name in ("tcuscan.hip", "levels.hip", "apps.hip", "stream.hip")]
 LIB = os.path.join(HERE, "libtcuscan.so")
+OBJ_DIR = os.path.join(HERE, "_build")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
+FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
          # packed fp32 VALU forms are kept out of the generated code on purpose
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]
 
 
 def build(verbose: bool = False, extra: list[str] | None = None) -> str:
-    cmd = [HIPCC, *FLAGS, *(extra or []), "-o", LIB, *SOURCES]
+    """Compile every source (one hipcc process each, side by side) and link the shared library."""
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    objs = [os.path.join(OBJ_DIR, os.path.basename(src) + ".o") for src in SOURCES]
+
+    def compile_one(pair):
+        src, obj = pair
+        cmd = [HIPCC, *FLAGS, *(extra or []), "-c", "-o", obj, src]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
+
+    with ThreadPoolExecutor(max_workers=len(SOURCES)) as pool:
+        list(pool.map(compile_one, zip(SOURCES, objs)))
+    link = [HIPCC, "--offload-arch=gfx950", "-fPIC", "-shared", "-o", LIB, *objs]
     if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+        print(" ".join(link), flush=True)
+    subprocess.run(link, check=True)
     return LIB
 
 

@@ -15,6 +15,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/tcuscan.h"
 
 extern "C" tcuscan_status_t tcuscan_internal_compact_fused(const void *d_values, const void *d_mask, void *d_out, size_t n, unsigned *d_count,
@@ -97,8 +99,10 @@ __global__ __launch_bounds__(kThreads) void copy_u32_kernel(const uint32_t *__re
 
 unsigned blocks_for(size_t items) { return (unsigned)((items + kThreads - 1) / kThreads); }
 
-bool g_force_unfused_sort = false;      // measurement / test knob, see tcuscan_set_sort_fusion
-int g_sort_digit_bits = 2;              // fused passes: bits per pass (2 or 1), same knob
+// measurement / test knob, see tcuscan_set_sort_fusion: 1 fused passes on two bits, 2 fused passes on one bit, 0 three
+// kernels per bit.  One atomic word, read once at the top of a sort, so that a change made by another thread while a
+// sort is being enqueued cannot mix the forms (or their count tables) within that sort.
+std::atomic<int> g_sort_form{1};
 
 }  // namespace
 
@@ -149,14 +153,16 @@ tcuscan_status_t tcuscan_split_radix_sort_u32(void *d_keys, void *d_vals, size_t
     // it is counted once, up front, into the first 96 words of d_positions (64 digit counts, 32 zero-bit counts).  The
     // unfused form below (mask kernel, tcuscan_exclusive, scatter kernel, one bit per pass) remains for n < 96 and as
     // the plain statement of the reduction.
-    const bool fused = n >= 96 && !g_force_unfused_sort;
+    const int form = g_sort_form.load(std::memory_order_relaxed);
+    const bool fused = n >= 96 && form != 0;
+    const int digit_bits = form == 2 ? 1 : 2;                                   // fused passes: bits per pass
     if (fused) {
         unsigned *hist = (unsigned *)d_positions, *zeros = hist + 64;
-        tcuscan_status_t st = g_sort_digit_bits == 2 ? tcuscan_internal_digit_counts(d_keys, n, hist, stream) : TCUSCAN_OK;
-        if (st == TCUSCAN_OK && (g_sort_digit_bits != 2 || (bits & 1))) st = tcuscan_internal_bit_zero_counts(d_keys, n, zeros, stream);
+        tcuscan_status_t st = digit_bits == 2 ? tcuscan_internal_digit_counts(d_keys, n, hist, stream) : TCUSCAN_OK;
+        if (st == TCUSCAN_OK && (digit_bits != 2 || (bits & 1))) st = tcuscan_internal_bit_zero_counts(d_keys, n, zeros, stream);
         if (st != TCUSCAN_OK) return st;
         for (int bit = 0; bit < bits;) {
-            const int step = g_sort_digit_bits == 2 && bits - bit >= 2 ? 2 : 1;
+            const int step = digit_bits == 2 && bits - bit >= 2 ? 2 : 1;
             st = step == 2 ? tcuscan_internal_split4_pass(src_k, src_v, dst_k, dst_v, n, bit, hist + 4 * (bit / 2), d_ws, ws_bytes, stream)
                            : tcuscan_internal_split_pass(src_k, src_v, dst_k, dst_v, n, bit, zeros + bit, d_ws, ws_bytes, stream);
             if (st != TCUSCAN_OK) return st;
@@ -200,7 +206,6 @@ tcuscan_status_t tcuscan_split_radix_sort_u32(void *d_keys, void *d_vals, size_t
 extern "C" tcuscan_status_t tcuscan_set_sort_fusion(int fused)
 {
     if (fused < 0 || fused > 2) return TCUSCAN_ERR_INVALID_ARG;
-    g_force_unfused_sort = fused == 0;
-    g_sort_digit_bits = fused == 2 ? 1 : 2;
+    g_sort_form.store(fused, std::memory_order_relaxed);
     return TCUSCAN_OK;
 }

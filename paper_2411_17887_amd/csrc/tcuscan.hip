@@ -40,6 +40,7 @@
 #include <atomic>
 
 #include "../../include/tcuscan.h"
+#include "chain_tags.h"
 
 namespace {
 
@@ -59,21 +60,25 @@ constexpr int kThreads = 64 * kWaves;
 constexpr size_t kStatusStride = 8;    // in 64-bit words
 struct WsHeader {
     uint32_t fault;    // sticky: 1 = a look-back wait hit its spin bound, 2 = a segmented scan was given bad offsets
-    uint32_t pad[63];
+    uint32_t ticket;   // ticket policy only: the next tile index to hand out (cleared in front of every such call)
+    uint32_t pad[62];
 };
 static_assert(sizeof(WsHeader) == 256, "header size");
 
 constexpr uint32_t kStateAggregate = 1u;   // value = total of this tile only
 constexpr uint32_t kStatePrefix    = 2u;   // value = total of this tile and all before it in the row
-constexpr uint32_t kTagMod         = (1u << 30) - 2u;   // tags run over 1 .. 2^30 - 2; 0 marks a zero-filled word
-constexpr uint32_t kSpinLimit      = 1u << 24;   // look-back polls before giving up (seconds of waiting)
+constexpr uint32_t kDefaultSpinLimit = 1u << 24;   // look-back polls before giving up (seconds of waiting)
+constexpr uint32_t kNoTile           = 0xFFFFFFFFu;
 
 struct Params {
     const void *in;
     void       *out;
     uint64_t    rows, cols;  // segmented scans: cols = number of elements of the arrays
     uint32_t    tiles_per_row, num_tiles;
-    uint32_t    tag;         // this call's tag for the status words
+    uint32_t    tag;         // this call's tag for the status words (30 bits; see chain_tags.h)
+    uint32_t    ticket;      // non-zero: workgroups draw their tile index from the counter in the workspace header
+    uint32_t    spin_limit;  // look-back polls per status word before the wait gives up and raises the fault word
+    uint32_t    mute_tile;   // test hook: the tile with this index does not publish its status word (kNoTile: none)
     uint32_t    reverse;     // non-zero: suffix sums (every row is scanned from its end)
     WsHeader   *ws;          // null when tiles_per_row == 1
     // segmented scans only: what every tile has to know about its row (built by seg_desc_kernel)
@@ -419,7 +424,7 @@ __device__ __forceinline__ uint64_t status_word(uint32_t tag, uint32_t state, ui
 // 5 % of the run time against 128, and 1024 and more cost 50 %).
 constexpr int kDepth = 2;
 template <class A>
-__device__ A look_back(const uint64_t *row_status, int tr, uint32_t tag, WsHeader *ws)
+__device__ A look_back(const uint64_t *row_status, int tr, uint32_t tag, WsHeader *ws, uint32_t spin_limit)
 {
     const int lane = __lane_id();
     A sum = acc_from_bits<A>(0u);
@@ -442,7 +447,7 @@ __device__ A look_back(const uint64_t *row_status, int tr, uint32_t tag, WsHeade
                 for (;;) {
                     uint32_t f = (uint32_t)(w[u] >> 32);
                     if ((f >> 2) == tag) { state = f & 3u; vbits = (uint32_t)w[u]; break; }
-                    if (++spins > kSpinLimit) {               // never in correct operation: give up instead of hanging
+                    if (++spins > spin_limit) {               // never in correct operation: give up instead of hanging
                         __hip_atomic_store(&ws->fault, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         break;
                     }
@@ -459,6 +464,22 @@ __device__ A look_back(const uint64_t *row_status, int tr, uint32_t tag, WsHeade
         if (done) break;
     }
     return sum;
+}
+
+// Which tile this workgroup scans.  Default: its index in the grid -- a tile then waits only for tiles with a smaller
+// workgroup index, and the chain makes progress as long as the hardware starts workgroups in index order (a workgroup
+// is never started while one with a smaller index is still waiting for a place on the chip).  Ticket policy: the
+// next number of a counter in the workspace header, drawn when the workgroup has started -- every smaller tile number
+// was then drawn by a workgroup that is running or done, whatever the dispatch order; the price is one atomic on a
+// single address per tile.  `s_slot`: an LDS word of the workgroup (free again when the call returns).
+__device__ __forceinline__ uint32_t take_tile(const Params &P, uint32_t *s_slot)
+{
+    if (!P.ticket) return blockIdx.x;
+    if (threadIdx.x == 0) *s_slot = __hip_atomic_fetch_add(&P.ws->ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    const uint32_t t = (uint32_t)__builtin_amdgcn_readfirstlane((int)*s_slot);
+    __syncthreads();
+    return t;
 }
 
 // ------------------------------------------------------------------- per-wavefront steps
@@ -708,13 +729,13 @@ void scan_kernel(Params P)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // wave-uniform: keeps tile bookkeeping in SGPRs
 
-    // ---- which tile.  Tiles are taken in workgroup-index order: a tile only ever waits for tiles with
-    // a smaller index, which the hardware dispatched earlier (or at the same time), so the lowest
-    // unfinished tile is always running and the chain cannot stall.  (A shared ticket counter would
-    // guarantee the same without that assumption, but one contended atomic per tile caps the whole
+    // ---- which tile.  Tiles are taken in workgroup-index order by default: a tile only ever waits for
+    // tiles with a smaller index, which the hardware dispatched earlier (or at the same time), so the
+    // lowest unfinished tile is always running and the chain cannot stall.  (The ticket policy
+    // guarantees the same without that assumption, but one contended atomic per tile caps the whole
     // kernel at the device's single-address atomic rate.)  Status words carry the call's tag, so
     // words left over from earlier calls read as "not published yet" and need no clearing.
-    const uint32_t tile = blockIdx.x;
+    const uint32_t tile = take_tile(P, &s_bcast);
     const uint32_t tag = P.tag;
     uint64_t row;
     uint32_t tr, tiles_in_row, first_tile;        // position in the carry chain of the row, its length, the row's first tile
@@ -783,16 +804,17 @@ void scan_kernel(Params P)
     if (chained) {
         uint64_t *row_status = (uint64_t *)(P.ws + 1) + (uint64_t)first_tile * kStatusStride;
         if (wave == 0) {
+            const bool speaks = lane == 0 && tile != P.mute_tile;      // (the test hook silences one tile)
             if (tr == 0) {
-                if (lane == 0)
+                if (speaks)
                     __hip_atomic_store(row_status, status_word(tag, kStatePrefix, acc_bits(wg_total)),
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             } else {
-                if (lane == 0)
+                if (speaks)
                     __hip_atomic_store(row_status + (size_t)tr * kStatusStride, status_word(tag, kStateAggregate, acc_bits(wg_total)),
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                prefix = look_back<A>(row_status, (int)tr, tag, P.ws);
-                if (lane == 0)
+                prefix = look_back<A>(row_status, (int)tr, tag, P.ws, P.spin_limit);
+                if (speaks)
                     __hip_atomic_store(row_status + (size_t)tr * kStatusStride, status_word(tag, kStatePrefix, acc_bits(acc_add(prefix, wg_total))),
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
@@ -967,10 +989,10 @@ __device__ __forceinline__ void split_scatter(int lane, const typename Tr<TCUSCA
 // From a wavefront's flag count to what lies before its run in the whole array: totals of the workgroup's wavefronts
 // through LDS, then the carry chain between workgroups (as in scan_kernel; one row, tiles in workgroup-index order).
 template <int W>
-__device__ __forceinline__ void flags_before_run(const Params &P, int lane, int wave, uint32_t wave_total, uint32_t *s_wave_total,
+__device__ __forceinline__ void flags_before_run(const Params &P, uint32_t tile, int lane, int wave, uint32_t wave_total, uint32_t *s_wave_total,
                                                  uint32_t *s_bcast, uint32_t &before_run, uint32_t &run_total, uint32_t &through_wg)
 {
-    const uint32_t tile = blockIdx.x, tag = P.tag;
+    const uint32_t tag = P.tag;
     if (lane == 0) s_wave_total[wave] = wave_total;
     __syncthreads();
     uint32_t wave_off = 0u, wg_total = 0u;
@@ -992,7 +1014,7 @@ __device__ __forceinline__ void flags_before_run(const Params &P, int lane, int 
                 if (lane == 0)
                     __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStateAggregate, wg_total),
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                prefix = look_back<uint32_t>(row_status, (int)tile, tag, P.ws);
+                prefix = look_back<uint32_t>(row_status, (int)tile, tag, P.ws, P.spin_limit);
                 if (lane == 0)
                     __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStatePrefix, prefix + wg_total),
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1040,7 +1062,8 @@ __global__ __launch_bounds__(64 * W) void split_kernel(Params P, SplitArgs S)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const uint64_t n = P.cols;
-    const uint64_t base = ((uint64_t)blockIdx.x * W + wave) * kEPW;                 // first key of this wavefront's run
+    const uint32_t tile = take_tile(P, &s_bcast);
+    const uint64_t base = ((uint64_t)tile * W + wave) * kEPW;                       // first key of this wavefront's run
     const uint32_t rem = base < n ? (n - base < 0x40000000ull ? (uint32_t)(n - base) : 0x40000000u) : 0u;
     const int bit = S.bit;
 
@@ -1059,7 +1082,7 @@ __global__ __launch_bounds__(64 * W) void split_kernel(Params P, SplitArgs S)
     }
     const typename T::AConst Aop = T::make_compact(lane);
     uint32_t zero_at, zeros_run, through_wg;
-    flags_before_run<W>(P, lane, wave, reduce_run<DT, NT>(lane, Aop, g), s_wave_total, &s_bcast, zero_at, zeros_run, through_wg);
+    flags_before_run<W>(P, tile, lane, wave, reduce_run<DT, NT>(lane, Aop, g), s_wave_total, &s_bcast, zero_at, zeros_run, through_wg);
 
     // ---- destinations and scatter of the run
     u32x4 val[VALS ? NT : 1][4];
@@ -1228,7 +1251,7 @@ __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(VALS ? 1
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const uint32_t tile = blockIdx.x, tag = P.tag;
+    const uint32_t tile = take_tile(P, &s_prefix[0]), tag = P.tag;
     const uint64_t n = P.cols;
     const uint64_t base = ((uint64_t)tile * W + wave) * kEPW;                       // first key of this wavefront's run
     const uint32_t rem = base < n ? (n - base < 0x40000000ull ? (uint32_t)(n - base) : 0x40000000u) : 0u;
@@ -1289,7 +1312,7 @@ __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(VALS ? 1
                 if (lane == 0)
                     __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStateAggregate, mine),
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                pre = look_back<uint32_t>(row_status, (int)tile, tag, P.ws);
+                pre = look_back<uint32_t>(row_status, (int)tile, tag, P.ws, P.spin_limit);
                 if (lane == 0)
                     __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStatePrefix, pre + mine),
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1342,7 +1365,8 @@ __global__ __launch_bounds__(64 * W) void compact_kernel(Params P, CompactArgs C
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const uint64_t n = P.cols;
-    const uint64_t base = ((uint64_t)blockIdx.x * W + wave) * kEPW;                 // first element of this wavefront's run
+    const uint32_t tile = take_tile(P, &s_bcast);
+    const uint64_t base = ((uint64_t)tile * W + wave) * kEPW;                       // first element of this wavefront's run
     const uint32_t rem = base < n ? (n - base < 0x40000000ull ? (uint32_t)(n - base) : 0x40000000u) : 0u;
 
     // ---- the mask granules (lane l: bytes 16 l .. 16 l + 15 of every MFMA tile; nothing beyond the end) and the values
@@ -1364,8 +1388,8 @@ __global__ __launch_bounds__(64 * W) void compact_kernel(Params P, CompactArgs C
     load_run_words<NT>(lane, C.values + base, rem, 0u, val);
     const typename T::AConst Aop = T::make_compact(lane);
     uint32_t kept_at, kept_run, through_wg;
-    flags_before_run<W>(P, lane, wave, reduce_run<DT, NT>(lane, Aop, g), s_wave_total, &s_bcast, kept_at, kept_run, through_wg);
-    if (C.count && blockIdx.x == P.num_tiles - 1 && threadIdx.x == 0) *C.count = through_wg;
+    flags_before_run<W>(P, tile, lane, wave, reduce_run<DT, NT>(lane, Aop, g), s_wave_total, &s_bcast, kept_at, kept_run, through_wg);
+    if (C.count && tile == P.num_tiles - 1 && threadIdx.x == 0) *C.count = through_wg;
     split_scatter<NT, kSlot, false>(lane, Aop, g, val, C.out, kept_at, 0u, kept_run, rem, n, s_pack[wave]);
 }
 
@@ -1391,7 +1415,13 @@ __global__ __launch_bounds__(64 * kSegPack) void seg_short_kernel(Params P)
     constexpr uint32_t kTile = NT * Geo<DT>::kTileElems;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const uint32_t tile0 = (blockIdx.x * kSegPack + (uint32_t)wave) * U;
+    uint32_t slot = blockIdx.x * kSegPack + (uint32_t)wave;            // which group of U tiles this wavefront takes
+    if (P.ticket) {                                                    // ticket policy: one draw per wavefront (they share nothing)
+        uint32_t t = 0u;
+        if (lane == 0) t = __hip_atomic_fetch_add(&P.ws->ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        slot = (uint32_t)__builtin_amdgcn_readfirstlane((int)t);
+    }
+    const uint32_t tile0 = slot * U;
 
     TileDesc d[U];
     bool live[U];
@@ -1435,7 +1465,7 @@ __global__ __launch_bounds__(64 * kSegPack) void seg_short_kernel(Params P)
         A prefix = acc_from_bits<A>(0u);
         if (d[u].tiles_in_row > 1 && tr[u] != 0) {
             uint64_t *row_status = (uint64_t *)(P.ws + 1) + (uint64_t)d[u].first_tile * kStatusStride;
-            prefix = look_back<A>(row_status, (int)tr[u], P.tag, P.ws);
+            prefix = look_back<A>(row_status, (int)tr[u], P.tag, P.ws, P.spin_limit);
             if (lane == 0)
                 __hip_atomic_store(row_status + (size_t)tr[u] * kStatusStride,
                                    status_word(P.tag, kStatePrefix, acc_bits(acc_add(prefix, total[u]))),
@@ -1541,12 +1571,12 @@ __device__ __forceinline__ A seg_open_sum_before_run(const Params &P, uint32_t t
                 if (lane == 0)
                     __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStatePrefix, acc_bits(wg_sum)),
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (tile != 0) prefix = look_back<A>(row_status, (int)tile, tag, P.ws);
+                if (tile != 0) prefix = look_back<A>(row_status, (int)tile, tag, P.ws, P.spin_limit);
             } else {
                 if (lane == 0)
                     __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStateAggregate, acc_bits(wg_sum)),
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                prefix = look_back<A>(row_status, (int)tile, tag, P.ws);
+                prefix = look_back<A>(row_status, (int)tile, tag, P.ws, P.spin_limit);
                 if (lane == 0)
                     __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStatePrefix, acc_bits(acc_add(prefix, wg_sum))),
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1572,7 +1602,7 @@ __global__ __launch_bounds__(64 * W) void seg_flat_kernel(Params P, const long l
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const uint32_t tile = blockIdx.x;
+    const uint32_t tile = take_tile(P, &s_bcast);
 
     // the range the rows cover, clamped to the arrays (offsets that leave them have raised the fault word already)
     long long lo = offsets[0], hi = offsets[P.rows];
@@ -1734,7 +1764,7 @@ __global__ __launch_bounds__(64 * W) void seg_flat_narrow_kernel(Params P, const
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const uint32_t tile = blockIdx.x;
+    const uint32_t tile = take_tile(P, &s_bcast);
 
     long long lo = offsets[0], hi = offsets[P.rows];
     const long long total = (long long)P.cols;
@@ -2033,8 +2063,11 @@ int choose_tile(int dt, size_t rows, size_t cols)
     return want;
 }
 
-std::atomic<uint32_t> g_calls{0};
+std::atomic<uint64_t> g_calls{0};          // calls that drew a tag so far (64 bits: does not wrap in practice)
 std::atomic<int> g_seg_flat{1};            // see tcuscan_set_segmented_form
+std::atomic<int> g_chain_policy{0};        // see tcuscan_set_chain_policy
+std::atomic<uint32_t> g_spin_limit{kDefaultSpinLimit}, g_mute_tile{kNoTile};     // see tcuscan_test_chain_fault
+chain_tags::CleanTable g_clean;            // which workspaces hold no status words of older tag generations
 
 // Short rows: the smallest run length (1, 2, 4 or 8 MFMA tiles per wavefront) that holds a row.
 // The four (exclusive, reverse) instantiations of one kernel shape.
@@ -2098,11 +2131,54 @@ hipError_t launch_fill(void *d, size_t bytes, hipStream_t s)
     return hipLaunchKernel((const void *)fill_zero_kernel, dim3((unsigned)((words / 4 + 1 + 255) / 256)), dim3(256), args, 0, s);
 }
 
-bool run_unaligned_rows(const void *d_in, void *d_out, size_t rows, size_t cols, int dt, int exclusive, int reverse, void *d_ws,
-                        size_t ws_bytes, hipStream_t s, tcuscan_status_t &st);      // below, with the segmented launches
+// What a launch has to know about the carry chain, and whatever has to run in front of it on the stream.  `tiles`
+// status words behind the header of `d_ws` are going to be used (0: no chain).
+//   * A call normally draws a fresh tag from the call counter; the first call on a workspace in a new tag generation
+//     clears the status words first (chain_tags.h).
+//   * A call recorded by stream capture is replayed with the tag it was recorded with, and `clear_first` marks a
+//     workspace region whose contents the library cannot vouch for: both get the reserved tag and a fill kernel in
+//     front of every run (a kernel, not a memset node).
+//   * Ticket policy: the header's ticket counter is cleared.
+tcuscan_status_t begin_chain(Params &P, void *d_ws, size_t tiles, bool clear_first, hipStream_t s)
+{
+    P.ticket = 0u;
+    P.spin_limit = g_spin_limit.load(std::memory_order_relaxed);
+    P.mute_tile = g_mute_tile.load(std::memory_order_relaxed);
+    P.tag = 1u;
+    if (!d_ws || tiles == 0) return TCUSCAN_OK;
+    const size_t status_bytes = 8 * kStatusStride * tiles;
+    void *status = (char *)d_ws + sizeof(WsHeader);
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &cs) != hipSuccess) { (void)hipGetLastError(); cs = hipStreamCaptureStatusNone; }
+    if (clear_first || cs == hipStreamCaptureStatusActive) {
+        P.tag = chain_tags::kClearFirstTag;
+        if (launch_fill(status, status_bytes, s) != hipSuccess) return TCUSCAN_ERR_HIP;
+    } else {
+        const chain_tags::CallId id = chain_tags::call_id(g_calls.fetch_add(1u, std::memory_order_relaxed));
+        P.tag = id.tag;
+        if (g_clean.needs_clear((uintptr_t)d_ws, sizeof(WsHeader) + status_bytes, id.generation) &&
+            launch_fill(status, status_bytes, s) != hipSuccess) return TCUSCAN_ERR_HIP;
+    }
+    if (g_chain_policy.load(std::memory_order_relaxed) == 1) {
+        P.ticket = 1u;
+        if (launch_fill(&((WsHeader *)d_ws)->ticket, sizeof(uint32_t), s) != hipSuccess) return TCUSCAN_ERR_HIP;
+    }
+    return TCUSCAN_OK;
+}
 
+// Which way a row-wise call takes (tcuscan_path_for reports it; run() follows it).
+struct Plan {
+    int path;            // TCUSCAN_PATH_*
+    int seg_cls;         // tiles from the boundary below: which tile (kSegSmall / kSegLarge)
+    size_t tpr, need;    // ... tiles per row (the row and the elements in front of it) and workspace bytes they take
+};
+Plan plan_for(uintptr_t in_addr, size_t rows, size_t cols, int dt, bool ws_usable, size_t ws_bytes);     // below, with the segmented launches
+tcuscan_status_t run_unaligned_rows(const void *d_in, void *d_out, size_t rows, size_t cols, int dt, int exclusive, int reverse, void *d_ws,
+                                    const Plan &plan, bool clear_first, hipStream_t s);
+
+// `clear_first`: the workspace is a region whose former contents are unknown (see begin_chain).
 tcuscan_status_t run(const void *d_in, void *d_out, size_t rows, size_t cols, int dt, int exclusive, int reverse,
-                     void *d_ws, size_t ws_bytes, tcuscan_stream_t stream)
+                     void *d_ws, size_t ws_bytes, tcuscan_stream_t stream, bool clear_first = false)
 {
     if (!valid_dtype(dt)) return TCUSCAN_ERR_UNSUPPORTED;
     if (rows == 0 || cols == 0) return TCUSCAN_OK;
@@ -2110,18 +2186,18 @@ tcuscan_status_t run(const void *d_in, void *d_out, size_t rows, size_t cols, in
     if (((uintptr_t)d_in % in_size(dt)) != 0 || ((uintptr_t)d_out % 4) != 0) return TCUSCAN_ERR_INVALID_ARG;
     if (d_in == d_out && in_size(dt) != 4) return TCUSCAN_ERR_INVALID_ARG;
     if (rows > 0x7FFFFFFFull / ((cols + kSmallTile - 1) / kSmallTile)) return TCUSCAN_ERR_UNSUPPORTED;   // tile index: 31 bits
-    const size_t need = tcuscan_workspace_bytes(rows, cols, (tcuscan_dtype_t)dt);
-    if (need && (!d_ws || ws_bytes < need || ((uintptr_t)d_ws % 8) != 0)) return TCUSCAN_ERR_WORKSPACE;
+    // the least a call needs: one status word per small tile of the rows themselves (tcuscan_workspace_bytes promises
+    // one more per row where a row and the elements in front of it can need one; see plan_for)
+    const size_t tpr_small = (cols + kSmallTile - 1) / kSmallTile;
+    const size_t need = tpr_small > 1 ? sizeof(WsHeader) + 8 * kStatusStride * rows * tpr_small : 0;
+    const bool ws_usable = d_ws && ((uintptr_t)d_ws % 8) == 0;
+    if (need && (!ws_usable || ws_bytes < need)) return TCUSCAN_ERR_WORKSPACE;
 
     hipStream_t s = (hipStream_t)stream;
-    {   // long rows that do not start at 16-byte boundaries: tiled from the boundary below, like segmented rows
-        const size_t row_max = in_size(dt) == 4 ? kShortRowMax32 : kShortRowMax;
-        const bool one_per_wavefront = rows >= kShortRowMinRows && cols <= row_max;
-        tcuscan_status_t st;
-        if ((((uintptr_t)d_in & 15) != 0 || (rows > 1 && (cols * in_size(dt)) % 16 != 0)) && !one_per_wavefront &&
-            run_unaligned_rows(d_in, d_out, rows, cols, dt, exclusive, reverse, d_ws, ws_bytes, s, st))
-            return st;
-    }
+    const Plan plan = plan_for((uintptr_t)d_in, rows, cols, dt, ws_usable, ws_bytes);
+    // long rows that do not start at 16-byte boundaries: tiled from the boundary below, like segmented rows
+    if (plan.path == TCUSCAN_PATH_TILES_FROM_BOUNDARY)
+        return run_unaligned_rows(d_in, d_out, rows, cols, dt, exclusive, reverse, d_ws, plan, clear_first, s);
     const int size = choose_tile(dt, rows, cols);
     const size_t tile = tile_elems(dt, size);
     const size_t tpr = (cols + tile - 1) / tile;
@@ -2131,16 +2207,9 @@ tcuscan_status_t run(const void *d_in, void *d_out, size_t rows, size_t cols, in
     P.ws = need ? (WsHeader *)d_ws : nullptr;
     P.reverse = reverse ? 1u : 0u;
     P.tile_desc = nullptr;
-    // Every call gets a fresh tag, so status words of earlier calls are stale by construction.  A call
-    // recorded into a graph is replayed with the SAME tag; it therefore clears its status words first
-    // (with a fill kernel, which a graph replays correctly).
-    P.tag = g_calls.fetch_add(1u, std::memory_order_relaxed) % kTagMod + 1u;
-    if (P.ws && tpr > 1) {
-        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-        if (hipStreamIsCapturing(s, &cs) != hipSuccess) { (void)hipGetLastError(); cs = hipStreamCaptureStatusNone; }
-        if (cs == hipStreamCaptureStatusActive &&
-            launch_fill((char *)d_ws + sizeof(WsHeader), 8 * kStatusStride * rows * tpr, s) != hipSuccess) return TCUSCAN_ERR_HIP;
-    }
+    // Every call gets a fresh tag, so status words of earlier calls are stale by construction.
+    const tcuscan_status_t bst = begin_chain(P, P.ws && tpr > 1 ? d_ws : nullptr, rows * tpr, clear_first, s);
+    if (bst != TCUSCAN_OK) return bst;
     hipError_t e;
     switch (dt) {
     case TCUSCAN_I32_I32:  e = launch_dt<TCUSCAN_I32_I32>(P, exclusive != 0, size, s); break;
@@ -2253,11 +2322,8 @@ tcuscan_status_t run_segmented_flat(const void *d_in, void *d_out, const long lo
     P.tiles_per_row = 0; P.num_tiles = (uint32_t)tiles;
     P.ws = (WsHeader *)d_ws;
     P.reverse = reverse ? 1u : 0u; P.tile_desc = nullptr;
-    P.tag = g_calls.fetch_add(1u, std::memory_order_relaxed) % kTagMod + 1u;
-    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing(s, &cs) != hipSuccess) { (void)hipGetLastError(); cs = hipStreamCaptureStatusNone; }
-    if (cs == hipStreamCaptureStatusActive && launch_fill((char *)d_ws + sizeof(WsHeader), 8 * kStatusStride * tiles, s) != hipSuccess)
-        return TCUSCAN_ERR_HIP;
+    const tcuscan_status_t bst = begin_chain(P, d_ws, tiles, true, s);
+    if (bst != TCUSCAN_OK) return bst;
     const long long *off = d_offsets; const uint32_t *hd = heads; uint32_t sh = shift;
     void *args[] = {&P, &off, &hd, &sh};
     const bool ex = exclusive != 0;
@@ -2276,34 +2342,42 @@ tcuscan_status_t run_segmented_flat(const void *d_in, void *d_out, const long lo
 // long for one wavefront each: the segmented kernel without descriptors (it derives the row from the tile index), so
 // that every full granule takes the 128-bit path (element by element such rows run at 22 .. 40 % of peak instead of
 // 74 .. 79 %).  A row and the few elements in front of it can need one tile more than the row alone; when the
-// caller's workspace has no status word for that tile, the call is left to the element-wise path (returns false).
-bool run_unaligned_rows(const void *d_in, void *d_out, size_t rows, size_t cols, int dt, int exclusive, int reverse, void *d_ws,
-                        size_t ws_bytes, hipStream_t s, tcuscan_status_t &st)
+// caller's workspace has no status word for that tile (it was sized by an older rule than tcuscan_workspace_bytes'), the
+// other tile size is tried, and failing that the call is left to the element-wise path.
+Plan plan_for(uintptr_t in_addr, size_t rows, size_t cols, int dt, bool ws_usable, size_t ws_bytes)
 {
-    // the tile the average-length rule picks, or the other one if the workspace only has the status words for that
+    Plan plan = {TCUSCAN_PATH_TILES, kSegSmall, 0, 0};
+    const size_t row_max = in_size(dt) == 4 ? kShortRowMax32 : kShortRowMax;
+    if (rows >= kShortRowMinRows && cols <= row_max) { plan.path = TCUSCAN_PATH_ROWS; return plan; }
+    if ((in_addr & 15) == 0 && (rows <= 1 || (cols * in_size(dt)) % 16 == 0)) return plan;       // every row starts at a 16-byte boundary
+    // the tile the row-length rule picks, or the other one if the workspace only has the status words for that
     int cls = cols < ((size_t)1 << 19) ? kSegSmall : kSegLarge;
-    size_t tpr = 0, need = 0;
     for (int attempt = 0; attempt < 2; ++attempt, cls = cls == kSegSmall ? kSegLarge : kSegSmall) {
         const size_t tile = seg_tile_elems(dt, cls), granule = 16 / in_size(dt);
-        tpr = (cols + granule - 1 + tile - 1) / tile;
-        need = tpr > 1 ? sizeof(WsHeader) + 8 * kStatusStride * rows * tpr : 0;
-        if (rows * tpr <= 0x7FFFFFFFull && rows <= 0x7FFFFFFFull && (!need || (d_ws && ws_bytes >= need && ((uintptr_t)d_ws % 8) == 0))) break;
-        if (attempt == 1) return false;
+        const size_t tpr = (cols + granule - 1 + tile - 1) / tile;
+        const size_t need = tpr > 1 ? sizeof(WsHeader) + 8 * kStatusStride * rows * tpr : 0;
+        if (rows * tpr <= 0x7FFFFFFFull && rows <= 0x7FFFFFFFull && (!need || (ws_usable && ws_bytes >= need))) {
+            plan.path = TCUSCAN_PATH_TILES_FROM_BOUNDARY; plan.seg_cls = cls; plan.tpr = tpr; plan.need = need;
+            return plan;
+        }
     }
+    plan.path = TCUSCAN_PATH_ELEMENTWISE;       // a workspace sized by an older rule: one status word per row short
+    return plan;
+}
+
+tcuscan_status_t run_unaligned_rows(const void *d_in, void *d_out, size_t rows, size_t cols, int dt, int exclusive, int reverse, void *d_ws,
+                                    const Plan &plan, bool clear_first, hipStream_t s)
+{
+    const int cls = plan.seg_cls;
+    const size_t tpr = plan.tpr, need = plan.need;
     Params P;
     P.in = d_in; P.out = d_out; P.rows = rows; P.cols = rows * cols;     // cols: the length of the arrays, as for segmented calls
     P.tiles_per_row = (uint32_t)tpr; P.num_tiles = (uint32_t)(rows * tpr);
     P.ws = need ? (WsHeader *)d_ws : nullptr;
     P.reverse = reverse ? 1u : 0u;
     P.tile_desc = nullptr;
-    P.tag = g_calls.fetch_add(1u, std::memory_order_relaxed) % kTagMod + 1u;
-    st = TCUSCAN_ERR_HIP;
-    if (need) {
-        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-        if (hipStreamIsCapturing(s, &cs) != hipSuccess) { (void)hipGetLastError(); cs = hipStreamCaptureStatusNone; }
-        if (cs == hipStreamCaptureStatusActive && launch_fill((char *)d_ws + sizeof(WsHeader), 8 * kStatusStride * rows * tpr, s) != hipSuccess)
-            return true;
-    }
+    const tcuscan_status_t bst = begin_chain(P, need ? d_ws : nullptr, rows * tpr, clear_first, s);
+    if (bst != TCUSCAN_OK) return bst;
     hipError_t e;
     switch (dt) {
     case TCUSCAN_I32_I32:  e = launch_seg<TCUSCAN_I32_I32>(P, exclusive != 0, cls, s); break;
@@ -2312,8 +2386,7 @@ bool run_unaligned_rows(const void *d_in, void *d_out, size_t rows, size_t cols,
     case TCUSCAN_F32_F32:  e = launch_seg<TCUSCAN_F32_F32>(P, exclusive != 0, cls, s); break;
     default:               e = launch_seg<TCUSCAN_BF16_F32>(P, exclusive != 0, cls, s); break;
     }
-    if (e == hipSuccess) st = TCUSCAN_OK;
-    return true;
+    return e == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
 }
 
 tcuscan_status_t run_segmented(const void *d_in, void *d_out, const long long *d_offsets, size_t rows, size_t total, int dt,
@@ -2329,6 +2402,9 @@ tcuscan_status_t run_segmented(const void *d_in, void *d_out, const long long *d
     if (!d_ws || ws_bytes < L.total_bytes || ((uintptr_t)d_ws % 8) != 0) return TCUSCAN_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     const int cls = seg_tile_class(dt, rows, total);
+    // This call puts row maps where a later call of another shape may expect status words: the workspace is no
+    // longer known to be clean (segmented calls themselves clear their status words in front of every run).
+    g_clean.mark_dirty((uintptr_t)d_ws, chain_tags::call_id(g_calls.load(std::memory_order_relaxed)).generation);
     if (L.heads_words && g_seg_flat.load(std::memory_order_relaxed))
         return run_segmented_flat(d_in, d_out, d_offsets, rows, total, dt, exclusive, reverse, d_ws, L, s);
     const size_t tile = seg_tile_elems(dt, cls);
@@ -2343,8 +2419,9 @@ tcuscan_status_t run_segmented(const void *d_in, void *d_out, const long long *d
             return TCUSCAN_ERR_HIP;
     }
     // step 2: first tile of every row = exclusive scan of the counts (this library's own int32 scan)
+    // (its workspace is a region of this one whose former contents depend on the shapes of earlier calls: cleared first)
     tcuscan_status_t st = run(counts, starts, 1, rows + 1, TCUSCAN_I32_I32, 1, 0, L.inner_bytes ? (char *)d_ws + L.inner_off : nullptr,
-                              L.inner_bytes, stream);
+                              L.inner_bytes, stream, true);
     if (st != TCUSCAN_OK) return st;
     {   // step 3: one descriptor per tile
         const uint32_t *ts = starts; const long long *off = d_offsets; size_t r = rows; uint32_t mt = (uint32_t)L.max_tiles;
@@ -2359,11 +2436,8 @@ tcuscan_status_t run_segmented(const void *d_in, void *d_out, const long long *d
     P.ws = (WsHeader *)d_ws;
     P.reverse = reverse ? 1u : 0u;
     P.tile_desc = desc;
-    P.tag = g_calls.fetch_add(1u, std::memory_order_relaxed) % kTagMod + 1u;
-    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing(s, &cs) != hipSuccess) { (void)hipGetLastError(); cs = hipStreamCaptureStatusNone; }
-    if (cs == hipStreamCaptureStatusActive &&
-        launch_fill((char *)d_ws + sizeof(WsHeader), 8 * kStatusStride * L.max_tiles, s) != hipSuccess) return TCUSCAN_ERR_HIP;
+    const tcuscan_status_t bst = begin_chain(P, d_ws, L.max_tiles, true, s);
+    if (bst != TCUSCAN_OK) return bst;
     hipError_t e;
     switch (dt) {
     case TCUSCAN_I32_I32:  e = launch_seg<TCUSCAN_I32_I32>(P, exclusive != 0, cls, s); break;
@@ -2387,14 +2461,7 @@ tcuscan_status_t flag_kernel_params(Params &P, size_t n, size_t tile, void *d_ws
     P.tiles_per_row = (uint32_t)tiles; P.num_tiles = (uint32_t)tiles;
     P.ws = need ? (WsHeader *)d_ws : nullptr;
     P.reverse = 0; P.tile_desc = nullptr;
-    P.tag = g_calls.fetch_add(1u, std::memory_order_relaxed) % kTagMod + 1u;
-    if (need) {
-        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-        if (hipStreamIsCapturing(s, &cs) != hipSuccess) { (void)hipGetLastError(); cs = hipStreamCaptureStatusNone; }
-        if (cs == hipStreamCaptureStatusActive &&
-            launch_fill((char *)d_ws + sizeof(WsHeader), 8 * kStatusStride * tiles, s) != hipSuccess) return TCUSCAN_ERR_HIP;
-    }
-    return TCUSCAN_OK;
+    return begin_chain(P, need ? d_ws : nullptr, tiles, false, s);
 }
 
 // 2048 elements per wavefront (their words stay in registers from the load to the scatter), 8 wavefronts: 16384 per
@@ -2510,8 +2577,14 @@ tcuscan_status_t tcuscan_set_tile_policy(int policy)
 size_t tcuscan_workspace_bytes(size_t rows, size_t cols, tcuscan_dtype_t dt)
 {
     if (!valid_dtype((int)dt) || rows == 0 || cols == 0) return 0;
-    const size_t tpr = (cols + kSmallTile - 1) / kSmallTile;
-    if (tpr <= 1) return 0;
+    // One status word per small tile of a row -- counted for the row AND the elements in front of it up to the
+    // 16-byte boundary below (fewer than a granule): rows that do not start at such a boundary are tiled from there,
+    // which takes one tile more when the row's length is within a granule of a multiple of the tile.
+    // (Rows of up to one small tile never need a workspace: if such a row needs a second small tile, it fits one
+    // large tile.)
+    if (cols <= kSmallTile) return 0;
+    const size_t granule = 16 / in_size((int)dt);
+    const size_t tpr = (cols + granule - 1 + kSmallTile - 1) / kSmallTile;
     return sizeof(WsHeader) + 8 * kStatusStride * rows * tpr;
 }
 
@@ -2561,6 +2634,35 @@ tcuscan_status_t tcuscan_segmented(const void *d_in, void *d_out, const long lon
     if (flags & ~(unsigned)(TCUSCAN_EXCLUSIVE | TCUSCAN_REVERSE)) return TCUSCAN_ERR_INVALID_ARG;
     return run_segmented(d_in, d_out, d_offsets, rows, total, (int)dt, (flags & TCUSCAN_EXCLUSIVE) != 0, (flags & TCUSCAN_REVERSE) != 0,
                          d_ws, ws_bytes, stream);
+}
+
+int tcuscan_path_for(const void *d_in, size_t rows, size_t cols, tcuscan_dtype_t dt, size_t ws_bytes)
+{
+    if (!valid_dtype((int)dt) || rows == 0 || cols == 0) return -1;
+    return plan_for((uintptr_t)d_in, rows, cols, (int)dt, true, ws_bytes).path;
+}
+
+tcuscan_status_t tcuscan_set_chain_policy(int policy)
+{
+    if (policy < 0 || policy > 1) return TCUSCAN_ERR_INVALID_ARG;
+    g_chain_policy.store(policy, std::memory_order_relaxed);
+    return TCUSCAN_OK;
+}
+
+tcuscan_status_t tcuscan_test_advance_calls(unsigned long long calls)
+{
+    g_calls.fetch_add(calls, std::memory_order_relaxed);
+    return TCUSCAN_OK;
+}
+
+unsigned long long tcuscan_test_tag_period(void) { return chain_tags::kTagMod; }
+
+tcuscan_status_t tcuscan_test_chain_fault(unsigned spin_limit, long long mute_tile)
+{
+    if (mute_tile > 0x7FFFFFFFll) return TCUSCAN_ERR_INVALID_ARG;
+    g_spin_limit.store(spin_limit ? spin_limit : kDefaultSpinLimit, std::memory_order_relaxed);
+    g_mute_tile.store(mute_tile < 0 ? kNoTile : (uint32_t)mute_tile, std::memory_order_relaxed);
+    return TCUSCAN_OK;
 }
 
 tcuscan_status_t tcuscan_workspace_fault(const void *d_ws, tcuscan_stream_t stream, unsigned *h_fault)

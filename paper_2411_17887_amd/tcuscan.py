@@ -20,7 +20,9 @@ EXPORTS = ["tcuscan_workspace_bytes", "tcuscan_workspace_init", "tcuscan_inclusi
            "tcuscan_batched", "tcuscan_scan", "tcuscan_segmented_workspace_bytes", "tcuscan_segmented", "tcuscan_tile_elems", "tcuscan_large_tile_elems", "tcuscan_huge_tile_elems",
            "tcuscan_set_tile_policy", "tcuscan_set_segmented_form",
            "tcuscan_workspace_fault", "tcuscan_matmulscan_levels", "tcuscan_matmulscan_levels_radix", "tcuscan_compact_u32",
-           "tcuscan_split_radix_sort_u32", "tcuscan_set_sort_fusion", "tcuscan_status_string"]
+           "tcuscan_split_radix_sort_u32", "tcuscan_set_sort_fusion", "tcuscan_status_string",
+           "tcuscan_set_chain_policy", "tcuscan_path_for", "tcuscan_measure_stream",
+           "tcuscan_test_advance_calls", "tcuscan_test_tag_period", "tcuscan_test_chain_fault"]
 
 _lib = None
 
@@ -70,6 +72,18 @@ def load() -> ctypes.CDLL:
         L.tcuscan_matmulscan_levels_radix.argtypes = [vp, vp, sz, ci, ci, ci, vp, vp]
         L.tcuscan_compact_u32.argtypes = [vp, vp, vp, sz, vp, vp, vp, sz, vp]
         L.tcuscan_split_radix_sort_u32.argtypes = [vp, vp, sz, ci, vp, vp, vp, vp, vp, sz, vp]
+        L.tcuscan_set_chain_policy.argtypes = [ci]
+        L.tcuscan_set_chain_policy.restype = ci
+        L.tcuscan_path_for.argtypes = [vp, sz, sz, ci, sz]
+        L.tcuscan_path_for.restype = ci
+        L.tcuscan_measure_stream.argtypes = [vp, vp, sz, ci, ctypes.c_uint, vp]
+        L.tcuscan_measure_stream.restype = ci
+        L.tcuscan_test_advance_calls.argtypes = [ctypes.c_ulonglong]
+        L.tcuscan_test_advance_calls.restype = ci
+        L.tcuscan_test_tag_period.argtypes = []
+        L.tcuscan_test_tag_period.restype = ctypes.c_ulonglong
+        L.tcuscan_test_chain_fault.argtypes = [ctypes.c_uint, ctypes.c_longlong]
+        L.tcuscan_test_chain_fault.restype = ci
         L.tcuscan_status_string.argtypes = [ci]
         L.tcuscan_status_string.restype = ctypes.c_char_p
         for f in ("tcuscan_workspace_init", "tcuscan_inclusive", "tcuscan_exclusive", "tcuscan_batched", "tcuscan_scan", "tcuscan_segmented",
@@ -230,6 +244,41 @@ def split_radix_sort_u32(keys, keys_tmp, flags, positions, vals=None, vals_tmp=N
                                              _ptr(flags), _ptr(positions), *_ws_args(ws), _stream(stream))
     if rc != OK:
         raise TcuscanError(rc, "tcuscan_split_radix_sort_u32")
+
+
+PATH_ROWS, PATH_TILES, PATH_TILES_FROM_BOUNDARY, PATH_ELEMENTWISE = 0, 1, 2, 3
+
+
+def path_for(in_ptr: int, rows: int, cols: int, dt, ws_bytes: int) -> int:
+    return int(load().tcuscan_path_for(int(in_ptr), rows, cols, _dt(dt), ws_bytes))
+
+
+def set_chain_policy(policy: int) -> None:
+    """0: tiles in workgroup-index order (default); 1: tiles drawn from a ticket counter."""
+    rc = load().tcuscan_set_chain_policy(int(policy))
+    if rc != OK:
+        raise TcuscanError(rc, "tcuscan_set_chain_policy")
+
+
+def measure_stream(x, out, out_bytes: int, in_bytes_per_out_word: int, variant: int = 0, stream=None) -> None:
+    """The streaming yardstick kernel (measurement only)."""
+    rc = load().tcuscan_measure_stream(_ptr(x), _ptr(out), out_bytes, int(in_bytes_per_out_word), int(variant), _stream(stream))
+    if rc != OK:
+        raise TcuscanError(rc, "tcuscan_measure_stream")
+
+
+def test_advance_calls(calls: int) -> None:
+    load().tcuscan_test_advance_calls(int(calls))
+
+
+def test_tag_period() -> int:
+    return int(load().tcuscan_test_tag_period())
+
+
+def test_chain_fault(spin_limit: int = 0, mute_tile: int = -1) -> None:
+    rc = load().tcuscan_test_chain_fault(int(spin_limit), int(mute_tile))
+    if rc != OK:
+        raise TcuscanError(rc, "tcuscan_test_chain_fault")
 
 
 def workspace_fault(ws, stream=None) -> int:

@@ -39,7 +39,12 @@ def test_workspace_sizing():
         assert tcuscan.workspace_bytes(1, tile, kind) == 0            # one tile per row: no carry chain
         assert tcuscan.workspace_bytes(1000, tile, kind) == 0
         assert tcuscan.workspace_bytes(1, tile + 1, kind) == 256 + 64 * 2
-        assert tcuscan.workspace_bytes(3, 5 * tile - 1, kind) == 256 + 64 * 15
+        # a row and the part of a 16-byte granule in front of it: one more tile when the length is within a granule
+        # of a multiple of the tile
+        granule = 16 // {"i8": 1, "f16": 2, "bf16": 2}.get(kind, 4)
+        assert tcuscan.workspace_bytes(3, 5 * tile - granule + 1, kind) == 256 + 64 * 15
+        assert tcuscan.workspace_bytes(3, 5 * tile - granule + 2, kind) == 256 + 64 * 18
+        assert tcuscan.workspace_bytes(3, 5 * tile, kind) == 256 + 64 * 18
         assert tcuscan.workspace_bytes(0, 100, kind) == 0 and tcuscan.workspace_bytes(4, 0, kind) == 0
     assert tcuscan.workspace_bytes(1, 1 << 20, 9) == 0 and tcuscan.tile_elems(9) == 0
 
@@ -75,9 +80,9 @@ def test_bad_arguments_are_rejected_before_any_launch():
     assert call("tcuscan_inclusive", FAKE, FAKE, 10, tcuscan.F16_F32, 0, 0, 0) == tcuscan.ERR_INVALID_ARG
     assert call("tcuscan_inclusive", FAKE, FAKE, 10, tcuscan.I8_I32, 0, 0, 0) == tcuscan.ERR_INVALID_ARG
     # workspace missing / too small / misaligned when the row spans several tiles
-    n = 3 * tile
+    n = 3 * tile - 100            # (not within a granule of a multiple of the tile: the size query is the exact minimum)
     need = tcuscan.workspace_bytes(1, n, "f32")
-    assert need > 0
+    assert need == 256 + 64 * 3
     assert call("tcuscan_inclusive", FAKE, FAKE + (1 << 30), n, tcuscan.F32_F32, 0, 0, 0) == tcuscan.ERR_WORKSPACE
     assert call("tcuscan_inclusive", FAKE, FAKE + (1 << 30), n, tcuscan.F32_F32, FAKE, need - 1, 0) == tcuscan.ERR_WORKSPACE
     assert call("tcuscan_inclusive", FAKE, FAKE + (1 << 30), n, tcuscan.F32_F32, FAKE + 4, need, 0) == tcuscan.ERR_WORKSPACE
@@ -147,3 +152,46 @@ def test_process_wide_knobs():
         tcuscan.set_sort_fusion(1)
         tcuscan.set_segmented_form(True)
         call("tcuscan_set_tile_policy", 0)
+
+
+def test_path_query_and_workspace_promise():
+    """tcuscan_path_for is the host-side decision run() itself follows.  With a workspace of tcuscan_workspace_bytes()
+    no shape is left to the element-wise path."""
+    A, U = 0x10000, 0x10004            # a 16-byte aligned address and one that is not
+    for kind, esz in (("i8", 1), ("f16", 2), ("bf16", 2), ("f32", 4), ("i32", 4)):
+        tile, large = tcuscan.tile_elems(kind), tcuscan.large_tile_elems(kind)
+        g = 16 // esz
+        assert tcuscan.path_for(A, 100, 512, kind, 0) == tcuscan.PATH_ROWS
+        assert tcuscan.path_for(U, 100, 513, kind, 0) == tcuscan.PATH_ROWS           # short rows handle their own alignment
+        assert tcuscan.path_for(A, 1, 10 * tile + 3, kind, 1 << 20) == tcuscan.PATH_TILES
+        assert tcuscan.path_for(A, 4, 10 * tile, kind, 1 << 20) == tcuscan.PATH_TILES
+        for rows, cols in ((1, 10 * tile), (3, 10 * tile + 1), (5, 3 * tile), (7, 2 * large), (2, 64 * large), (3, 64 * large - 1),
+                           (1000, tile), (9, 2 * tile - 1)):
+            ptr = U if rows == 1 or (cols * esz) % 16 == 0 else A
+            new = tcuscan.workspace_bytes(rows, cols, kind)
+            assert tcuscan.path_for(ptr, rows, cols, kind, new) == tcuscan.PATH_TILES_FROM_BOUNDARY, (kind, rows, cols)
+            # a workspace sized by the older rule (tiles of the rows alone) is still enough for one of the two tile sizes
+            old_tiles = -(-cols // tile)
+            old = 256 + 64 * rows * old_tiles if old_tiles > 1 else 0
+            assert old <= new and tcuscan.path_for(ptr, rows, cols, kind, old) == tcuscan.PATH_TILES_FROM_BOUNDARY
+    assert tcuscan.path_for(A, 0, 5, "f32", 0) == -1 and tcuscan.path_for(A, 5, 5, 9, 0) == -1
+
+
+def test_chain_knobs_and_stream_kernel_reject_bad_arguments():
+    try:
+        assert call("tcuscan_set_chain_policy", 1) == tcuscan.OK
+        for bad in (-1, 2):
+            assert call("tcuscan_set_chain_policy", bad) == tcuscan.ERR_INVALID_ARG
+    finally:
+        assert call("tcuscan_set_chain_policy", 0) == tcuscan.OK
+    assert call("tcuscan_test_chain_fault", 0, 1 << 40) == tcuscan.ERR_INVALID_ARG
+    assert call("tcuscan_test_chain_fault", 0, -1) == tcuscan.OK
+    assert tcuscan.test_tag_period() == (1 << 30) - 2
+    # streaming yardstick: mixes 0, 1, 2, 4 only; aligned pointers; whole 64-byte groups
+    assert call("tcuscan_measure_stream", FAKE, FAKE, 0, 1, 0, 0) == tcuscan.OK
+    assert call("tcuscan_measure_stream", FAKE, FAKE, 64, 3, 0, 0) == tcuscan.ERR_INVALID_ARG
+    assert call("tcuscan_measure_stream", FAKE, FAKE, 64, 1, 4, 0) == tcuscan.ERR_INVALID_ARG
+    assert call("tcuscan_measure_stream", FAKE, FAKE, 64, 1, 0x800, 0) == tcuscan.ERR_INVALID_ARG
+    assert call("tcuscan_measure_stream", FAKE, FAKE + 4, 64, 1, 0, 0) == tcuscan.ERR_INVALID_ARG
+    assert call("tcuscan_measure_stream", 0, FAKE, 64, 2, 0, 0) == tcuscan.ERR_INVALID_ARG
+    assert call("tcuscan_measure_stream", FAKE, FAKE, 48, 4, 0, 0) == tcuscan.ERR_INVALID_ARG
