@@ -207,6 +207,22 @@ tcuscan_status_t tcuscan_set_segmented_form(int flat);
 tcuscan_status_t tcuscan_workspace_fault(const void *d_ws, tcuscan_stream_t stream, unsigned *h_fault);
 
 /*
+ * tcuscan_scan for callers that cannot allocate and have no workspace to pass: code running under stream capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as tcuscan_scan, without d_ws /
+ * ws_bytes: the carry chain's status words live in a fixed array of TCUSCAN_STATIC_SCRATCH_BYTES inside the library's
+ * device code (one copy per GPU, held until the process ends).  The call allocates and frees nothing.  Shapes whose
+ * tcuscan_workspace_bytes() exceed the array (more than 65,536 small tiles: e.g. one row of more than 2^29 elements)
+ * return TCUSCAN_ERR_WORKSPACE.  All calls on one GPU share the array: calls that overlap in time on the same GPU
+ * (two streams, two threads) race and give wrong results; calls in stream order are fine, whatever their shapes.  The
+ * array's address is looked up on the first call on each GPU (hipGetSymbolAddress, with that GPU current); make that
+ * first call outside stream capture.  Its fault word is read with tcuscan_workspace_fault(TCUSCAN_STATIC_SCRATCH, ..).
+ */
+#define TCUSCAN_STATIC_SCRATCH_BYTES 4194560 /* 256-byte header + 65,536 status slots of 64 bytes */
+#define TCUSCAN_STATIC_SCRATCH ((const void *)(size_t)1)
+tcuscan_status_t tcuscan_scan_static(const void *d_in, void *d_out, size_t rows, size_t cols, tcuscan_dtype_t dt, unsigned flags,
+                                     tcuscan_stream_t stream);
+
+/*
  * Which way tcuscan_scan takes for this input pointer, shape and workspace size (a host-side query, nothing is
  * enqueued; d_in is only looked at for its alignment).  Rows that start at 16-byte boundaries take ROWS or TILES; other
  * rows are tiled from the boundary below (Section 2.2's segments, with BatchMatMul's zero-pad in front), unless the

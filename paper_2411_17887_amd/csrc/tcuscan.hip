@@ -38,6 +38,7 @@
 #include <stdint.h>
 
 #include <atomic>
+#include <mutex>
 
 #include "../../include/tcuscan.h"
 #include "chain_tags.h"
@@ -2553,6 +2554,36 @@ tcuscan_status_t tcuscan_internal_compact_fused(const void *d_values, const void
     return hipLaunchKernel((const void *)compact_kernel<NT, W>, dim3(P.num_tiles), dim3(64 * W), args, 0, s) == hipSuccess ? TCUSCAN_OK : TCUSCAN_ERR_HIP;
 }
 
+// ---- the entry point that allocates nothing: its carry-chain workspace is a fixed device array of the library
+//
+// One copy of the array exists on every GPU the library's code object is loaded on, each at its own address; in host
+// code the array's NAME is only a handle for hipGetSymbolAddress (passing it to a kernel would hand the kernel a host
+// address).  The device address is looked up once per device, with that device current, and kept.
+static __device__ __align__(256) unsigned char g_static_scratch[TCUSCAN_STATIC_SCRATCH_BYTES];
+static_assert(TCUSCAN_STATIC_SCRATCH_BYTES % 256 == 0 && TCUSCAN_STATIC_SCRATCH_BYTES > sizeof(WsHeader), "scratch size");
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mu;
+void *g_static_ptr[kMaxDevices] = {};          // device address of g_static_scratch on device i (null: not looked up yet)
+
+tcuscan_status_t static_scratch_of_current_device(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return TCUSCAN_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return TCUSCAN_ERR_HIP; }
+        g_static_ptr[dev] = p;
+    }
+    *out = g_static_ptr[dev];
+    return TCUSCAN_OK;
+}
+
+}  // namespace
+
 extern "C" {
 
 size_t tcuscan_tile_elems(tcuscan_dtype_t dt) { return valid_dtype((int)dt) ? kSmallTile : 0; }
@@ -2665,9 +2696,30 @@ tcuscan_status_t tcuscan_test_chain_fault(unsigned spin_limit, long long mute_ti
     return TCUSCAN_OK;
 }
 
+tcuscan_status_t tcuscan_scan_static(const void *d_in, void *d_out, size_t rows, size_t cols, tcuscan_dtype_t dt, unsigned flags,
+                                     tcuscan_stream_t stream)
+{
+    if (flags & ~(unsigned)(TCUSCAN_EXCLUSIVE | TCUSCAN_REVERSE)) return TCUSCAN_ERR_INVALID_ARG;
+    if (!valid_dtype((int)dt)) return TCUSCAN_ERR_UNSUPPORTED;
+    if (rows == 0 || cols == 0) return TCUSCAN_OK;
+    if (rows > 0x7FFFFFFFull / ((cols + kSmallTile - 1) / kSmallTile)) return TCUSCAN_ERR_UNSUPPORTED;
+    if (tcuscan_workspace_bytes(rows, cols, dt) > sizeof(g_static_scratch)) return TCUSCAN_ERR_WORKSPACE;   // beyond the fixed scratch
+    void *scratch = nullptr;
+    const tcuscan_status_t st = static_scratch_of_current_device(&scratch);
+    if (st != TCUSCAN_OK) return st;
+    return run(d_in, d_out, rows, cols, (int)dt, (flags & TCUSCAN_EXCLUSIVE) != 0, (flags & TCUSCAN_REVERSE) != 0,
+               scratch, sizeof(g_static_scratch), stream);
+}
+
 tcuscan_status_t tcuscan_workspace_fault(const void *d_ws, tcuscan_stream_t stream, unsigned *h_fault)
 {
     if (!d_ws || !h_fault) return TCUSCAN_ERR_INVALID_ARG;
+    if (d_ws == TCUSCAN_STATIC_SCRATCH) {          // the fixed scratch of tcuscan_scan_static on the current device
+        void *scratch = nullptr;
+        const tcuscan_status_t st = static_scratch_of_current_device(&scratch);
+        if (st != TCUSCAN_OK) return st;
+        d_ws = scratch;
+    }
     if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return TCUSCAN_ERR_HIP;
     const WsHeader *h = (const WsHeader *)d_ws;
     if (hipMemcpy(h_fault, &h->fault, sizeof(unsigned), hipMemcpyDeviceToHost) != hipSuccess) return TCUSCAN_ERR_HIP;

@@ -21,7 +21,7 @@ EXPORTS = ["tcuscan_workspace_bytes", "tcuscan_workspace_init", "tcuscan_inclusi
            "tcuscan_set_tile_policy", "tcuscan_set_segmented_form",
            "tcuscan_workspace_fault", "tcuscan_matmulscan_levels", "tcuscan_matmulscan_levels_radix", "tcuscan_compact_u32",
            "tcuscan_split_radix_sort_u32", "tcuscan_set_sort_fusion", "tcuscan_status_string",
-           "tcuscan_set_chain_policy", "tcuscan_path_for", "tcuscan_measure_stream",
+           "tcuscan_set_chain_policy", "tcuscan_scan_static", "tcuscan_path_for", "tcuscan_measure_stream",
            "tcuscan_test_advance_calls", "tcuscan_test_tag_period", "tcuscan_test_chain_fault"]
 
 _lib = None
@@ -74,6 +74,8 @@ def load() -> ctypes.CDLL:
         L.tcuscan_split_radix_sort_u32.argtypes = [vp, vp, sz, ci, vp, vp, vp, vp, vp, sz, vp]
         L.tcuscan_set_chain_policy.argtypes = [ci]
         L.tcuscan_set_chain_policy.restype = ci
+        L.tcuscan_scan_static.argtypes = [vp, vp, sz, sz, ci, ctypes.c_uint, vp]
+        L.tcuscan_scan_static.restype = ci
         L.tcuscan_path_for.argtypes = [vp, sz, sz, ci, sz]
         L.tcuscan_path_for.restype = ci
         L.tcuscan_measure_stream.argtypes = [vp, vp, sz, ci, ctypes.c_uint, vp]
@@ -246,7 +248,16 @@ def split_radix_sort_u32(keys, keys_tmp, flags, positions, vals=None, vals_tmp=N
         raise TcuscanError(rc, "tcuscan_split_radix_sort_u32")
 
 
+STATIC_SCRATCH = "static"      # workspace_fault(STATIC_SCRATCH): the fixed scratch of scan_static on the current GPU
+STATIC_SCRATCH_BYTES = 4194560
 PATH_ROWS, PATH_TILES, PATH_TILES_FROM_BOUNDARY, PATH_ELEMENTWISE = 0, 1, 2, 3
+
+
+def scan_static(x, out, rows: int, cols: int, dt, flags: int = 0, stream=None) -> None:
+    """tcuscan_scan without a workspace argument: the library's fixed device scratch is used; allocates nothing."""
+    rc = load().tcuscan_scan_static(_ptr(x), _ptr(out), rows, cols, _dt(dt), int(flags), _stream(stream))
+    if rc != OK:
+        raise TcuscanError(rc, "tcuscan_scan_static")
 
 
 def path_for(in_ptr: int, rows: int, cols: int, dt, ws_bytes: int) -> int:
@@ -283,7 +294,7 @@ def test_chain_fault(spin_limit: int = 0, mute_tile: int = -1) -> None:
 
 def workspace_fault(ws, stream=None) -> int:
     v = ctypes.c_uint(0)
-    rc = load().tcuscan_workspace_fault(_ptr(ws), _stream(stream), ctypes.byref(v))
+    rc = load().tcuscan_workspace_fault(1 if isinstance(ws, str) and ws == STATIC_SCRATCH else _ptr(ws), _stream(stream), ctypes.byref(v))
     if rc != OK:
         raise TcuscanError(rc, "tcuscan_workspace_fault")
     return int(v.value)

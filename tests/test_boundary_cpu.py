@@ -177,7 +177,7 @@ def test_path_query_and_workspace_promise():
     assert tcuscan.path_for(A, 0, 5, "f32", 0) == -1 and tcuscan.path_for(A, 5, 5, 9, 0) == -1
 
 
-def test_chain_knobs_and_stream_kernel_reject_bad_arguments():
+def test_chain_knobs_static_entry_and_stream_kernel_reject_bad_arguments():
     try:
         assert call("tcuscan_set_chain_policy", 1) == tcuscan.OK
         for bad in (-1, 2):
@@ -187,6 +187,14 @@ def test_chain_knobs_and_stream_kernel_reject_bad_arguments():
     assert call("tcuscan_test_chain_fault", 0, 1 << 40) == tcuscan.ERR_INVALID_ARG
     assert call("tcuscan_test_chain_fault", 0, -1) == tcuscan.OK
     assert tcuscan.test_tag_period() == (1 << 30) - 2
+    # the entry point without a workspace argument: same host-side checks, and a clear refusal beyond its fixed scratch
+    assert call("tcuscan_scan_static", 0, 0, 0, 10, tcuscan.F32_F32, 0, 0) == tcuscan.OK
+    assert call("tcuscan_scan_static", FAKE, FAKE + (1 << 30), 1, 10, tcuscan.F32_F32, 4, 0) == tcuscan.ERR_INVALID_ARG
+    assert call("tcuscan_scan_static", FAKE, FAKE + (1 << 30), 1, 10, 9, 0, 0) == tcuscan.ERR_UNSUPPORTED
+    tile = tcuscan.tile_elems("i8")
+    assert tcuscan.workspace_bytes(1, 65535 * tile, "i8") <= tcuscan.STATIC_SCRATCH_BYTES < tcuscan.workspace_bytes(1, 65536 * tile + 1, "i8")
+    assert call("tcuscan_scan_static", FAKE, FAKE + (1 << 34), 1, 65536 * tile + 1, tcuscan.I8_I32, 0, 0) == tcuscan.ERR_WORKSPACE
+    assert call("tcuscan_scan_static", FAKE, FAKE + (1 << 34), 70000, 2 * tile, tcuscan.I8_I32, 0, 0) == tcuscan.ERR_WORKSPACE
     # streaming yardstick: mixes 0, 1, 2, 4 only; aligned pointers; whole 64-byte groups
     assert call("tcuscan_measure_stream", FAKE, FAKE, 0, 1, 0, 0) == tcuscan.OK
     assert call("tcuscan_measure_stream", FAKE, FAKE, 64, 3, 0, 0) == tcuscan.ERR_INVALID_ARG
