@@ -7,14 +7,23 @@ A step is one pass of the whole hot path (tile load, MFMA local scans, in-workgr
 carry chain between workgroups, down-sweep add, store) over one batch of seeded synthetic
 input that is already resident in HBM.  Prints ONE JSON line.  `value` is G elements/s of the
 headline workload; `roofline` prices the scan kernel against the 8 TB/s HBM peak using
-algorithmic bytes (input read once + output written once); `cpu_baseline` is the sequential
-CPU oracle timed on this host in the same run, `cpu_all_cores` a chunked scan on one thread
-per available core (a second host figure, checked against the oracle here); `others` holds the
-remaining benchmark configurations measured the same way.
+algorithmic bytes (input read once + output written once) and, beside it, against the best
+plain streaming kernel of the same read : write mix and size measured in the same run
+(`ceiling_GBps`, `frac_of_ceiling`: tcuscan_measure_stream, 128-bit loads, non-temporal stores,
+no dependencies); `cpu_baseline` is the sequential CPU oracle timed on this host in the same
+run, `cpu_all_cores` a chunked scan on one thread per available core (a second host figure,
+checked against the oracle here); `others` holds the remaining benchmark configurations, the
+five single-row scans of 2^28 elements, the latency of the smallest configuration and the
+shapes beyond the hot path, all measured the same way.
+
+Timing: `kernel_ms` is the mean over back-to-back launches between two HIP events on the launch
+stream; `kernel_ms_median` / `kernel_ms_min` come from an event pair around every single launch
+(the events add a gap, so for kernels of a few microseconds they can exceed the mean).
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -35,9 +44,72 @@ DESCR = {
     "C4": "C4: inclusive scan, n=100,000,007, fp32 N(0,1) -> fp32",
     "C5": "C5: batched row-wise inclusive scan, 4096 x 65536 (2^28 elements), bf16 U[-1,1] -> fp32",
 }
-# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the same
-# counters on a plain 1 GiB device copy (fetch x2.000, write x1.000); profiles/scan_kernel_bench_default.md.
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the same counters on a plain
+# 1 GiB device copy; the table and the commands are in TRAFFIC_SOURCE.  The figures belong to the kernels they were
+# measured on: TRAFFIC_KERNEL_SHA is the hash of the kernel source at that time, and a run on any other source
+# reports `traffic: null` instead of a stale number.
 MEASURED_TRAFFIC_BYTES = {"C5": 1627055368, "C3": 1350949057, "C4": 805459263, "C2": 101638485}
+TRAFFIC_SOURCE = "profiles/scan_kernel_bench_default.md"
+TRAFFIC_KERNEL_SHA = "unset"
+KERNEL_SOURCE = os.path.join(ROOT, "paper_2411_17887_amd", "csrc", "tcuscan.hip")
+
+
+def kernel_source_sha() -> str:
+    with open(KERNEL_SOURCE, "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()[:16]
+
+
+def timed_mean(fn, steps: int, warmup: int = 2) -> float:
+    """ms per call: `steps` calls back to back between two events on the current stream."""
+    import torch
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(steps):
+        fn(i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def timed_each(fn, m: int):
+    """Sorted ms of m single calls, an event pair around each."""
+    import torch
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(m + 1)]
+    evs[0].record()
+    for i in range(m):
+        fn(i)
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    return sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(m))
+
+
+STREAM_VARIANTS = [u | ntl | runs | res for u in range(4) for ntl in (0, 0x100) for runs in (0, 0x200) for res in (0, 0x400)]
+_ceiling_cache = {}
+
+
+def stream_ceiling(d_ins, d_outs, n: int, in_bytes: int):
+    """The best plain streaming kernel with this read : write mix on the same buffers: 4 n bytes written, in_bytes * n
+    read (tcuscan_measure_stream, every variant tried).  GB/s counts both directions."""
+    out_bytes = (4 * n) // 64 * 64
+    key = (out_bytes, in_bytes)
+    if key in _ceiling_cache:
+        return _ceiling_cache[key]
+    pairs = len(d_ins)
+    best = None
+    for v in STREAM_VARIANTS:
+        if in_bytes == 0 and (v & 0x100):
+            continue
+        ms = timed_mean(lambda i: tcuscan.measure_stream(d_ins[i % pairs], d_outs[i % pairs], out_bytes, in_bytes, v), 6, 2)
+        if best is None or ms < best[0]:
+            best = (ms, v)
+    ms = timed_mean(lambda i: tcuscan.measure_stream(d_ins[i % pairs], d_outs[i % pairs], out_bytes, in_bytes, best[1]), 20, 2)
+    ms = min(ms, best[0])
+    res = {"GBps": out_bytes * (1 + in_bytes / 4) / (ms * 1e-3) / 1e9, "ms": ms, "variant": "0x%03x" % best[1]}
+    _ceiling_cache[key] = res
+    return res
 
 
 def device_input(x: np.ndarray, kind: str):
@@ -55,6 +127,17 @@ def launch(cfg, d_in, d_out, ws):
         tcuscan.exclusive(d_in, d_out, kind, ws=ws)
     else:
         tcuscan.batched(d_in, d_out, cfg["rows"], cfg["cols"], kind, ws=ws)
+
+
+def figures(n: int, kind: str, ms: float, ceiling=None) -> dict:
+    nbytes = n * (IN_BYTES[kind] + 4)
+    res = {"kernel_ms": ms, "gelems_per_s": n / (ms * 1e-3) / 1e9, "achieved_GBps": nbytes / (ms * 1e-3) / 1e9}
+    res["frac_of_peak"] = res["achieved_GBps"] / PEAK_HBM_GBPS
+    if ceiling is not None:
+        res["ceiling_GBps"] = ceiling["GBps"]
+        res["frac_of_ceiling"] = res["achieved_GBps"] / ceiling["GBps"]
+        res["ceiling_variant"] = ceiling["variant"]
+    return res
 
 
 def measure(name: str, steps: int, warmup: int, keep_host: bool = False):
@@ -81,31 +164,115 @@ def measure(name: str, steps: int, warmup: int, keep_host: bool = False):
         launch(cfg, d_ins[i % pairs], d_outs[i % pairs], ws)
     ev1.record()
     torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps          # exactly `steps` steps between two synchronisations
     kern_ms = ev0.elapsed_time(ev1) / steps
     if ws is not None and tcuscan.workspace_fault(ws) != 0:
         raise RuntimeError("carry chain fault flag set")
-    # launch by launch (an event between consecutive launches, outside the timed region above): median and minimum
-    m = min(steps, 30)
-    evs = [torch.cuda.Event(enable_timing=True) for _ in range(m + 1)]
-    evs[0].record()
-    for i in range(m):
-        launch(cfg, d_ins[i % pairs], d_outs[i % pairs], ws)
-        evs[i + 1].record()
-    torch.cuda.synchronize()
-    each = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(m))
-    res = {
-        "workload": DESCR.get(name, name), "n": n, "dtype": kind, "bytes_per_elem": bytes_per_elem,
-        "ms_per_step": wall_ms, "kernel_ms": kern_ms, "kernel_ms_median": each[m // 2], "kernel_ms_min": each[0],
-        "gelems_per_s": n / (wall_ms * 1e-3) / 1e9,
-        "achieved_GBps": n * bytes_per_elem / (kern_ms * 1e-3) / 1e9,
-        "buffer_pairs": pairs,
-    }
-    res["frac_of_peak"] = res["achieved_GBps"] / PEAK_HBM_GBPS
     last = d_outs[(steps - 1) % pairs].cpu().numpy() if keep_host else None
+    each = timed_each(lambda i: launch(cfg, d_ins[i % pairs], d_outs[i % pairs], ws), min(steps, 30))
+    ceiling = stream_ceiling(d_ins, d_outs, n, IN_BYTES[kind])
+    res = {"workload": DESCR.get(name, name), "n": n, "dtype": kind, "bytes_per_elem": bytes_per_elem,
+           "ms_per_step": wall_ms, "kernel_ms_median": each[len(each) // 2], "kernel_ms_min": each[0], "buffer_pairs": pairs}
+    res.update(figures(n, kind, kern_ms, ceiling))
+    res["gelems_per_s"] = n / (wall_ms * 1e-3) / 1e9           # whole-job throughput by the host clock; the roofline uses kernel_ms
     del d_ins, d_outs, d_in0
     torch.cuda.empty_cache()
     return res, x, last
+
+
+def measure_shapes(steps: int):
+    """Timing-only entries (device-generated seeded data; parity of these shapes is the tests' business): the five
+    single-row inclusive scans of 2^28 elements, shapes without a carry chain, short rows, the smallest
+    configuration's latency, and the ticket policy's price."""
+    import torch
+    torch.manual_seed(241117887)
+    n = 1 << 28
+    raw = torch.randint(0, 2 ** 31 - 1, (n,), dtype=torch.int32, device="cuda")          # 1 GiB of seeded bits
+    out = torch.empty(n, dtype=torch.int32, device="cuda")
+
+    def view(kind, count):
+        """`count` elements of `kind` over the random bits, made harmless for floating point (no Inf / NaN)."""
+        if kind == "i8":
+            return raw.view(torch.int8)[:count]
+        if kind == "i32":
+            return raw[:count]
+        if kind == "f32":
+            return (raw[:count] & 0x3FFFFFFF | 0x30000000).view(torch.float32)            # exponents 96 .. 127: |x| < 2
+        w = raw.view(torch.int16)[:count]
+        return (w & 0x3FFF | 0x3000).view(torch.float16 if kind == "f16" else torch.bfloat16)
+
+    def outv(kind):
+        return out if kind in ("i8", "i32") else out.view(torch.float32)
+
+    res = {}
+    rows_1 = {}
+    for kind in ("f32", "i32", "bf16", "f16", "i8"):
+        x, o = view(kind, n), outv(kind)
+        ws = tcuscan.new_workspace(1, n, kind)
+        ms = timed_mean(lambda i: tcuscan.inclusive(x, o, kind, ws=ws), steps)
+        assert tcuscan.workspace_fault(ws) == 0
+        rows_1[kind] = figures(n, kind, ms, stream_ceiling([x], [o], n, IN_BYTES[kind]))
+    res["single_row_2p28"] = {"workload": "inclusive scan of ONE row of 2^28 elements (one carry chain through the whole input)", **rows_1}
+
+    shapes = {}
+    for label, kind, rows, cols in (("no_chain_i8_32768x8192", "i8", 32768, 8192), ("no_chain_bf16_32768x8192", "bf16", 32768, 8192),
+                                    ("no_chain_f32_16384x8192", "f32", 16384, 8192), ("short_rows_f32_1048576x256", "f32", 1048576, 256),
+                                    ("short_rows_i8_262144x1024", "i8", 262144, 1024), ("short_rows_f16_524288x512", "f16", 524288, 512)):
+        m = rows * cols
+        x, o = view(kind, m), outv(kind)[:m]
+        ws = tcuscan.new_workspace(rows, cols, kind)
+        ms = timed_mean(lambda i: tcuscan.batched(x, o, rows, cols, kind, ws=ws), steps)
+        shapes[label] = figures(m, kind, ms, stream_ceiling([x], [o], m, IN_BYTES[kind]))
+    res["rows_without_a_chain"] = {"workload": "batched inclusive scans whose rows fit one workgroup tile (8192) or one wavefront", **shapes}
+
+    # C1: n = 4096 int32, one workgroup, no carry chain -- launch latency, not bandwidth
+    x, o = view("i32", 4096), out[:4096]
+    each = timed_each(lambda i: tcuscan.inclusive(x, o, "i32"), 200)
+    mean_ms = timed_mean(lambda i: tcuscan.inclusive(x, o, "i32"), 1000, 10)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        tcuscan.inclusive(x, o, "i32", stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        tcuscan.inclusive(x, o, "i32", stream=side)
+    for _ in range(5):
+        g.replay()
+    torch.cuda.synchronize()
+    replay = timed_each(lambda i: g.replay(), 200)
+    g100 = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g100, stream=side):
+        for _ in range(100):
+            tcuscan.inclusive(x, o, "i32", stream=side)
+    g100.replay()
+    torch.cuda.synchronize()
+    chain = timed_each(lambda i: g100.replay(), 20)
+    res["C1_latency"] = {"workload": "C1: inclusive scan, n=4096 int32 (one workgroup, no carry chain): launch latency in microseconds",
+                         "us_median_of_200_launches": each[100] * 1e3, "us_min": each[0] * 1e3,
+                         "us_mean_back_to_back_1000": mean_ms * 1e3,
+                         "us_median_graph_replay_of_one_launch": replay[100] * 1e3,
+                         "us_per_launch_in_a_graph_of_100": chain[10] * 1e3 / 100}
+
+    # the ticket policy (tiles drawn from a counter: no reliance on dispatch order) on the C5 shape and one long row
+    rows, cols = 4096, 65536
+    x, o = view("bf16", n), outv("bf16")
+    ws = tcuscan.new_workspace(rows, cols, "bf16")
+    ws1 = tcuscan.new_workspace(1, n, "bf16")
+    tick = {}
+    for policy in (0, 1):
+        tcuscan.set_chain_policy(policy)
+        try:
+            tick["index_order" if policy == 0 else "ticket"] = {
+                "C5_shape_ms": timed_mean(lambda i: tcuscan.batched(x, o, rows, cols, "bf16", ws=ws), max(3, steps // 4)),
+                "single_row_2p28_bf16_ms": timed_mean(lambda i: tcuscan.inclusive(x, o, "bf16", ws=ws1), max(3, steps // 4))}
+        finally:
+            tcuscan.set_chain_policy(0)
+    res["chain_policy"] = {"workload": "how tiles are handed to workgroups: by workgroup index (default) or from a ticket counter", **tick}
+    del raw, out
+    torch.cuda.empty_cache()
+    return res
 
 
 def measure_levels(steps: int):
@@ -310,7 +477,7 @@ def measure_apps(steps: int):
 
 
 def copy_ceiling_gbps() -> float:
-    """A plain device-to-device copy of 1 GiB (read + write counted), as a measured ceiling."""
+    """A plain device-to-device copy of 1 GiB (read + write counted): calibrates the HBM byte counters of rocprofv3."""
     import torch
     a = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
     b = torch.empty_like(a)
@@ -411,17 +578,20 @@ def main() -> int:
     del x, last
     others = {}
     if not args.no_others:
+        keep = ("workload", "kernel_ms", "kernel_ms_median", "kernel_ms_min", "gelems_per_s", "achieved_GBps", "frac_of_peak",
+                "ceiling_GBps", "frac_of_ceiling", "ceiling_variant", "buffer_pairs")
         for name in ["C2", "C3", "C4", "C5"]:
             if name == args.workload:
                 continue
             r, _, _ = measure(name, max(10, args.steps // 2), args.warmup)
-            others[name] = {k: r[k] for k in ("workload", "kernel_ms", "kernel_ms_median", "kernel_ms_min", "gelems_per_s",
-                                              "achieved_GBps", "frac_of_peak")}
+            others[name] = {k: r[k] for k in keep}
+        others.update(measure_shapes(max(10, args.steps // 2)))
         others["algorithm1_round_by_round"] = measure_levels(5)
         others.update(measure_apps(5))
         others.update(measure_variants(10))
-    ceiling = copy_ceiling_gbps()
 
+    sha = kernel_source_sha()
+    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload) if sha == TRAFFIC_KERNEL_SHA else None
     line = {
         "metric": "G elements/s (and fraction of peak HBM bandwidth in roofline.frac), inclusive scan of 2^28 elements, 1x MI355X",
         "value": head["gelems_per_s"], "unit": "G elements/s",
@@ -431,15 +601,21 @@ def main() -> int:
         "data": "synthetic (seeded SplitMix64 streams, resident in HBM before timing)",
         "config": {"workload": head["workload"], "n": head["n"], "buffer_pairs_rotated": head["buffer_pairs"]},
         "roofline": {"bound": "hbm", "achieved": head["achieved_GBps"], "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                     "frac": head["frac_of_peak"], "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+                     "frac": head["frac_of_peak"], "traffic": traffic,
+                     "traffic_source": (f"{TRAFFIC_SOURCE} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, measured on kernel source {TRAFFIC_KERNEL_SHA})"
+                                        if traffic is not None else
+                                        f"none for kernel source {sha}: the stored figures were measured on {TRAFFIC_KERNEL_SHA} ({TRAFFIC_SOURCE})"),
                      "kernel": "scan_kernel", "kernel_ms": head["kernel_ms"],
                      "kernel_ms_median": head["kernel_ms_median"], "kernel_ms_min": head["kernel_ms_min"],
+                     "timing": "kernel_ms: mean of back-to-back launches between two HIP events on the launch stream; median / min: an "
+                               "event pair around every launch",
                      "algorithmic_bytes_per_elem": head["bytes_per_elem"],
-                     "frac_of_measured_copy": head["achieved_GBps"] / ceiling},
+                     "ceiling_GBps": head["ceiling_GBps"], "frac_of_ceiling": head["frac_of_ceiling"],
+                     "ceiling": "best tcuscan_measure_stream variant (" + head["ceiling_variant"] + ") with the same read:write mix, "
+                                "byte count and buffers, same run"},
         "cpu_baseline": cpu,
         "cpu_all_cores": cpu_all,
         "parity_of_timed_output": parity,
-        "copy_ceiling_GBps": ceiling,
         "others": others,
     }
     print(json.dumps(line))
