@@ -527,7 +527,7 @@ def cpu_all_cores(name: str, x: np.ndarray):
     """The usual multi-thread host scan (rows dealt to threads, or chunk sums / offsets / chunk scans), one thread per
     available core, on the same workload; its output is checked against the oracle."""
     import oracle
-    from oracle import host_threads
+    import hostbaseline as host_threads
     cfg = inputs.CONFIGS[name]
     kind, rows, cols = cfg["kind"], cfg["rows"], cfg["cols"]
     excl = cfg["call"] == "exclusive"

@@ -1,9 +1,10 @@
 """
 ctypes front end of ``host_threads.c``: the all-core host baseline that the benchmark times next to the GPU path.
 
-Test and measurement infrastructure only, and not the oracle: the oracle is the sequential definition in
-``scan_oracle.c``; this is the usual chunked multi-thread scan, checked against the oracle in
-``tests/test_host_threads.py``.  The product path never imports it.
+Measurement infrastructure only, and not the oracle: the oracle is the sequential definition in
+``oracle/scan_oracle.c``; this is the usual chunked multi-thread scan, kept in a folder of its own because it has a
+blocking (chunks per thread) that the yardstick must not have.  It is checked against the oracle in
+``tests/test_host_threads.py`` and again in every benchmark run.  The product path never imports it.
 """
 from __future__ import annotations
 

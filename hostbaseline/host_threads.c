@@ -1,7 +1,7 @@
 /*
  * All-core host baseline for the benchmark.  TEST AND MEASUREMENT INFRASTRUCTURE ONLY.
  *
- * This is NOT the oracle: the oracle (scan_oracle.c) is the sequential definition and stays untouched.  This file is
+ * This is NOT the oracle: the oracle (oracle/scan_oracle.c) is the sequential definition and stays untouched.  This file is
  * the textbook way to scan on a multi-core host, timed next to the GPU path so that the single-core oracle figure is
  * not the only host number: one thread per core; many rows -> rows are dealt to the threads; few rows -> every row is
  * cut into one chunk per thread, the chunks are summed, each thread adds up the sums of the chunks before its own and

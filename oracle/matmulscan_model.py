@@ -24,16 +24,17 @@ import numpy as np
 
 
 def L(s: int, dtype=np.int64) -> np.ndarray:
-    """Section 2: lower-triangular all-ones matrix, diagonal included; L_s w = prefix sum of w."""
-    return np.tril(np.ones((s, s), dtype=dtype))
+    """Section 2: lower-triangular all-ones matrix, diagonal included -- entry (i, j) is 1 exactly when j <= i -- so
+    that L_s w is the prefix sum of w."""
+    i = np.arange(s)
+    return (i[None, :] <= i[:, None]).astype(dtype)
 
 
 def B(s: int, dtype=np.int64) -> np.ndarray:
-    """Section 2, displayed equation: identity whose first column is all ones;
-    B_s [a; q] = [a; q + a 1]  (scalar broadcast-add)."""
-    m = np.eye(s, dtype=dtype)
-    m[:, 0] = 1
-    return m
+    """Section 2, displayed equation: ones on the diagonal and down the first column, zeros elsewhere, so that
+    B_s [a; q] = [a; q + a 1]  (the scalar a is added to every other entry)."""
+    i = np.arange(s)
+    return ((i[None, :] == i[:, None]) | (i[None, :] == 0)).astype(dtype)
 
 
 @dataclass
@@ -93,36 +94,47 @@ def _exact_log(n: int, s: int) -> int:
     return k
 
 
+@dataclass(frozen=True)
+class Round:
+    """One round of Algorithm 1: which entries of x it touches and which constant matrix multiplies them."""
+    phase: str          # "up": first phase, operand L_s;  "down": second phase, operand B_s
+    t: int              # the level
+    first: int          # index of the first entry touched
+    stride: int         # distance between touched entries
+
+    def touched(self, n: int) -> np.ndarray:
+        return np.arange(self.first, n, self.stride)
+
+
+def schedule(n: int, s: int) -> list:
+    """Algorithm 1 as a table of rounds, in execution order, for n = s^k.  First phase, levels t = 0 .. k-1: the
+    entries s^t - 1, 2 s^t - 1, ... (the last entry of every block of s^t) are scanned in runs of s.  Second phase,
+    levels t = k-1 down to 1: starting from the same entry s^t - 1 but with the finer stride s^(t-1), every run of s
+    gets its first entry (a finished prefix) added to the s - 1 partial sums behind it."""
+    k = _exact_log(n, s)
+    first_phase = [Round("up", t, s ** t - 1, s ** t) for t in range(k)]
+    second_phase = [Round("down", t, s ** t - 1, s ** (t - 1)) for t in reversed(range(1, k))]
+    return first_phase + second_phase
+
+
 def matmul_scan(x: np.ndarray, s: int, trace: Trace | None = None) -> np.ndarray:
-    """Algorithm 1, MatMulScan: k up-sweep rounds with L_s on the stride-s^t subvector that
-    starts at s^t - 1, then k-1 down-sweep rounds with B_s on the stride-s^(t-1) subvector
-    that starts at s^t - 1.  Returns a new array; n must be s^k."""
+    """Algorithm 1, MatMulScan, round by round from `schedule`: gather the touched entries, BatchMatMul them with
+    the round's matrix, scatter them back.  Returns a new array; n must be s^k."""
     x = np.array(x, copy=True)
     n = x.shape[0]
-    k = _exact_log(n, s)
-    Ls, Bs = L(s, x.dtype), B(s, x.dtype)
-    for t in range(k):                                    # first phase (up-sweep)
-        start, step = s ** t - 1, s ** t
-        y = x[start::step].copy()                          # gather
-        x[start::step] = batch_matmul(y, Ls, trace)       # scatter
+    operand = {"up": L(s, x.dtype), "down": B(s, x.dtype)}
+    for rnd in schedule(n, s):
+        where = rnd.touched(n)
+        x[where] = batch_matmul(x[where], operand[rnd.phase], trace)
         if trace is not None:
-            trace.end_round(x, y.shape[0])
-    for t in range(k - 1, 0, -1):                         # second phase (down-sweep)
-        start, step = s ** t - 1, s ** (t - 1)
-        y = x[start::step].copy()
-        x[start::step] = batch_matmul(y, Bs, trace)
-        if trace is not None:
-            trace.end_round(x, y.shape[0])
+            trace.end_round(x, where.size)
     return x
 
 
 def gathered_lengths(n: int, s: int):
-    """Lengths of the subvectors Algorithm 1 gathers, round by round, for n = s^k: the up-sweep round t
-    takes x[s^t - 1 :: s^t], the down-sweep round t takes x[s^t - 1 :: s^(t-1)]."""
-    k = _exact_log(n, s)
-    ups = [(n - s ** t) // s ** t + 1 for t in range(k)]
-    downs = [(n - s ** t) // s ** (t - 1) + 1 for t in range(k - 1, 0, -1)]
-    return ups + downs
+    """Lengths of the subvectors Algorithm 1 gathers, round by round, for n = s^k (how many entries each round of
+    `schedule` touches)."""
+    return [rnd.touched(n).size for rnd in schedule(n, s)]
 
 
 def product_count(n: int, s: int) -> int:

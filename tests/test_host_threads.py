@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 
 import oracle
-from oracle import host_threads
+import hostbaseline as host_threads
 from paper_2411_17887_amd import inputs
 
 
