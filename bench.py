@@ -86,7 +86,7 @@ def timed_each(fn, m: int):
     return sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(m))
 
 
-STREAM_VARIANTS = [u | ntl | runs | res for u in range(4) for ntl in (0, 0x100) for runs in (0, 0x200) for res in (0, 0x400)]
+STREAM_VARIANTS = [u | ntl | runs | res for u in range(6) for ntl in (0, 0x100) for runs in (0, 0x200) for res in (0, 0x400)]
 _ceiling_cache = {}
 
 

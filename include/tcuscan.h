@@ -241,8 +241,8 @@ int tcuscan_path_for(const void *d_in, size_t rows, size_t cols, tcuscan_dtype_t
  * prices the scans against (a scan reads every input once and writes every output once; Section 2.3's cost model
  * counts the matrix products, the device counts the bytes).  Writes out_bytes (a multiple of 64) to d_out and reads
  * in_bytes_per_out_word (0: nothing, 1, 2 or 4) bytes from d_in for every 4 bytes written -- the mix of 8-, 16- and
- * 32-bit inputs with 32-bit outputs.  Both pointers 16-byte aligned.  variant: bits 0-1 = log2 of the 16-byte loads
- * (write-only: stores) each lane has in flight (1, 2, 4, 8), bit 8 = non-temporal loads, bit 9 = every wavefront reads
+ * 32-bit inputs with 32-bit outputs.  Both pointers 16-byte aligned.  variant: bits 0-2 = log2 of the 16-byte loads
+ * (write-only: stores) each lane has in flight (1, 2, 4, 8, 16, 32), bit 8 = non-temporal loads, bit 9 = every wavefront reads
  * a run of consecutive KiB (a scan tile's shape) instead of interleaving with its workgroup's other wavefronts, bit 10 =
  * a grid of 2048 workgroups that walk over the data instead of one workgroup per chunk; a caller takes the best of them.
  * 128-bit loads, non-temporal 128-bit stores, 1 KiB per wavefront and instruction, no dependencies.  The output is a

@@ -70,7 +70,9 @@ template <int R> const void *stream_fn_u(int log2u, bool ntl, bool runs)
     case 0:  return stream_fn<1, R>(ntl, runs);
     case 1:  return stream_fn<2, R>(ntl, runs);
     case 2:  return stream_fn<4, R>(ntl, runs);
-    default: return stream_fn<8, R>(ntl, runs);
+    case 3:  return stream_fn<8, R>(ntl, runs);
+    case 4:  return stream_fn<16, R>(ntl, runs);
+    default: return stream_fn<32, R>(ntl, runs);
     }
 }
 
@@ -80,10 +82,10 @@ extern "C" tcuscan_status_t tcuscan_measure_stream(const void *d_in, void *d_out
                                                    unsigned variant, tcuscan_stream_t stream)
 {
     const int b = in_bytes_per_out_word;
-    if ((b != 0 && b != 1 && b != 2 && b != 4) || (variant & ~0x703u)) return TCUSCAN_ERR_INVALID_ARG;
+    if ((b != 0 && b != 1 && b != 2 && b != 4) || (variant & ~0x707u) || (variant & 7u) > 5u) return TCUSCAN_ERR_INVALID_ARG;
     if (out_bytes == 0) return TCUSCAN_OK;
     if (!d_out || (b && !d_in) || ((uintptr_t)d_out % 16) || ((uintptr_t)d_in % 16) || (out_bytes % 64)) return TCUSCAN_ERR_INVALID_ARG;
-    const int log2u = (int)(variant & 3u);
+    const int log2u = (int)(variant & 7u);
     const bool ntl = (variant & 0x100u) != 0, runs = (variant & 0x200u) != 0, resident = (variant & 0x400u) != 0;
     const int R = b ? 4 / b : 0;
     size_t n_out = out_bytes / 16, n_in = R ? n_out / R : 0;

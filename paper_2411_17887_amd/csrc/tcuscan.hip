@@ -779,8 +779,18 @@ void scan_kernel(Params P)
     }
     const bool chained = tiles_in_row > 1;
 
+    // A workgroup of the big tiles issues its loads at raised wave priority.  It has just taken the place of a
+    // workgroup that finished, and the compute unit's other wavefronts are in the middle of their stores: at equal
+    // priority the newcomer's load instructions queue up behind theirs, its tile total -- which every later tile of
+    // the row is waiting for -- comes late, and the memory system has nothing to read while it drains the stores.
+    // Measured (us, 2^28 elements in one row unless noted): i8 215 -> 203, f32 358 -> 340, n = 100,000,007 f32 143 ->
+    // 136, bf16 on the 32768-element tile 287 -> 264.  Small tiles lose with it (4096 x 65536 bf16 256 -> 271, 16384 x
+    // 8192 f32 171 -> 192: with many short-lived workgroups the stores are what must not wait), so they keep the default.
+    constexpr bool kLoadsFirst = kWgElems > 8192;
+    if constexpr (kLoadsFirst) __builtin_amdgcn_s_setprio(3);
     u32x4 g[NT];
     load_run<DT, NT, REV, SEG>(R, lane, g);
+    if constexpr (kLoadsFirst) __builtin_amdgcn_s_setprio(0);
     const typename T::AConst Aop = T::make(lane, EXCL, REV);
 
     // ---- the total of the run (the up-sweep of this tile in one step)
@@ -1070,7 +1080,9 @@ __global__ __launch_bounds__(64 * W) void split_kernel(Params P, SplitArgs S)
 
     // ---- the keys, and from them the mask granules (keys past the end read as all ones: flag 0)
     u32x4 key[NT][4], g[NT];
+    __builtin_amdgcn_s_setprio(3);                  // loads first, as in scan_kernel
     load_run_words<NT>(lane, S.keys + base, rem, ~0u, key);
+    __builtin_amdgcn_s_setprio(0);
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         uint32_t w[4];
@@ -1262,7 +1274,9 @@ __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(VALS ? 1
 
     // ---- the keys; their digit flags as bytes for the two products; this lane's keys per digit
     u32x4 key[NT][4], gA[NT], gB[NT];
+    __builtin_amdgcn_s_setprio(3);                  // loads first, as in scan_kernel
     load_run_words<NT>(lane, S.keys + base, rem, ~0u, key);
+    __builtin_amdgcn_s_setprio(0);
     uint32_t sumA = 0u, sumB = 0u;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
@@ -1371,6 +1385,7 @@ __global__ __launch_bounds__(64 * W) void compact_kernel(Params P, CompactArgs C
     const uint32_t rem = base < n ? (n - base < 0x40000000ull ? (uint32_t)(n - base) : 0x40000000u) : 0u;
 
     // ---- the mask granules (lane l: bytes 16 l .. 16 l + 15 of every MFMA tile; nothing beyond the end) and the values
+    __builtin_amdgcn_s_setprio(3);                  // loads first, as in scan_kernel
     const uint8_t *m = C.mask + base;
     u32x4 g[NT], val[NT][4];
     if ((((uintptr_t)m) & 15) == 0 && rem >= kEPW) {
@@ -1387,6 +1402,7 @@ __global__ __launch_bounds__(64 * W) void compact_kernel(Params P, CompactArgs C
         }
     }
     load_run_words<NT>(lane, C.values + base, rem, 0u, val);
+    __builtin_amdgcn_s_setprio(0);
     const typename T::AConst Aop = T::make_compact(lane);
     uint32_t kept_at, kept_run, through_wg;
     flags_before_run<W>(P, tile, lane, wave, reduce_run<DT, NT>(lane, Aop, g), s_wave_total, &s_bcast, kept_at, kept_run, through_wg);
@@ -1626,6 +1642,7 @@ __global__ __launch_bounds__(64 * W) void seg_flat_kernel(Params P, const long l
     // a run that lies inside the range as a whole (all but the first and the last few) takes straight-line loads and stores
     const bool whole_in = !REV && __builtin_amdgcn_readfirstlane((int)(R.in_vec && R.lead == 0u && R.rem >= kEPW)) != 0;
     const bool whole_out = __builtin_amdgcn_readfirstlane((int)(R.out_vec && R.lead == 0u && R.rem >= kEPW)) != 0;   // (either direction)
+    __builtin_amdgcn_s_setprio(3);                  // loads first, as in scan_kernel
     u32x4 g[NT];
     // row starts among this lane's elements: 4 bits per granule, granule t in bits 4t .. 4t + 3
     const uint64_t bit0 = (uint64_t)(lo - (long long)lead) + base + shift;     // bit of the run's first slot (a multiple of 4)
@@ -1656,6 +1673,7 @@ __global__ __launch_bounds__(64 * W) void seg_flat_kernel(Params P, const long l
         }
     }
 
+    __builtin_amdgcn_s_setprio(0);
     // ---- the run by itself: segmented scan in place, (sum since the last row start, any row start) of the run
     const typename T::AConst Aop = T::make(lane, false, REV);
     A carry = acc_from_bits<A>(0u);                            // sum since the last row start, up to the end of the tile before
@@ -1782,6 +1800,7 @@ __global__ __launch_bounds__(64 * W) void seg_flat_narrow_kernel(Params P, const
     const bool whole_in = !REV && __builtin_amdgcn_readfirstlane((int)(R.in_vec && R.lead == 0u && R.rem >= kEPW)) != 0;
     const bool whole_out = __builtin_amdgcn_readfirstlane((int)(R.out_vec && R.lead == 0u && R.rem >= kEPW)) != 0;
 
+    __builtin_amdgcn_s_setprio(3);                  // loads first, as in scan_kernel
     u32x4 g[NT];
     const uint64_t bit0 = (uint64_t)(lo - (long long)lead) + base + shift;     // bit of the run's first slot (a multiple of G)
     uint32_t starts = 0u;                                      // G bits per granule, granule t in bits G t ..
@@ -1811,6 +1830,7 @@ __global__ __launch_bounds__(64 * W) void seg_flat_narrow_kernel(Params P, const
         }
     }
 
+    __builtin_amdgcn_s_setprio(0);
     // ---- the run by itself
     A y[NT][G];
     A carry = acc_from_bits<A>(0u);
@@ -2046,22 +2066,26 @@ int choose_tile(int dt, size_t rows, size_t cols)
 {
     const int f = g_tile_policy.load(std::memory_order_relaxed);
     if (f) return (f == 1 || cols <= kSmallTile) ? kTileSmall : (f == 2 ? kTileLarge : kTileHuge);
-    // Measured on MI355X (2^27 .. 2^28 elements split into rows of 2^14 .. 2^24): short carry chains run best
-    // on small tiles (loads and stores alternate at a finer grain), long ones on big tiles (fewer status
-    // words per byte); the crossover depends on the input width.  Big tiles need enough tiles to fill the chip.
+    // Measured on MI355X (2^27 .. 2^28 elements split into rows of 2^14 .. 2^28): short carry chains run best on
+    // small tiles (loads and stores alternate at a finer grain), long ones on big tiles (fewer status words per
+    // byte); the crossover depends on the input width.  Big tiles need enough tiles to fill the chip.
+    //   8-bit   large from 8193 elements per row (2^28 in one row: small 293, large 200, huge 202 us)
+    //   16-bit  large beyond 2^18 (2^28 in one row: small 395, large 265, huge 279 us)
+    //   32-bit  large beyond 2^17, huge beyond 2^19 (2^27 in one row: small 230, large 184, huge 174 us)
+    // For 8- and 16-bit inputs the huge tile only pays when the whole call is one generation of workgroups anyway
+    // (no more than 512 large tiles: everything is resident at once, and fewer, larger tiles mean fewer hops of the
+    // carry chain: 2^24 f16 in one row 18.4 us against 19.0; from 2^25 on the large tile is ahead, 34.1 against 35.8).
     const size_t esz = in_size(dt);
     const size_t to_large = esz == 2 ? ((size_t)1 << 18) + 1 : esz == 1 ? kSmallTile + 1 : ((size_t)1 << 17) + 1;
-    const size_t to_huge  = esz == 2 ? ((size_t)1 << 23) + 1 : ((size_t)1 << 22) + 1;
-    int want = cols >= to_huge ? kTileHuge : cols >= to_large ? kTileLarge : kTileSmall;
-    if (want == kTileHuge) {
-        const size_t ht = tile_elems(dt, kTileHuge);
-        if (rows * ((cols + ht - 1) / ht) < 256) want = kTileLarge;
+    if (cols < to_large) return kTileSmall;
+    const size_t lt = tile_elems(dt, kTileLarge), ht = tile_elems(dt, kTileHuge);
+    const size_t large_tiles = rows * ((cols + lt - 1) / lt), huge_tiles = rows * ((cols + ht - 1) / ht);
+    if (esz == 4) {
+        if (cols > ((size_t)1 << 19) && huge_tiles >= 256) return kTileHuge;
+    } else {
+        if (cols > ((size_t)1 << (esz == 2 ? 23 : 22)) && large_tiles <= 512 && huge_tiles >= 256) return kTileHuge;
     }
-    if (want == kTileLarge) {
-        const size_t lt = tile_elems(dt, kTileLarge);
-        if (rows * ((cols + lt - 1) / lt) < 512) want = kTileSmall;
-    }
-    return want;
+    return large_tiles >= 512 ? kTileLarge : kTileSmall;
 }
 
 std::atomic<uint64_t> g_calls{0};          // calls that drew a tag so far (64 bits: does not wrap in practice)

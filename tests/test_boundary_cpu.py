@@ -198,7 +198,8 @@ def test_chain_knobs_static_entry_and_stream_kernel_reject_bad_arguments():
     # streaming yardstick: mixes 0, 1, 2, 4 only; aligned pointers; whole 64-byte groups
     assert call("tcuscan_measure_stream", FAKE, FAKE, 0, 1, 0, 0) == tcuscan.OK
     assert call("tcuscan_measure_stream", FAKE, FAKE, 64, 3, 0, 0) == tcuscan.ERR_INVALID_ARG
-    assert call("tcuscan_measure_stream", FAKE, FAKE, 64, 1, 4, 0) == tcuscan.ERR_INVALID_ARG
+    assert call("tcuscan_measure_stream", FAKE, FAKE, 64, 1, 6, 0) == tcuscan.ERR_INVALID_ARG
+    assert call("tcuscan_measure_stream", FAKE, FAKE, 64, 1, 8, 0) == tcuscan.ERR_INVALID_ARG
     assert call("tcuscan_measure_stream", FAKE, FAKE, 64, 1, 0x800, 0) == tcuscan.ERR_INVALID_ARG
     assert call("tcuscan_measure_stream", FAKE, FAKE + 4, 64, 1, 0, 0) == tcuscan.ERR_INVALID_ARG
     assert call("tcuscan_measure_stream", 0, FAKE, 64, 2, 0, 0) == tcuscan.ERR_INVALID_ARG
