@@ -1995,9 +1995,13 @@ __global__ void seg_desc_kernel(const uint32_t *tile_start, const long long *off
 
 // One 16-byte store per thread where the address allows it (p is 4-byte aligned; the words in front of the first
 // 16-byte boundary and behind the last go one by one).
-__global__ void fill_zero_kernel(uint32_t *p, size_t words)
+// A second range (p2, words2) is cleared by the blocks behind the first range's `blocks1` blocks: two regions of a
+// workspace in one launch.
+__global__ void fill_zero_kernel(uint32_t *p, size_t words, uint32_t *p2, size_t words2, unsigned blocks1)
 {
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;      // group of four words, counted from the boundary
+    unsigned block = blockIdx.x;
+    if (block >= blocks1) { p = p2; words = words2; block -= blocks1; }
+    const size_t i = (size_t)block * blockDim.x + threadIdx.x;           // group of four words, counted from the boundary
     const size_t head = ((16u - ((uintptr_t)p & 15u)) & 15u) / 4u;         // words before the first boundary
     const size_t h = head < words ? head : words;
     const size_t first = h + 4 * i;
@@ -2148,12 +2152,14 @@ template <int DT> hipError_t launch_dt(Params P, bool excl, int size, hipStream_
     return hipLaunchKernel(fn, dim3(P.num_tiles), dim3(64 * waves), args, 0, s);
 }
 
-hipError_t launch_fill(void *d, size_t bytes, hipStream_t s)
+hipError_t launch_fill(void *d, size_t bytes, hipStream_t s, void *d2 = nullptr, size_t bytes2 = 0)
 {
-    size_t words = bytes / 4;
-    uint32_t *p = (uint32_t *)d;
-    void *args[] = {&p, &words};
-    return hipLaunchKernel((const void *)fill_zero_kernel, dim3((unsigned)((words / 4 + 1 + 255) / 256)), dim3(256), args, 0, s);
+    size_t words = bytes / 4, words2 = d2 ? bytes2 / 4 : 0;
+    uint32_t *p = (uint32_t *)d, *p2 = (uint32_t *)d2;
+    unsigned blocks1 = (unsigned)((words / 4 + 1 + 255) / 256);
+    const unsigned blocks2 = words2 ? (unsigned)((words2 / 4 + 1 + 255) / 256) : 0u;
+    void *args[] = {&p, &words, &p2, &words2, &blocks1};
+    return hipLaunchKernel((const void *)fill_zero_kernel, dim3(blocks1 + blocks2), dim3(256), args, 0, s);
 }
 
 // What a launch has to know about the carry chain, and whatever has to run in front of it on the stream.  `tiles`
@@ -2164,7 +2170,9 @@ hipError_t launch_fill(void *d, size_t bytes, hipStream_t s)
 //     workspace region whose contents the library cannot vouch for: both get the reserved tag and a fill kernel in
 //     front of every run (a kernel, not a memset node).
 //   * Ticket policy: the header's ticket counter is cleared.
-tcuscan_status_t begin_chain(Params &P, void *d_ws, size_t tiles, bool clear_first, hipStream_t s)
+// `also` / `also_bytes`: another region of the workspace that a clear-first call wants zeroed (same launch).
+tcuscan_status_t begin_chain(Params &P, void *d_ws, size_t tiles, bool clear_first, hipStream_t s, void *also = nullptr,
+                             size_t also_bytes = 0)
 {
     P.ticket = 0u;
     P.spin_limit = g_spin_limit.load(std::memory_order_relaxed);
@@ -2177,8 +2185,9 @@ tcuscan_status_t begin_chain(Params &P, void *d_ws, size_t tiles, bool clear_fir
     if (hipStreamIsCapturing(s, &cs) != hipSuccess) { (void)hipGetLastError(); cs = hipStreamCaptureStatusNone; }
     if (clear_first || cs == hipStreamCaptureStatusActive) {
         P.tag = chain_tags::kClearFirstTag;
-        if (launch_fill(status, status_bytes, s) != hipSuccess) return TCUSCAN_ERR_HIP;
+        if (launch_fill(status, status_bytes, s, also, also_bytes) != hipSuccess) return TCUSCAN_ERR_HIP;
     } else {
+        if (also && launch_fill(also, also_bytes, s) != hipSuccess) return TCUSCAN_ERR_HIP;
         const chain_tags::CallId id = chain_tags::call_id(g_calls.fetch_add(1u, std::memory_order_relaxed));
         P.tag = id.tag;
         if (g_clean.needs_clear((uintptr_t)d_ws, sizeof(WsHeader) + status_bytes, id.generation) &&
@@ -2335,20 +2344,20 @@ tcuscan_status_t run_segmented_flat(const void *d_in, void *d_out, const long lo
     if (tiles > L.max_tiles) return TCUSCAN_ERR_UNSUPPORTED;     // (never: the general layout counts smaller tiles)
     uint32_t *heads = (uint32_t *)((char *)d_ws + L.heads_off);
     const uint32_t shift = (uint32_t)(((uintptr_t)d_in / in_size(dt)) & (16 / in_size(dt) - 1));    // granules start at bit multiples of their length
-    if (launch_fill(heads, 4 * L.heads_words, s) != hipSuccess) return TCUSCAN_ERR_HIP;
+    Params P;
+    P.in = d_in; P.out = d_out; P.rows = rows; P.cols = total;
+    P.tiles_per_row = 0; P.num_tiles = (uint32_t)tiles;
+    P.ws = (WsHeader *)d_ws;
+    P.reverse = reverse ? 1u : 0u; P.tile_desc = nullptr;
+    // one fill launch clears the status words and the row-start bits
+    const tcuscan_status_t bst = begin_chain(P, d_ws, tiles, true, s, heads, 4 * L.heads_words);
+    if (bst != TCUSCAN_OK) return bst;
     {
         const long long *off = d_offsets; size_t r = rows, t = total; uint32_t sh = shift; WsHeader *h = (WsHeader *)d_ws;
         void *args[] = {&off, &r, &t, &sh, &heads, &h};
         if (hipLaunchKernel((const void *)seg_heads_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), args, 0, s) != hipSuccess)
             return TCUSCAN_ERR_HIP;
     }
-    Params P;
-    P.in = d_in; P.out = d_out; P.rows = rows; P.cols = total;
-    P.tiles_per_row = 0; P.num_tiles = (uint32_t)tiles;
-    P.ws = (WsHeader *)d_ws;
-    P.reverse = reverse ? 1u : 0u; P.tile_desc = nullptr;
-    const tcuscan_status_t bst = begin_chain(P, d_ws, tiles, true, s);
-    if (bst != TCUSCAN_OK) return bst;
     const long long *off = d_offsets; const uint32_t *hd = heads; uint32_t sh = shift;
     void *args[] = {&P, &off, &hd, &sh};
     const bool ex = exclusive != 0;

@@ -114,6 +114,38 @@ def test_ticket_policy_compaction_and_sort(ticket_policy):
             tcuscan.set_sort_fusion(1)
 
 
+def test_ticket_policy_recorded_into_a_graph(ticket_policy):
+    """The ticket counter is cleared by a kernel in front of the scan, so a recorded call draws its tickets from zero
+    on every replay; eager calls (also ticketed) run on the same workspace between the replays."""
+    import torch
+    n = 90 * tcuscan.tile_elems("i8") + 17
+    ws = tcuscan.new_workspace(1, n, "i8")
+    d_in = torch.zeros(n, dtype=torch.int8, device="cuda")
+    d_out = torch.empty(n, dtype=torch.int32, device="cuda")
+    eager_out = torch.empty_like(d_out)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        tcuscan.inclusive(d_in, d_out, "i8", ws=ws, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        tcuscan.inclusive(d_in, d_out, "i8", ws=ws, stream=side)
+    for rep in range(4):
+        x = inputs.int8_full(n, 300 + rep)
+        d_in.copy_(torch.from_numpy(x).cuda())
+        d_out.fill_(-1)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        check(x, "i8", d_out.cpu().numpy())
+        tcuscan.exclusive(d_in, eager_out, "i8", ws=ws)
+        torch.cuda.synchronize()
+        check(x, "i8", eager_out.cpu().numpy(), exclusive=True)
+    assert tcuscan.workspace_fault(ws) == 0
+
+
 def test_a_tile_that_never_publishes_ends_in_a_fault_word_not_in_a_hang():
     """Forced from the host: tile 3 keeps silent and the wait's poll limit is tiny, so every later tile gives up,
     publishes a (wrong) prefix and goes on; the kernel ends normally and the sticky fault word reads 1."""

@@ -64,6 +64,38 @@ def test_static_entry_at_the_full_batched_configuration():
     both("i8", 1, 1 << 20, tcuscan.EXCLUSIVE, 4)
 
 
+def test_static_entry_recorded_into_a_graph():
+    """What the entry point is for: a call under stream capture, where nothing may be allocated.  (Its first call on
+    the device was made outside capture by the tests above or by the warm-up here.)  Replayed with new data, eager
+    calls on the same scratch between the replays."""
+    import torch
+    n = 60 * tcuscan.tile_elems("i32") + 9
+    d_in = torch.zeros(n, dtype=torch.int32, device="cuda")
+    d_out = torch.empty(n, dtype=torch.int32, device="cuda")
+    eager_out = torch.empty_like(d_out)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        tcuscan.scan_static(d_in, d_out, 1, n, "i32", stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        tcuscan.scan_static(d_in, d_out, 1, n, "i32", stream=side)
+    for rep in range(4):
+        x = inputs.int32_full(n, 900 + rep)
+        d_in.copy_(torch.from_numpy(x).cuda())
+        d_out.fill_(-1)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert oracle.compare_int(x, "i32", d_out.cpu().numpy())[0] == 0
+        tcuscan.scan_static(d_in, eager_out, 1, n // 2, "i32", flags=tcuscan.EXCLUSIVE)
+        torch.cuda.synchronize()
+        assert oracle.compare_int(x[: n // 2], "i32", eager_out.cpu().numpy()[: n // 2], exclusive=True)[0] == 0
+    assert tcuscan.workspace_fault(tcuscan.STATIC_SCRATCH) == 0
+
+
 def test_static_entry_refuses_what_its_scratch_cannot_hold():
     import torch
     t = torch.zeros(16, dtype=torch.int8, device="cuda")
