@@ -787,6 +787,19 @@ void scan_kernel(Params P)
     // 136, bf16 on the 32768-element tile 287 -> 264.  Small tiles lose with it (4096 x 65536 bf16 256 -> 271, 16384 x
     // 8192 f32 171 -> 192: with many short-lived workgroups the stores are what must not wait), so they keep the default.
     constexpr bool kLoadsFirst = kWgElems > 8192;
+    // The first generation of the huge 32-bit tiles (two workgroups of 8 wavefronts per compute unit: 512 tiles) starts
+    // 20 ns apart instead of all at once -- half the interval at which the memory system finishes such tiles (256 KiB
+    // at 6.4 TB/s: 41 ns).  Started together, the whole generation only loads for 10 us and the first stores leave
+    // when the last loads have landed; spread out, the early tiles store while the late ones load.  Measured (us):
+    // n = 100,000,007 f32 136 -> 132, one i32 row of 2^28 359 -> 345; 10 or 30 ns, or half as many tiles, lose the gain,
+    // and the 8- and 16-bit tiles (more workgroups per compute unit, less data each) do not gain at any interval.
+    // The wait reads the constant-rate wall clock (10 ns per tick) and is bounded.
+    if constexpr (T::kEsz == 4 && W == 8 && NT == 16) {
+        if (tile < 512u && P.num_tiles >= 1024u) {
+            const uint64_t t0 = wall_clock64(), ticks = 2u * tile;
+            for (int i = 0; i < 4096 && wall_clock64() - t0 < ticks; ++i) __builtin_amdgcn_s_sleep(2);
+        }
+    }
     if constexpr (kLoadsFirst) __builtin_amdgcn_s_setprio(3);
     u32x4 g[NT];
     load_run<DT, NT, REV, SEG>(R, lane, g);
