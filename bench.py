@@ -272,6 +272,14 @@ def measure_shapes(steps: int):
         finally:
             tcuscan.set_chain_policy(0)
     res["chain_policy"] = {"workload": "how tiles are handed to workgroups: by workgroup index (default) or from a ticket counter", **tick}
+    # the entry point that allocates nothing (status words in the library's fixed device array) beside the one with a workspace
+    res["static_entry"] = {
+        "workload": "C5 shape and one bf16 row of 2^28 through tcuscan_scan_static (no workspace argument) and through tcuscan_scan",
+        "C5_shape_ms": {"scan_static": timed_mean(lambda i: tcuscan.scan_static(x, o, rows, cols, "bf16"), max(3, steps // 4)),
+                        "scan": timed_mean(lambda i: tcuscan.scan(x, o, rows, cols, "bf16", ws=ws), max(3, steps // 4))},
+        "single_row_2p28_bf16_ms": {"scan_static": timed_mean(lambda i: tcuscan.scan_static(x, o, 1, n, "bf16"), max(3, steps // 4)),
+                                    "scan": timed_mean(lambda i: tcuscan.scan(x, o, 1, n, "bf16", ws=ws1), max(3, steps // 4))}}
+    assert tcuscan.workspace_fault(tcuscan.STATIC_SCRATCH) == 0
     del raw, out
     torch.cuda.empty_cache()
     return res
