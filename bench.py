@@ -48,9 +48,9 @@ DESCR = {
 # 1 GiB device copy; the table and the commands are in TRAFFIC_SOURCE.  The figures belong to the kernels they were
 # measured on: TRAFFIC_KERNEL_SHA is the hash of the kernel source at that time, and a run on any other source
 # reports `traffic: null` instead of a stale number.
-MEASURED_TRAFFIC_BYTES = {"C5": 1627348660, "C3": 1358382255, "C4": 805141890, "C2": 101662799}
+MEASURED_TRAFFIC_BYTES = {"C5": 1627021100, "C3": 1358403571, "C4": 805163465, "C2": 101670564}
 TRAFFIC_SOURCE = "profiles/scan_kernel_bench_default.md"
-TRAFFIC_KERNEL_SHA = "cb55b3da51f18595"
+TRAFFIC_KERNEL_SHA = "fb56615df4c3b11b"
 KERNEL_SOURCE = os.path.join(ROOT, "paper_2411_17887_amd", "csrc", "tcuscan.hip")
 
 

@@ -467,6 +467,75 @@ __device__ A look_back(const uint64_t *row_status, int tr, uint32_t tag, WsHeade
     return sum;
 }
 
+// The same walk in steps that never wait, for a wavefront that has other work to do while its predecessors' totals
+// are still on their way: start() puts the loads of the first window in flight, every poll() looks at what has
+// arrived -- a window whose words all carry the call's tag is consumed (and the next window requested), otherwise
+// only the missing words are asked for again -- and finish() polls until the prefix is known.  All 64 lanes call.
+template <class A> struct LookBackPoll {
+    const uint64_t *row_status;
+    uint32_t tag;
+    int base;                    // the window covers tiles base, base - 1, ..., base - 64 * kDepth + 1
+    A sum;
+    uint64_t w[kDepth];
+    bool done;
+
+    __device__ __forceinline__ void request(bool all)
+    {
+        const int lane = __lane_id();
+#pragma unroll
+        for (int u = 0; u < kDepth; ++u) {
+            const int idx = base - 64 * u - lane;
+            if (idx >= 0 && (all || (uint32_t)(w[u] >> 34) != tag))
+                w[u] = __hip_atomic_load(row_status + (size_t)idx * kStatusStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    __device__ __forceinline__ void start(const uint64_t *status, int tr, uint32_t call_tag)
+    {
+        row_status = status; tag = call_tag; base = tr - 1; sum = acc_from_bits<A>(0u); done = base < 0;
+#pragma unroll
+        for (int u = 0; u < kDepth; ++u) w[u] = 0u;
+        if (!done) request(true);
+    }
+    __device__ __forceinline__ bool poll()
+    {
+        if (done) return true;
+        const int lane = __lane_id();
+        bool missing = false;
+#pragma unroll
+        for (int u = 0; u < kDepth; ++u) missing = missing || (base - 64 * u - lane >= 0 && (uint32_t)(w[u] >> 34) != tag);
+        if (__ballot(missing) != 0) { request(false); return false; }
+        bool found = false;
+        A part = acc_from_bits<A>(0u);
+#pragma unroll
+        for (int u = 0; u < kDepth; ++u) {
+            const int idx = base - 64 * u - lane;
+            const uint32_t state = idx >= 0 ? (uint32_t)(w[u] >> 32) & 3u : kStatePrefix;      // before the row start: "prefix 0"
+            const uint32_t vbits = idx >= 0 ? (uint32_t)w[u] : 0u;
+            const uint64_t have_prefix = __ballot(state == kStatePrefix);
+            const int first = have_prefix ? __builtin_ctzll(have_prefix) : 63;
+            if (!found && lane <= first) part = acc_add(part, acc_from_bits<A>(vbits));
+            found = found || have_prefix != 0;
+        }
+        sum = acc_add(sum, wave_sum(part));
+        base -= 64 * kDepth;
+        done = found || base < 0;
+        if (!done) request(true);
+        return done;
+    }
+    __device__ __forceinline__ A finish(WsHeader *ws, uint32_t spin_limit)
+    {
+        uint32_t spins = 0;
+        while (!poll()) {
+            if (++spins > spin_limit) {                       // never in correct operation: give up instead of hanging
+                __hip_atomic_store(&ws->fault, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        return sum;
+    }
+};
+
 // Which tile this workgroup scans.  Default: its index in the grid -- a tile then waits only for tiles with a smaller
 // workgroup index, and the chain makes progress as long as the hardware starts workgroups in index order (a workgroup
 // is never started while one with a smaller index is still waiting for a place on the chip).  Ticket policy: the
@@ -935,42 +1004,42 @@ __device__ __forceinline__ u32x4 load_block_words(const uint32_t *run, bool vec,
     return x;
 }
 
-// One ordered range of the slot to global memory.  The range was placed in the slot at the same offset inside a
-// 16-byte group as it has in global memory (a = that offset in words), so a lane moves whole aligned groups: one
-// 16-byte LDS read and one 16-byte store that is 1 KiB contiguous over the wavefront; the two ragged groups at the ends
-// go word by word.  q0: first word of the range's groups in the slot (a multiple of 4); gq: the global address that
-// word 0 of those groups stands for; lim: words from gq on that exist in the destination.
-__device__ __forceinline__ void split_store_range(int lane, const uint32_t *slot, uint32_t q0, uint32_t a, uint32_t cnt,
-                                                  uint32_t *gq, uint32_t lim)
+// One ordered range of the slot (cnt words from word q on) to global memory, cnt words from dst on.  The slot was
+// filled before the destination was known, so the range lies in it at whatever offset; a lane still moves whole
+// aligned 16-byte groups of the destination (four words of the slot at any word offset, one 16-byte store that is
+// 1 KiB contiguous over the wavefront), and the two ragged groups at the ends go word by word.
+// lim: words from dst on that exist in the destination.
+__device__ __forceinline__ void split_store_range(int lane, const uint32_t *slot, uint32_t q, uint32_t cnt, uint32_t *dst, uint32_t lim)
 {
-    const uint32_t end = (a + cnt < lim ? a + cnt : lim);
-    const uint32_t first = (a + 3u) >> 2, past = end >> 2;               // whole groups: first .. past - 1
-    for (uint32_t j = first + (uint32_t)lane; j < past; j += 64u)
-        __builtin_nontemporal_store(*(const u32x4 *)(slot + q0 + 4u * j), (u32x4 *)(gq + 4u * j));
+    const uint32_t a = (uint32_t)((uintptr_t)dst >> 2) & 3u;             // offset of the range inside a 16-byte group
+    const uint32_t end = a + (cnt < lim ? cnt : lim);
+    const uint32_t first = (a + 3u) >> 2, past = end >> 2;               // whole groups: first .. past - 1 (group 0 starts at dst - a)
+    const uint32_t *sl = slot + q - a;                                   // only words a .. end - 1 of it are touched
+    uint32_t *gq = dst - a;
+    for (uint32_t j = first + (uint32_t)lane; j < past; j += 64u) {
+        const uint32_t *src = sl + 4u * j;
+        __builtin_nontemporal_store(u32x4{src[0], src[1], src[2], src[3]}, (u32x4 *)(gq + 4u * j));
+    }
     // the ragged group in front (words a .. 3) and the one behind (words 4 past ..): lanes 0 .. 3 and 4 .. 7, a word each
     if (lane < 8) {
         const uint32_t i = lane < 4 ? (uint32_t)lane : 4u * past + (uint32_t)(lane - 4);
         const bool mine = lane < 4 ? (i >= a && i < end && first == 1u) : (i < end && past >= first);
-        if (mine) gq[i] = slot[q0 + i];
+        if (mine) gq[i] = sl[i];
     }
 }
 
-// The words x (keys, payloads or values, in result layout) of one wavefront's run to their places: those with the
-// flag ("zeros": the split flags a key whose bit is 0) from dst[zero_at] on and, if ONES, the others from dst[one_at]
-// on, both in their old order.  The run is ordered in the wavefront's LDS slot
-// first (zeros, then ones; destinations from the product 2 * zeros before + own flag) and leaves it in two ranges.
-template <int NT, uint32_t SLOT, bool ONES>
-__device__ __forceinline__ void split_scatter(int lane, const typename Tr<TCUSCAN_I8_I32>::AConst &Aop, const u32x4 (&g)[NT],
-                                              const u32x4 (&x)[NT][4], uint32_t *dst, uint64_t zero_at, uint64_t one_at,
-                                              uint32_t zeros_run, uint32_t rem, uint64_t n, uint32_t *slot)
+// The words x (keys, payloads or values, in result layout) of one wavefront's run put in order in the wavefront's
+// LDS slot: those with the flag ("zeros": the split flags a key whose bit is 0) first and, if ONES, the others behind
+// them, both in their old order (positions from the product 2 * zeros before + own flag).  Nothing here depends on
+// where the ranges go in the destination, so this runs while the tile's predecessors are still publishing: if
+// `polling`, the chain is polled once per result block.
+template <int NT, uint32_t SLOT, bool ONES, class Chain>
+__device__ __forceinline__ void split_order(int lane, const typename Tr<TCUSCAN_I8_I32>::AConst &Aop, const u32x4 (&g)[NT],
+                                            const u32x4 (&x)[NT][4], uint32_t zeros_run, uint32_t rem, uint32_t *slot, Chain &chain,
+                                            bool polling)
 {
     using T = Tr<TCUSCAN_I8_I32>;
-    constexpr uint32_t kEPW = NT * 1024u;
-    const uint32_t valid = rem < kEPW ? rem : kEPW;
-    const bool ragged = rem < kEPW;
-    uint32_t *dz = dst + zero_at, *d1 = dst + one_at;
-    const uint32_t a0 = (uint32_t)((uintptr_t)dz >> 2) & 3u, a1 = (uint32_t)((uintptr_t)d1 >> 2) & 3u;
-    const uint32_t base1 = ((a0 + zeros_run + 3u) & ~3u) + a1;              // where the ones start in the slot
+    const bool ragged = rem < NT * 1024u;
     const int c = lane & 15, q = lane >> 4;
     const uint32_t in_blk = 16u * c + 4u * q;
     uint32_t before = 0u;                                                    // zeros in the earlier blocks of the run
@@ -986,7 +1055,7 @@ __device__ __forceinline__ void split_scatter(int lane, const typename Tr<TCUSCA
             const uint32_t idx0 = (uint32_t)t * 1024u + 256u * p + in_blk;
             for (int r = 0; r < 4; ++r) {
                 const uint32_t w = (uint32_t)d[p][r], zb = before + ex + (w >> 1), idx = idx0 + r;
-                uint32_t at = (w & 1u) ? a0 + zb : base1 + (idx - zb);
+                uint32_t at = (w & 1u) ? zb : zeros_run + (idx - zb);
                 if constexpr (ONES) {                          // every key has a place: no branch around the write;
                     if (ragged && idx >= rem) at = SLOT - 1u;  // keys past the end go to the slot's spare last word,
                     at = at < SLOT - 1u ? at : SLOT - 1u;      // and so would a position beyond the ranges (never)
@@ -996,30 +1065,40 @@ __device__ __forceinline__ void split_scatter(int lane, const typename Tr<TCUSCA
                 }
             }
             before += zeros;
+            if (polling) chain.poll();
         }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// The ordered run from the slot to the destination: the zeros from dst[zero_at] on and, if ONES, the others (up to
+// `valid` words in all) from dst[one_at] on.
+template <bool ONES>
+__device__ __forceinline__ void split_store(int lane, const uint32_t *slot, uint32_t *dst, uint64_t zero_at, uint64_t one_at, uint32_t zeros_run,
+                                            uint32_t valid, uint64_t n)
+{
     const uint64_t room0 = zero_at < n ? n - zero_at : 0u, room1 = one_at < n ? n - one_at : 0u;
-    split_store_range(lane, slot, 0u, a0, zeros_run, dz - a0, a0 + (uint32_t)(room0 < 0x40000000ull ? room0 : 0x40000000ull));
+    split_store_range(lane, slot, 0u, zeros_run, dst + zero_at, (uint32_t)(room0 < 0x40000000ull ? room0 : 0x40000000ull));
     if constexpr (ONES)
-        split_store_range(lane, slot, base1 - a1, a1, valid - zeros_run, d1 - a1, a1 + (uint32_t)(room1 < 0x40000000ull ? room1 : 0x40000000ull));
+        split_store_range(lane, slot, zeros_run, valid - zeros_run, dst + one_at, (uint32_t)(room1 < 0x40000000ull ? room1 : 0x40000000ull));
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// From a wavefront's flag count to what lies before its run in the whole array: totals of the workgroup's wavefronts
-// through LDS, then the carry chain between workgroups (as in scan_kernel; one row, tiles in workgroup-index order).
+// From a wavefront's flag count to what lies before its run in the whole array, in two steps with the ordering of the
+// run between them.  Setting out: totals of the workgroup's wavefronts through LDS; wavefront 0 publishes the
+// workgroup's total and asks for the status words of the tiles before (the carry chain of scan_kernel; one row, tiles
+// in workgroup-index order).
 template <int W>
-__device__ __forceinline__ void flags_before_run(const Params &P, uint32_t tile, int lane, int wave, uint32_t wave_total, uint32_t *s_wave_total,
-                                                 uint32_t *s_bcast, uint32_t &before_run, uint32_t &run_total, uint32_t &through_wg)
+__device__ __forceinline__ void flags_set_out(const Params &P, uint32_t tile, int lane, int wave, uint32_t wave_total, uint32_t *s_wave_total,
+                                              LookBackPoll<uint32_t> &lb, uint32_t &wave_off, uint32_t &run_total, uint32_t &wg_total)
 {
-    const uint32_t tag = P.tag;
     if (lane == 0) s_wave_total[wave] = wave_total;
     __syncthreads();
-    uint32_t wave_off = 0u, wg_total = 0u;
+    wave_off = 0u; wg_total = 0u;
 #pragma unroll
     for (int w = 0; w < W; ++w) {
         const uint32_t v = s_wave_total[w];
@@ -1027,29 +1106,35 @@ __device__ __forceinline__ void flags_before_run(const Params &P, uint32_t tile,
         wg_total += v;
     }
     run_total = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_wave_total[wave]);
+    lb.done = true;
+    if (P.num_tiles > 1 && wave == 0) {
+        uint64_t *row_status = (uint64_t *)(P.ws + 1);
+        if (lane == 0)
+            __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(P.tag, tile == 0 ? kStatePrefix : kStateAggregate, wg_total),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        lb.start(row_status, (int)tile, P.tag);
+    }
+}
+
+// Arriving: the flags in all tiles before this one, known to every wavefront of the workgroup.
+__device__ __forceinline__ uint32_t flags_arrive(const Params &P, uint32_t tile, int lane, int wave, uint32_t wg_total, LookBackPoll<uint32_t> &lb,
+                                                 uint32_t *s_bcast)
+{
     uint32_t prefix = 0u;
     if (P.num_tiles > 1) {
-        uint64_t *row_status = (uint64_t *)(P.ws + 1);
         if (wave == 0) {
-            if (tile == 0) {
-                if (lane == 0)
-                    __hip_atomic_store(row_status, status_word(tag, kStatePrefix, wg_total), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            } else {
-                if (lane == 0)
-                    __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStateAggregate, wg_total),
+            prefix = lb.finish(P.ws, P.spin_limit);
+            if (lane == 0) {
+                if (tile != 0)
+                    __hip_atomic_store((uint64_t *)(P.ws + 1) + (size_t)tile * kStatusStride, status_word(P.tag, kStatePrefix, prefix + wg_total),
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                prefix = look_back<uint32_t>(row_status, (int)tile, tag, P.ws, P.spin_limit);
-                if (lane == 0)
-                    __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStatePrefix, prefix + wg_total),
-                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                *s_bcast = prefix;
             }
-            if (lane == 0) *s_bcast = prefix;
         }
         __syncthreads();
         prefix = *s_bcast;
     }
-    before_run = prefix + wave_off;
-    through_wg = prefix + wg_total;
+    return prefix;
 }
 
 // The 16-byte words of a wavefront's run in result layout: block p of MFMA tile t, words 16 c + 4 q .. + 3 of it.
@@ -1078,7 +1163,7 @@ __global__ __launch_bounds__(64 * W) void split_kernel(Params P, SplitArgs S)
     using T = Tr<DT>;
     static_assert(T::kBlocks == 4, "four result blocks of 256 per MFMA tile");
     constexpr uint32_t kEPW = NT * Geo<DT>::kTileElems;
-    constexpr uint32_t kSlot = kEPW + 16u;                      // both ranges, each shifted by up to 3 words and rounded up
+    constexpr uint32_t kSlot = kEPW + 16u;                      // the run in order, and a spare last word
     __shared__ uint32_t s_wave_total[W];
     __shared__ uint32_t s_bcast;
     __shared__ __attribute__((aligned(16))) uint32_t s_pack[W][kSlot];
@@ -1107,15 +1192,22 @@ __global__ __launch_bounds__(64 * W) void split_kernel(Params P, SplitArgs S)
         g[t] = rows_transpose(w);
     }
     const typename T::AConst Aop = T::make_compact(lane);
-    uint32_t zero_at, zeros_run, through_wg;
-    flags_before_run<W>(P, tile, lane, wave, reduce_run<DT, NT>(lane, Aop, g), s_wave_total, &s_bcast, zero_at, zeros_run, through_wg);
+    LookBackPoll<uint32_t> lb;
+    uint32_t wave_off, zeros_run, wg_total;
+    flags_set_out<W>(P, tile, lane, wave, reduce_run<DT, NT>(lane, Aop, g), s_wave_total, lb, wave_off, zeros_run, wg_total);
 
-    // ---- destinations and scatter of the run
-    u32x4 val[VALS ? NT : 1][4];
-    if constexpr (VALS) load_run_words<NT>(lane, S.vals + base, rem, 0u, val);
+    // ---- the run in order in the slot while the chain is on its way, then to its two places
+    const uint32_t valid = rem < kEPW ? rem : kEPW;
+    split_order<NT, kSlot, true>(lane, Aop, g, key, zeros_run, rem, s_pack[wave], lb, P.num_tiles > 1 && wave == 0);
+    const uint32_t zero_at = flags_arrive(P, tile, lane, wave, wg_total, lb, &s_bcast) + wave_off;
     const uint64_t one_at = (uint64_t)*S.zeros_total + (base - zero_at);     // behind all zeros, after the ones before this run
-    split_scatter<NT, kSlot, true>(lane, Aop, g, key, S.keys_out, zero_at, one_at, zeros_run, rem, n, s_pack[wave]);
-    if constexpr (VALS) split_scatter<NT, kSlot, true>(lane, Aop, g, val, S.vals_out, zero_at, one_at, zeros_run, rem, n, s_pack[wave]);
+    split_store<true>(lane, s_pack[wave], S.keys_out, zero_at, one_at, zeros_run, valid, n);
+    if constexpr (VALS) {
+        u32x4 val[NT][4];
+        load_run_words<NT>(lane, S.vals + base, rem, 0u, val);
+        split_order<NT, kSlot, true>(lane, Aop, g, val, zeros_run, rem, s_pack[wave], lb, false);
+        split_store<true>(lane, s_pack[wave], S.vals_out, zero_at, one_at, zeros_run, valid, n);
+    }
 }
 
 // ---- the split on two bits at once: four buckets per pass, half the passes
@@ -1202,27 +1294,21 @@ __global__ void digit_zero_counts_kernel(uint32_t *counts, size_t n)
     if (j < 16) counts[4 * j] = (uint32_t)n - counts[4 * j + 1] - counts[4 * j + 2] - counts[4 * j + 3];
 }
 
-// The words x of one wavefront's run to the four ranges: digit d's from dst[at0[d]] on, cnt[d] of them.
-template <int NT, uint32_t SLOT>
-__device__ __forceinline__ void split4_scatter(int lane, const typename Tr<TCUSCAN_I8_I32>::AConst &Aex, const u32x4 (&gA)[NT],
-                                               const u32x4 (&gB)[NT], const u32x4 (&key)[NT][4], int bit, const u32x4 (&x)[NT][4],
-                                               uint32_t *dst, const uint64_t (&at0)[4], const uint32_t (&cnt)[4], uint32_t rem, uint64_t n,
-                                               uint32_t *slot)
+// The words x of one wavefront's run put in order in the wavefront's slot: digit 0's first, then digit 1's, 2's, 3's,
+// each in the old order (cnt[d] of them).  Nothing here depends on where the ranges go in the destination, so this
+// runs while the tile's predecessors are still publishing: if `polling`, the chain is polled once per result block.
+// `slots` is the workgroup's array of slots and slot0 this wavefront's first word in it: positions are kept as word
+// offsets into the array, two to a register (16-bit halves), so that picking the one for a key's digit is one byte
+// permute.  Words past the end of a ragged run go to the slot's spare last word.
+template <int NT, uint32_t SLOT, class Chain>
+__device__ __forceinline__ void split4_order(int lane, const typename Tr<TCUSCAN_I8_I32>::AConst &Aex, const u32x4 (&gA)[NT],
+                                             const u32x4 (&gB)[NT], const u32x4 (&key)[NT][4], int bit, const u32x4 (&x)[NT][4],
+                                             const uint32_t (&cnt)[4], uint32_t rem, uint32_t *slots, uint32_t slot0, Chain &chain, bool polling)
 {
     using T = Tr<TCUSCAN_I8_I32>;
     const bool ragged = rem < NT * 1024u;
-    // the four ranges in the slot, each at the offset it has inside a 16-byte group of the destination
-    uint32_t a[4], q0[4], next = 0u;
-    uint32_t *gp[4];
-#pragma unroll
-    for (int d = 0; d < 4; ++d) {
-        gp[d] = dst + at0[d];
-        a[d] = (uint32_t)((uintptr_t)gp[d] >> 2) & 3u;
-        q0[d] = next;
-        next = (next + a[d] + cnt[d] + 3u) & ~3u;
-    }
-    uint32_t runA = (q0[0] + a[0]) | ((q0[1] + a[1]) << 16);          // where the next key of digit 0 / 1 goes (two halves)
-    uint32_t runB = (q0[2] + a[2]) | ((q0[3] + a[3]) << 16);          // ... of digit 2 / 3
+    uint32_t runA = slot0 | ((slot0 + cnt[0]) << 16);                 // where the next key of digit 0 / 1 goes (two halves)
+    uint32_t runB = (slot0 + cnt[0] + cnt[1]) | ((slot0 + cnt[0] + cnt[1] + cnt[2]) << 16);      // ... of digit 2 / 3
     const uint32_t in_blk = 16u * (lane & 15) + 4u * (lane >> 4);
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
@@ -1237,25 +1323,42 @@ __device__ __forceinline__ void split4_scatter(int lane, const typename Tr<TCUSC
             const uint32_t blkA = uniform_from_lane(exA + pairA, 15), blkB = uniform_from_lane(exB + pairB, 15);
             const uint32_t baseA = runA + exA, baseB = runB + exB;
             const uint32_t idx0 = (uint32_t)t * 1024u + 256u * p + in_blk;
+            uint32_t at[4];
+#pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const uint32_t d = (key[t][p][r] >> bit) & 3u;
-                const uint32_t w = (d & 2u) ? (uint32_t)dB[r] : (uint32_t)dA[r];
-                const uint32_t bs = (d & 2u) ? baseB : baseA;
-                uint32_t at = ((bs >> (16u * (d & 1u))) & 0xFFFFu) + ((w >> (6u * (d & 1u))) & 63u);
-                if (ragged && idx0 + r >= rem) at = SLOT - 1u;       // keys past the end go to the slot's spare last word,
-                at = at < SLOT - 1u ? at : SLOT - 1u;                // and so would a position beyond the ranges (never)
-                slot[at] = x[t][p][r];
+                // half d of {baseB : baseA}: bytes 2 d and 2 d + 1 of the pair, zeros above
+                const uint32_t bs = __builtin_amdgcn_perm(baseB, baseA, 0x0c0c0100u + 0x0202u * d);
+                // the four 6-bit counts of the two products side by side, field d of them
+                const uint32_t ranks = (uint32_t)dA[r] | ((uint32_t)dB[r] << 12);
+                at[r] = bs + ((ranks >> (6u * d)) & 63u);
             }
+            if (ragged) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (idx0 + r >= rem) at[r] = slot0 + SLOT - 1u;
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) slots[at[r]] = x[t][p][r];
             runA += blkA; runB += blkB;
+            if (polling) chain.poll();
         }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// The four ordered ranges of the slot to the destination: digit d's from dst[at0[d]] on.
+__device__ __forceinline__ void split4_store(int lane, const uint32_t *slot, uint32_t *dst, const uint64_t (&at0)[4], const uint32_t (&cnt)[4],
+                                             uint64_t n)
+{
+    uint32_t q = 0u;
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
         const uint64_t room = at0[d] < n ? n - at0[d] : 0u;
-        split_store_range(lane, slot, q0[d], a[d], cnt[d], gp[d] - a[d], a[d] + (uint32_t)(room < 0x40000000ull ? room : 0x40000000ull));
+        split_store_range(lane, slot, q, cnt[d], dst + at0[d], (uint32_t)(room < 0x40000000ull ? room : 0x40000000ull));
+        q += cnt[d];
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -1269,8 +1372,8 @@ __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(VALS ? 1
     using T = Tr<DT>;
     static_assert(T::kBlocks == 4 && W >= 4, "four result blocks of 256 per MFMA tile; one wavefront per digit for the carry chain");
     constexpr uint32_t kEPW = NT * Geo<DT>::kTileElems;
-    constexpr uint32_t kSlot = kEPW + 32u;                      // four ranges, each shifted by up to 3 words and rounded up
-    static_assert(kSlot < 65536u, "slot positions travel in 16-bit halves");
+    constexpr uint32_t kSlot = kEPW + 16u;                      // the run in order, and a spare last word
+    static_assert(W * kSlot < 65536u, "positions in the workgroup's slots travel in 16-bit halves");
     __shared__ uint32_t s_cnt[W][2];
     __shared__ uint32_t s_prefix[4];
     __shared__ __attribute__((aligned(16))) uint32_t s_pack[W][kSlot];
@@ -1327,25 +1430,40 @@ __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(VALS ? 1
         if (w < wave) { off01 += v01; off23 += v23; }
         wg01 += v01; wg23 += v23;
     }
+
+    // ---- the carry chain sets out: wavefront d < 4 publishes the tile's count of digit d in its word of the tile's
+    // status slot and asks for the words of the tiles before
+    const bool chained = P.num_tiles > 1 && wave < 4;
+    uint64_t *row_status = (uint64_t *)(P.ws + 1) + (wave & 3);
+    const uint32_t mine = ((wave & 2 ? wg23 : wg01) >> (16 * (wave & 1))) & 0xFFFFu;
+    LookBackPoll<uint32_t> lb;
+    lb.done = true;
+    if (chained) {
+        if (lane == 0)
+            __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, tile == 0 ? kStatePrefix : kStateAggregate, mine),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        lb.start(row_status, (int)tile, tag);
+    }
+
+    // ---- meanwhile the run is put in order in the slot
+    uint32_t cnt[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d)
+        cnt[d] = (uint32_t)__builtin_amdgcn_readfirstlane((int)(((d & 2 ? run23 : run01) >> (16 * (d & 1))) & 0xFFFFu));
+    const typename T::AConst Aex = T::make(lane, true, false);
+    split4_order<NT, kSlot>(lane, Aex, gA, gB, key, bit, key, cnt, rem, &s_pack[0][0], (uint32_t)wave * kSlot, lb, chained);
+
+    // ---- the chain arrives
     uint32_t prefix[4] = {0u, 0u, 0u, 0u};
     if (P.num_tiles > 1) {
-        if (wave < 4) {                                          // digit `wave`: its word of the tile's status slot
-            uint64_t *row_status = (uint64_t *)(P.ws + 1) + wave;
-            const uint32_t mine = ((wave & 2 ? wg23 : wg01) >> (16 * (wave & 1))) & 0xFFFFu;
-            uint32_t pre = 0u;
-            if (tile == 0) {
-                if (lane == 0)
-                    __hip_atomic_store(row_status, status_word(tag, kStatePrefix, mine), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            } else {
-                if (lane == 0)
-                    __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStateAggregate, mine),
-                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                pre = look_back<uint32_t>(row_status, (int)tile, tag, P.ws, P.spin_limit);
-                if (lane == 0)
+        if (wave < 4) {
+            const uint32_t pre = lb.finish(P.ws, P.spin_limit);
+            if (lane == 0) {
+                if (tile != 0)
                     __hip_atomic_store(row_status + (size_t)tile * kStatusStride, status_word(tag, kStatePrefix, pre + mine),
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                s_prefix[wave] = pre;
             }
-            if (lane == 0) s_prefix[wave] = pre;
         }
         __syncthreads();
 #pragma unroll
@@ -1355,20 +1473,20 @@ __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(VALS ? 1
     // ---- where this run's keys of each digit go: behind the smaller digits of the whole array, the same digit of the
     // tiles before, of the wavefronts before
     uint64_t at0[4];
-    uint32_t cnt[4];
     uint64_t bucket = 0u;
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
         const uint32_t off = ((d & 2 ? off23 : off01) >> (16 * (d & 1))) & 0xFFFFu;
-        cnt[d] = (uint32_t)__builtin_amdgcn_readfirstlane((int)(((d & 2 ? run23 : run01) >> (16 * (d & 1))) & 0xFFFFu));
         at0[d] = bucket + prefix[d] + off;
         bucket += S.hist[d];
     }
-    u32x4 val[VALS ? NT : 1][4];
-    if constexpr (VALS) load_run_words<NT>(lane, S.vals + base, rem, 0u, val);
-    const typename T::AConst Aex = T::make(lane, true, false);
-    split4_scatter<NT, kSlot>(lane, Aex, gA, gB, key, bit, key, S.keys_out, at0, cnt, rem, n, s_pack[wave]);
-    if constexpr (VALS) split4_scatter<NT, kSlot>(lane, Aex, gA, gB, key, bit, val, S.vals_out, at0, cnt, rem, n, s_pack[wave]);
+    split4_store(lane, s_pack[wave], S.keys_out, at0, cnt, n);
+    if constexpr (VALS) {
+        u32x4 val[NT][4];
+        load_run_words<NT>(lane, S.vals + base, rem, 0u, val);
+        split4_order<NT, kSlot>(lane, Aex, gA, gB, key, bit, val, cnt, rem, &s_pack[0][0], (uint32_t)wave * kSlot, lb, false);
+        split4_store(lane, s_pack[wave], S.vals_out, at0, cnt, n);
+    }
 }
 
 struct CompactArgs {
@@ -1417,10 +1535,13 @@ __global__ __launch_bounds__(64 * W) void compact_kernel(Params P, CompactArgs C
     load_run_words<NT>(lane, C.values + base, rem, 0u, val);
     __builtin_amdgcn_s_setprio(0);
     const typename T::AConst Aop = T::make_compact(lane);
-    uint32_t kept_at, kept_run, through_wg;
-    flags_before_run<W>(P, tile, lane, wave, reduce_run<DT, NT>(lane, Aop, g), s_wave_total, &s_bcast, kept_at, kept_run, through_wg);
-    if (C.count && tile == P.num_tiles - 1 && threadIdx.x == 0) *C.count = through_wg;
-    split_scatter<NT, kSlot, false>(lane, Aop, g, val, C.out, kept_at, 0u, kept_run, rem, n, s_pack[wave]);
+    LookBackPoll<uint32_t> lb;
+    uint32_t wave_off, kept_run, wg_total;
+    flags_set_out<W>(P, tile, lane, wave, reduce_run<DT, NT>(lane, Aop, g), s_wave_total, lb, wave_off, kept_run, wg_total);
+    split_order<NT, kSlot, false>(lane, Aop, g, val, kept_run, rem, s_pack[wave], lb, P.num_tiles > 1 && wave == 0);
+    const uint32_t kept_before = flags_arrive(P, tile, lane, wave, wg_total, lb, &s_bcast);
+    if (C.count && tile == P.num_tiles - 1 && threadIdx.x == 0) *C.count = kept_before + wg_total;
+    split_store<false>(lane, s_pack[wave], C.out, kept_before + wave_off, 0u, kept_run, 0u, n);
 }
 
 // ------------------------------------------------------------- segmented scans, short rows
