@@ -16,6 +16,12 @@ checked against the oracle here); `others` holds the remaining benchmark configu
 five single-row scans of 2^28 elements, the latency of the smallest configuration and the
 shapes beyond the hot path, all measured the same way.
 
+Cold inputs: the device has a 256 MB memory-side cache, and an input that is read again before a few times that many
+bytes of other data have been READ is served from it in part (the kernels' non-temporal stores do not displace it:
+an int8 input of 256 MiB scanned over and over on one buffer runs 10-35 % faster than on rotated buffers).  Every
+timed loop here therefore cycles over copies of its input (and as many output buffers) that hold at least
+ROTATE_INPUT_BYTES together, so each launch reads its input from HBM; `buffer_pairs` says how many.
+
 Timing: `kernel_ms` is the mean over back-to-back launches between two HIP events on the launch
 stream; `kernel_ms_median` / `kernel_ms_min` come from an event pair around every single launch
 (the events add a gap, so for kernels of a few microseconds they can exceed the mean).
@@ -37,6 +43,7 @@ sys.path.insert(0, ROOT)
 from paper_2411_17887_amd import inputs, tcuscan  # noqa: E402
 
 PEAK_HBM_GBPS = 8000.0
+ROTATE_INPUT_BYTES = 1 << 30          # distinct input bytes a timed loop cycles over: 4 x the memory-side cache
 IN_BYTES = {"i32": 4, "f16": 2, "i8": 1, "f32": 4, "bf16": 2}
 DESCR = {
     "C2": "C2: inclusive scan, n=2^24, fp16 U[0,1) -> fp32",
@@ -48,15 +55,20 @@ DESCR = {
 # 1 GiB device copy; the table and the commands are in TRAFFIC_SOURCE.  The figures belong to the kernels they were
 # measured on: TRAFFIC_KERNEL_SHA is the hash of the kernel source at that time, and a run on any other source
 # reports `traffic: null` instead of a stale number.
-MEASURED_TRAFFIC_BYTES = {"C5": 1627021100, "C3": 1358403571, "C4": 805163465, "C2": 101670564}
+MEASURED_TRAFFIC_BYTES = {"C5": 1626828265, "C3": 1358173692, "C4": 805141876, "C2": 101650644}
 TRAFFIC_SOURCE = "profiles/scan_kernel_bench_default.md"
-TRAFFIC_KERNEL_SHA = "fb56615df4c3b11b"
+TRAFFIC_KERNEL_SHA = "57ef7bd8359372d8"
 KERNEL_SOURCE = os.path.join(ROOT, "paper_2411_17887_amd", "csrc", "tcuscan.hip")
 
 
 def kernel_source_sha() -> str:
     with open(KERNEL_SOURCE, "rb") as f:
         return hashlib.sha256(f.read()).hexdigest()[:16]
+
+
+def pairs_for(input_bytes: int) -> int:
+    """Copies of an input a timed loop rotates over so that the copies hold ROTATE_INPUT_BYTES together (at most 32)."""
+    return int(max(1, min(32, -(-ROTATE_INPUT_BYTES // max(1, input_bytes)))))
 
 
 def timed_mean(fn, steps: int, warmup: int = 2) -> float:
@@ -150,8 +162,7 @@ def measure(name: str, steps: int, warmup: int, keep_host: bool = False):
     x = inputs.make_config(name)
     out_dt = torch.int32 if kind in ("i32", "i8") else torch.float32
     bytes_per_elem = IN_BYTES[kind] + 4
-    # rotate over enough buffer pairs that the working set exceeds the 256 MB memory-side cache
-    pairs = max(1, min(8, int(np.ceil(1.2e9 / (n * bytes_per_elem)))))
+    pairs = pairs_for(n * IN_BYTES[kind])          # every launch reads its input from HBM, not from the memory-side cache
     d_in0 = device_input(x, kind)
     d_ins = [d_in0] + [d_in0.clone() for _ in range(pairs - 1)]
     d_outs = [torch.empty(n, dtype=out_dt, device="cuda") for _ in range(pairs)]
@@ -190,30 +201,36 @@ def measure_shapes(steps: int):
     torch.manual_seed(241117887)
     n = 1 << 28
     raw = torch.randint(0, 2 ** 31 - 1, (n,), dtype=torch.int32, device="cuda")          # 1 GiB of seeded bits
-    out = torch.empty(n, dtype=torch.int32, device="cuda")
+    outs = [torch.empty(n, dtype=torch.int32, device="cuda") for _ in range(2)]
 
-    def view(kind, count):
-        """`count` elements of `kind` over the random bits, made harmless for floating point (no Inf / NaN)."""
-        if kind == "i8":
-            return raw.view(torch.int8)[:count]
-        if kind == "i32":
-            return raw[:count]
-        if kind == "f32":
-            return (raw[:count] & 0x3FFFFFFF | 0x30000000).view(torch.float32)            # exponents 96 .. 127: |x| < 2
-        w = raw.view(torch.int16)[:count]
-        return (w & 0x3FFF | 0x3000).view(torch.float16 if kind == "f16" else torch.bfloat16)
-
-    def outv(kind):
-        return out if kind in ("i8", "i32") else out.view(torch.float32)
+    def views(kind, count):
+        """Inputs of `count` elements of `kind` over successive parts of the random bits (as many as fit, see pairs_for),
+        made harmless for floating point (no Inf / NaN), and an output buffer for each."""
+        k = min(pairs_for(count * IN_BYTES[kind]), (4 * n) // (count * IN_BYTES[kind]))
+        xs = []
+        for j in range(k):
+            if kind == "i8":
+                xs.append(raw.view(torch.int8)[j * count:(j + 1) * count])
+            elif kind == "i32":
+                xs.append(raw[j * count:(j + 1) * count])
+            elif kind == "f32":
+                xs.append((raw[j * count:(j + 1) * count] & 0x3FFFFFFF | 0x30000000).view(torch.float32))   # exponents 96 .. 127: |x| < 2
+            else:
+                w = raw.view(torch.int16)[j * count:(j + 1) * count]
+                xs.append((w & 0x3FFF | 0x3000).view(torch.float16 if kind == "f16" else torch.bfloat16))
+        os_ = [(outs[j % 2] if kind in ("i8", "i32") else outs[j % 2].view(torch.float32))[:count] for j in range(k)]
+        return xs, os_
 
     res = {}
     rows_1 = {}
     for kind in ("f32", "i32", "bf16", "f16", "i8"):
-        x, o = view(kind, n), outv(kind)
+        xs, os_ = views(kind, n)
         ws = tcuscan.new_workspace(1, n, kind)
-        ms = timed_mean(lambda i: tcuscan.inclusive(x, o, kind, ws=ws), steps)
+        ms = timed_mean(lambda i: tcuscan.inclusive(xs[i % len(xs)], os_[i % len(xs)], kind, ws=ws), steps)
         assert tcuscan.workspace_fault(ws) == 0
-        rows_1[kind] = figures(n, kind, ms, stream_ceiling([x], [o], n, IN_BYTES[kind]))
+        rows_1[kind] = figures(n, kind, ms, stream_ceiling(xs, os_, n, IN_BYTES[kind]))
+        rows_1[kind]["buffer_pairs"] = len(xs)
+        del xs, os_
     res["single_row_2p28"] = {"workload": "inclusive scan of ONE row of 2^28 elements (one carry chain through the whole input)", **rows_1}
 
     shapes = {}
@@ -221,14 +238,16 @@ def measure_shapes(steps: int):
                                     ("no_chain_f32_16384x8192", "f32", 16384, 8192), ("short_rows_f32_1048576x256", "f32", 1048576, 256),
                                     ("short_rows_i8_262144x1024", "i8", 262144, 1024), ("short_rows_f16_524288x512", "f16", 524288, 512)):
         m = rows * cols
-        x, o = view(kind, m), outv(kind)[:m]
+        xs, os_ = views(kind, m)
         ws = tcuscan.new_workspace(rows, cols, kind)
-        ms = timed_mean(lambda i: tcuscan.batched(x, o, rows, cols, kind, ws=ws), steps)
-        shapes[label] = figures(m, kind, ms, stream_ceiling([x], [o], m, IN_BYTES[kind]))
+        ms = timed_mean(lambda i: tcuscan.batched(xs[i % len(xs)], os_[i % len(xs)], rows, cols, kind, ws=ws), steps)
+        shapes[label] = figures(m, kind, ms, stream_ceiling(xs, os_, m, IN_BYTES[kind]))
+        shapes[label]["buffer_pairs"] = len(xs)
+        del xs, os_
     res["rows_without_a_chain"] = {"workload": "batched inclusive scans whose rows fit one workgroup tile (8192) or one wavefront", **shapes}
 
     # C1: n = 4096 int32, one workgroup, no carry chain -- launch latency, not bandwidth
-    x, o = view("i32", 4096), out[:4096]
+    x, o = raw[:4096], outs[0][:4096]
     each = timed_each(lambda i: tcuscan.inclusive(x, o, "i32"), 200)
     mean_ms = timed_mean(lambda i: tcuscan.inclusive(x, o, "i32"), 1000, 10)
     side = torch.cuda.Stream()
@@ -259,7 +278,8 @@ def measure_shapes(steps: int):
 
     # the ticket policy (tiles drawn from a counter: no reliance on dispatch order) on the C5 shape and one long row
     rows, cols = 4096, 65536
-    x, o = view("bf16", n), outv("bf16")
+    xs, os_ = views("bf16", n)
+    k = len(xs)
     ws = tcuscan.new_workspace(rows, cols, "bf16")
     ws1 = tcuscan.new_workspace(1, n, "bf16")
     tick = {}
@@ -267,20 +287,20 @@ def measure_shapes(steps: int):
         tcuscan.set_chain_policy(policy)
         try:
             tick["index_order" if policy == 0 else "ticket"] = {
-                "C5_shape_ms": timed_mean(lambda i: tcuscan.batched(x, o, rows, cols, "bf16", ws=ws), max(3, steps // 4)),
-                "single_row_2p28_bf16_ms": timed_mean(lambda i: tcuscan.inclusive(x, o, "bf16", ws=ws1), max(3, steps // 4))}
+                "C5_shape_ms": timed_mean(lambda i: tcuscan.batched(xs[i % k], os_[i % k], rows, cols, "bf16", ws=ws), max(3, steps // 4)),
+                "single_row_2p28_bf16_ms": timed_mean(lambda i: tcuscan.inclusive(xs[i % k], os_[i % k], "bf16", ws=ws1), max(3, steps // 4))}
         finally:
             tcuscan.set_chain_policy(0)
     res["chain_policy"] = {"workload": "how tiles are handed to workgroups: by workgroup index (default) or from a ticket counter", **tick}
     # the entry point that allocates nothing (status words in the library's fixed device array) beside the one with a workspace
     res["static_entry"] = {
         "workload": "C5 shape and one bf16 row of 2^28 through tcuscan_scan_static (no workspace argument) and through tcuscan_scan",
-        "C5_shape_ms": {"scan_static": timed_mean(lambda i: tcuscan.scan_static(x, o, rows, cols, "bf16"), max(3, steps // 4)),
-                        "scan": timed_mean(lambda i: tcuscan.scan(x, o, rows, cols, "bf16", ws=ws), max(3, steps // 4))},
-        "single_row_2p28_bf16_ms": {"scan_static": timed_mean(lambda i: tcuscan.scan_static(x, o, 1, n, "bf16"), max(3, steps // 4)),
-                                    "scan": timed_mean(lambda i: tcuscan.scan(x, o, 1, n, "bf16", ws=ws1), max(3, steps // 4))}}
+        "C5_shape_ms": {"scan_static": timed_mean(lambda i: tcuscan.scan_static(xs[i % k], os_[i % k], rows, cols, "bf16"), max(3, steps // 4)),
+                        "scan": timed_mean(lambda i: tcuscan.scan(xs[i % k], os_[i % k], rows, cols, "bf16", ws=ws), max(3, steps // 4))},
+        "single_row_2p28_bf16_ms": {"scan_static": timed_mean(lambda i: tcuscan.scan_static(xs[i % k], os_[i % k], 1, n, "bf16"), max(3, steps // 4)),
+                                    "scan": timed_mean(lambda i: tcuscan.scan(xs[i % k], os_[i % k], 1, n, "bf16", ws=ws1), max(3, steps // 4))}}
     assert tcuscan.workspace_fault(tcuscan.STATIC_SCRATCH) == 0
-    del raw, out
+    del raw, outs, xs, os_
     torch.cuda.empty_cache()
     return res
 
@@ -291,21 +311,14 @@ def measure_levels(steps: int):
     n = 1 << 28
     x = inputs.mask_i8(n, inputs.CONFIGS["C3"]["seed"])
     d_in = torch.from_numpy(x).cuda()
+    np_ = pairs_for(n)
+    d_ins = [d_in] + [d_in.clone() for _ in range(np_ - 1)]         # cold inputs (see the module's note)
     d_out = torch.empty(n, dtype=torch.int32, device="cuda")
     ws = tcuscan.new_workspace(1, n, "i8")
     res = {}
-    for name, fn in (("levels", lambda: tcuscan.matmulscan_levels(d_in, d_out, "i8")),
-                     ("fused", lambda: tcuscan.inclusive(d_in, d_out, "i8", ws=ws))):
-        for _ in range(2):
-            fn()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(steps):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / steps
+    for name, fn in (("levels", lambda i: tcuscan.matmulscan_levels(d_ins[i % np_], d_out, "i8")),
+                     ("fused", lambda i: tcuscan.inclusive(d_ins[i % np_], d_out, "i8", ws=ws))):
+        ms = timed_mean(fn, steps)
         res[name] = {"ms": ms, "gelems_per_s": n / (ms * 1e-3) / 1e9}
     res["workload"] = "inclusive scan, n=2^28=16^7, int8 {0,1} -> int32; 'levels' = 13 launches of Algorithm 1's rounds"
     res["fused_speedup"] = res["levels"]["ms"] / res["fused"]["ms"]
@@ -315,16 +328,7 @@ def measure_levels(steps: int):
     radices = []
     for s, k in ((4, 10), (16, 5), (32, 4), (4, 14), (16, 7), (32, 5)):
         m = s ** k
-        for _ in range(2):
-            tcuscan.matmulscan_levels(d_in, d_out, "i8", n=m, s=s)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(steps):
-            tcuscan.matmulscan_levels(d_in, d_out, "i8", n=m, s=s)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / steps
+        ms = timed_mean(lambda i: tcuscan.matmulscan_levels(d_ins[i % np_], d_out, "i8", n=m, s=s), steps)
         radices.append({"s": s, "n": m, "rounds": 2 * k - 1, "ms": ms, "gelems_per_s": m / (ms * 1e-3) / 1e9})
     res["radices"] = radices
     return res
@@ -334,32 +338,27 @@ def measure_variants(steps: int):
     """Reverse scans on the C3 / C5 shapes and segmented scans on two ragged layouts (seeded geometric row lengths)."""
     import torch
 
+    def copies(t):
+        """The input and enough copies of it that a timed loop reads cold data (see the module's note)."""
+        return [t] + [t.clone() for _ in range(pairs_for(t.numel() * t.element_size()) - 1)]
+
     def timed(fn):
-        for _ in range(2):
-            fn()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(steps):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / steps
+        return timed_mean(fn, steps)
 
     res = {}
     n = 1 << 28
-    d_in = torch.from_numpy(inputs.mask_i8(n, inputs.CONFIGS["C3"]["seed"])).cuda()
+    d_in = copies(torch.from_numpy(inputs.mask_i8(n, inputs.CONFIGS["C3"]["seed"])).cuda())
     d_out = torch.empty(n, dtype=torch.int32, device="cuda")
     ws = tcuscan.new_workspace(1, n, "i8")
-    ms = timed(lambda: tcuscan.scan(d_in, d_out, 1, n, "i8", flags=tcuscan.REVERSE | tcuscan.EXCLUSIVE, ws=ws))
+    ms = timed(lambda i: tcuscan.scan(d_in[i % len(d_in)], d_out, 1, n, "i8", flags=tcuscan.REVERSE | tcuscan.EXCLUSIVE, ws=ws))
     res["reverse_C3_shape"] = {"workload": "exclusive suffix sums, n=2^28, int8 {0,1} -> int32", "ms": ms,
                                "gelems_per_s": n / ms / 1e6, "frac_of_peak": n * 5 / ms / 1e6 / PEAK_HBM_GBPS}
     del d_in, ws
     rows, cols = 4096, 65536
-    xb = torch.from_numpy(inputs.bf16_uniform_pm1(rows * cols, 5).view(np.int16)).cuda().view(torch.bfloat16)
+    xb = copies(torch.from_numpy(inputs.bf16_uniform_pm1(rows * cols, 5).view(np.int16)).cuda().view(torch.bfloat16))
     d_of = d_out.view(torch.float32)
     ws = tcuscan.new_workspace(rows, cols, "bf16")
-    ms = timed(lambda: tcuscan.scan(xb, d_of, rows, cols, "bf16", flags=tcuscan.REVERSE, ws=ws))
+    ms = timed(lambda i: tcuscan.scan(xb[i % len(xb)], d_of, rows, cols, "bf16", flags=tcuscan.REVERSE, ws=ws))
     res["reverse_C5_shape"] = {"workload": "inclusive suffix sums, 4096 x 65536, bf16 -> fp32", "ms": ms,
                                "gelems_per_s": rows * cols / ms / 1e6, "frac_of_peak": rows * cols * 6 / ms / 1e6 / PEAK_HBM_GBPS}
     # segmented: (a) 2^27 bf16 elements in 64 rows cut at seeded random places; (b) 2^26 fp32 elements in rows of
@@ -369,10 +368,11 @@ def measure_variants(steps: int):
     off = np.concatenate([[0], np.sort(rng.integers(0, m, size=63)), [m]]).astype(np.int64)
     d_off = torch.from_numpy(off).cuda()
     ws = tcuscan.new_segmented_workspace(64, m, "bf16")
-    ms = timed(lambda: tcuscan.segmented(xb, d_of, d_off, 64, m, "bf16", ws=ws))
+    xh = copies(xb[0][:m])                                      # 2^27 elements: 256 MiB, four copies
+    ms = timed(lambda i: tcuscan.segmented(xh[i % len(xh)], d_of, d_off, 64, m, "bf16", ws=ws))
     res["segmented_long_rows"] = {"workload": "2^27 bf16 -> fp32 in 64 rows of random lengths", "ms": ms,
                                   "gelems_per_s": m / ms / 1e6, "frac_of_peak": m * 6 / ms / 1e6 / PEAK_HBM_GBPS}
-    del xb, ws
+    del xb, xh, ws
     m = 1 << 26
     lens = rng.geometric(1.0 / 200, size=int(m / 199)) - 1
     lens[:: 97] = 0
@@ -380,17 +380,17 @@ def measure_variants(steps: int):
     off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
     off = off[off <= m]
     nrows = off.size - 1
-    xf = torch.from_numpy(inputs.f32_normal(m, 6)).cuda()
+    xf = copies(torch.from_numpy(inputs.f32_normal(m, 6)).cuda())
     d_off = torch.from_numpy(off).cuda()
     ws = tcuscan.new_segmented_workspace(nrows, m, "f32")
-    ms = timed(lambda: tcuscan.segmented(xf, d_of, d_off, nrows, m, "f32", ws=ws))
+    ms = timed(lambda i: tcuscan.segmented(xf[i % len(xf)], d_of, d_off, nrows, m, "f32", ws=ws))
     covered = int(off[-1])
     res["segmented_short_rows"] = {"workload": f"{covered} fp32 elements in {nrows} rows, geometric lengths (mean 200), some empty, some of 8013; "
                                                "the range scanned as one row with row-start bits",
                                    "ms": ms, "gelems_per_s": covered / ms / 1e6, "frac_of_peak": covered * 8 / ms / 1e6 / PEAK_HBM_GBPS}
     tcuscan.set_segmented_form(False)
     try:
-        ms = timed(lambda: tcuscan.segmented(xf, d_of, d_off, nrows, m, "f32", ws=ws))
+        ms = timed(lambda i: tcuscan.segmented(xf[i % len(xf)], d_of, d_off, nrows, m, "f32", ws=ws))
         res["segmented_short_rows_own_tiles"] = {"workload": "the same with tiles of its own for every row", "ms": ms,
                                                  "gelems_per_s": covered / ms / 1e6, "frac_of_peak": covered * 8 / ms / 1e6 / PEAK_HBM_GBPS}
     finally:
@@ -404,14 +404,14 @@ def measure_variants(steps: int):
     off = off[off <= m]
     nrows = off.size - 1
     covered = int(off[-1])
-    xb = torch.from_numpy(inputs.bf16_uniform_pm1(m, 7).view(np.int16)).cuda()
+    xb = copies(torch.from_numpy(inputs.bf16_uniform_pm1(m, 7).view(np.int16)).cuda())
     d_ob = torch.empty(m, dtype=torch.float32, device="cuda")
     d_off = torch.from_numpy(off).cuda()
     ws = tcuscan.new_segmented_workspace(nrows, m, "bf16")
     for name, flat in (("segmented_short_rows_bf16", True), ("segmented_short_rows_bf16_own_tiles", False)):
         tcuscan.set_segmented_form(flat)
         try:
-            ms = timed(lambda: tcuscan.segmented(xb, d_ob, d_off, nrows, m, "bf16", ws=ws))
+            ms = timed(lambda i: tcuscan.segmented(xb[i % len(xb)], d_ob, d_off, nrows, m, "bf16", ws=ws))
         finally:
             tcuscan.set_segmented_form(True)
         res[name] = {"workload": f"{covered} bf16 -> fp32 elements in {nrows} rows, geometric lengths (mean 200), "

@@ -852,10 +852,11 @@ void scan_kernel(Params P)
     // workgroup that finished, and the compute unit's other wavefronts are in the middle of their stores: at equal
     // priority the newcomer's load instructions queue up behind theirs, its tile total -- which every later tile of
     // the row is waiting for -- comes late, and the memory system has nothing to read while it drains the stores.
-    // Measured (us, 2^28 elements in one row unless noted): i8 215 -> 203, f32 358 -> 340, n = 100,000,007 f32 143 ->
-    // 136, bf16 on the 32768-element tile 287 -> 264.  Small tiles lose with it (4096 x 65536 bf16 256 -> 271, 16384 x
-    // 8192 f32 171 -> 192: with many short-lived workgroups the stores are what must not wait), so they keep the default.
-    constexpr bool kLoadsFirst = kWgElems > 8192;
+    // Measured (us, 2^28 elements in one row unless noted): f32 358 -> 340, n = 100,000,007 f32 143 -> 136, bf16 on the
+    // 32768-element tile 287 -> 264.  The small 16- and 32-bit tiles lose with it (4096 x 65536 bf16 259 -> 273, 16384 x
+    // 8192 f32 172 -> 193: with many short-lived workgroups the stores are what must not wait) and keep the default;
+    // the small 8-bit tile, which stores four bytes for every byte it loads, gains (32768 x 8192 i8 258 -> 217).
+    constexpr bool kLoadsFirst = kWgElems > 8192 || DT == TCUSCAN_I8_I32;
     // The first generation of the huge 32-bit tiles (two workgroups of 8 wavefronts per compute unit: 512 tiles) starts
     // 20 ns apart instead of all at once -- half the interval at which the memory system finishes such tiles (256 KiB
     // at 6.4 TB/s: 41 ns).  Started together, the whole generation only loads for 10 us and the first stores leave
@@ -2204,26 +2205,33 @@ int choose_tile(int dt, size_t rows, size_t cols)
 {
     const int f = g_tile_policy.load(std::memory_order_relaxed);
     if (f) return (f == 1 || cols <= kSmallTile) ? kTileSmall : (f == 2 ? kTileLarge : kTileHuge);
-    // Measured on MI355X (2^27 .. 2^28 elements split into rows of 2^14 .. 2^28): short carry chains run best on
-    // small tiles (loads and stores alternate at a finer grain), long ones on big tiles (fewer status words per
-    // byte); the crossover depends on the input width.  Big tiles need enough tiles to fill the chip.
-    //   8-bit   large from 8193 elements per row (2^28 in one row: small 293, large 200, huge 202 us)
+    // Measured on MI355X with inputs that come from HBM (every launch of a timing loop on another copy of the input;
+    // an input read again within a few hundred MB of reads comes from the memory-side cache in part and shifts these
+    // crossovers): 2^28 elements split into rows of 2^14 .. 2^28, and single rows and groups of four rows of 2^18 ..
+    // 2^26.  Short carry chains run best on small tiles (loads and stores alternate at a finer grain), long ones on
+    // big tiles (fewer status words per byte); the crossover depends on the input width:
+    //   8-bit   large beyond 2^17 (rows of 2^16: small 219, large 239 us; 2^18: 241, 232; one row of 2^28: 364, 222, huge 236)
     //   16-bit  large beyond 2^18 (2^28 in one row: small 395, large 265, huge 279 us)
     //   32-bit  large beyond 2^17, huge beyond 2^19 (2^27 in one row: small 230, large 184, huge 174 us)
+    // Big tiles need enough tiles to fill the chip, but a long chain of small tiles costs more than idle compute
+    // units: the large tile pays from 256 tiles in all, or from 128 of them in a row (one f16 row of 2^22: small 9.4,
+    // large 8.2 us; four rows of 2^20: 7.0, 8.0), the huge 32-bit tile from 512 (four rows of 2^22: large 28.2, huge
+    // 23.0 us; one row of 2^23: 13.3, 13.9).
     // For 8- and 16-bit inputs the huge tile only pays when the whole call is one generation of workgroups anyway
     // (no more than 512 large tiles: everything is resident at once, and fewer, larger tiles mean fewer hops of the
-    // carry chain: 2^24 f16 in one row 18.4 us against 19.0; from 2^25 on the large tile is ahead, 34.1 against 35.8).
+    // carry chain: 2^24 f16 in one row 19.1 us against 19.6; from 2^25 on the large tile is ahead, 35.2 against 36.6).
     const size_t esz = in_size(dt);
-    const size_t to_large = esz == 2 ? ((size_t)1 << 18) + 1 : esz == 1 ? kSmallTile + 1 : ((size_t)1 << 17) + 1;
+    const size_t to_large = esz == 2 ? ((size_t)1 << 18) + 1 : ((size_t)1 << 17) + 1;
     if (cols < to_large) return kTileSmall;
     const size_t lt = tile_elems(dt, kTileLarge), ht = tile_elems(dt, kTileHuge);
-    const size_t large_tiles = rows * ((cols + lt - 1) / lt), huge_tiles = rows * ((cols + ht - 1) / ht);
+    const size_t large_per_row = (cols + lt - 1) / lt;
+    const size_t large_tiles = rows * large_per_row, huge_tiles = rows * ((cols + ht - 1) / ht);
     if (esz == 4) {
-        if (cols > ((size_t)1 << 19) && huge_tiles >= 256) return kTileHuge;
+        if (cols > ((size_t)1 << 19) && huge_tiles >= 512) return kTileHuge;
     } else {
         if (cols > ((size_t)1 << (esz == 2 ? 23 : 22)) && large_tiles <= 512 && huge_tiles >= 256) return kTileHuge;
     }
-    return large_tiles >= 512 ? kTileLarge : kTileSmall;
+    return large_tiles >= 256 || large_per_row >= 128 ? kTileLarge : kTileSmall;
 }
 
 std::atomic<uint64_t> g_calls{0};          // calls that drew a tag so far (64 bits: does not wrap in practice)
