@@ -343,12 +343,27 @@ def test_tile_policies_give_the_same_integers(kind, policy, tile_policy):
 
 
 def test_auto_policy_picks_the_large_tile_only_for_long_inputs():
-    # observable through results only: both must be right; the sizes sit on either side of the switch
+    # observable through results only: both must be right; the sizes sit on either side of the switches (128 large
+    # tiles in a row, 256 huge tiles of 8- and 16-bit inputs, 512 huge 32-bit tiles)
     for kind in ("i8", "f32", "bf16"):
         lt, ht = tcuscan.large_tile_elems(kind), tcuscan.huge_tile_elems(kind)
-        for n in (512 * lt - 1, 512 * lt + 1, 256 * ht - 1, 256 * ht + 1, (1 << 22) - 1, (1 << 22) + 1):
+        for n in (127 * lt, 127 * lt + 1, 128 * lt + 1, 512 * lt - 1, 512 * lt + 1, 256 * ht - 1, 256 * ht + 1, 512 * ht - ht + 1,
+                  512 * ht + 1):
             x = (INT_GEN.get(kind) or TRI_GEN[kind])(n, 7)
             check(x, kind, run_scan(x, kind, "inclusive"), exact_float=kind not in INT_GEN)
+
+
+@pytest.mark.parametrize("kind", ["i8", "f16", "f32"])
+def test_auto_policy_switches_in_batched_calls(kind):
+    """Row lengths on either side of the small / large switch (2^17 for 8- and 32-bit inputs, 2^18 for 16-bit), with row
+    counts on either side of 256 large tiles in the call."""
+    lt = tcuscan.large_tile_elems(kind)
+    edge = (1 << 18) if kind in ("f16", "bf16") else (1 << 17)
+    for cols in (edge, edge + 8):
+        per_row = -(-cols // lt)
+        for rows in (1, 255 // per_row, 255 // per_row + 1, 256 // per_row + 2):
+            x = (INT_GEN.get(kind) or TRI_GEN[kind])(rows * cols, rows + cols)
+            check(x, kind, run_scan(x, kind, "batched", rows=rows, cols=cols), rows=rows, cols=cols, exact_float=kind not in INT_GEN)
 
 
 # ------------------------------------------------------------------------ graph capture
