@@ -2087,32 +2087,24 @@ __global__ __launch_bounds__(kThreads) void scan_rows_kernel(Params P)
 // start, so it needs ceil((lead + len) / tile) tiles (none when it is empty).  Offsets that decrease or leave
 // [0, total] give the row no tiles and raise the fault word instead of letting the scan touch memory outside the
 // caller's arrays.  Entry `rows` is zero: the exclusive scan of this array then ends with the total number of tiles.
-__global__ void seg_tiles_kernel(const long long *offsets, size_t rows, size_t total, uintptr_t in_addr, uint32_t esz,
-                                 uint32_t tile, int32_t *counts, WsHeader *ws)
+// Tiles of row r (a row is tiled from the 16-byte boundary at or below its first element); offsets that leave the
+// arrays or run backwards get no tiles and raise fault word 2.
+__device__ __forceinline__ int32_t seg_row_tiles(const long long *offsets, size_t r, size_t total, uintptr_t in_addr, uint32_t esz,
+                                                 uint32_t tile, WsHeader *ws)
 {
-    const size_t r = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (r > rows) return;
-    int32_t c = 0;
-    if (r < rows) {
-        const long long off = offsets[r], end = offsets[r + 1];
-        if (off < 0 || end < off || (unsigned long long)end > total) {
-            __hip_atomic_store(&ws->fault, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        } else if (end > off) {
-            const uint64_t lead = ((in_addr + (uint64_t)off * esz) & 15) / esz;
-            c = (int32_t)((lead + (uint64_t)(end - off) + tile - 1) / tile);
-        }
+    const long long off = offsets[r], end = offsets[r + 1];
+    if (off < 0 || end < off || (unsigned long long)end > total) {
+        __hip_atomic_store(&ws->fault, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return 0;
     }
-    counts[r] = c;
+    if (end == off) return 0;
+    const uint64_t lead = ((in_addr + (uint64_t)off * esz) & 15) / esz;
+    return (int32_t)((lead + (uint64_t)(end - off) + tile - 1) / tile);
 }
 
-// Segmented scans, step 3: one descriptor per tile of the launch.  The row of a tile is the last row that starts at
-// or before it (rows without tiles share their start with the next row and are skipped by taking the last): a binary
-// search per tile, done here, where thousands of independent searches overlap, rather than at the head of every
-// workgroup of the scan, where it would be pure latency.  Tiles beyond the real total get an empty descriptor.
-__global__ void seg_desc_kernel(const uint32_t *tile_start, const long long *offsets, size_t rows, TileDesc *desc, uint32_t max_tiles)
+// The descriptor of tile t, given the first tile of every row (tile_start[0 .. rows], in global memory or LDS).
+__device__ __forceinline__ TileDesc seg_tile_desc(const uint32_t *tile_start, const long long *offsets, size_t rows, uint32_t t)
 {
-    const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= max_tiles) return;
     TileDesc d = {0, 0ull, 0u, 0u, {0u, 0u}};
     if (t < tile_start[rows]) {
         size_t lo = 0, hi = rows;                 // tile_start[lo] <= t < tile_start[hi]
@@ -2125,7 +2117,60 @@ __global__ void seg_desc_kernel(const uint32_t *tile_start, const long long *off
         d.first_tile = tile_start[lo];
         d.tiles_in_row = tile_start[lo + 1] - d.first_tile;
     }
-    desc[t] = d;
+    return d;
+}
+
+__global__ void seg_tiles_kernel(const long long *offsets, size_t rows, size_t total, uintptr_t in_addr, uint32_t esz,
+                                 uint32_t tile, int32_t *counts, WsHeader *ws)
+{
+    const size_t r = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r > rows) return;
+    counts[r] = r < rows ? seg_row_tiles(offsets, r, total, in_addr, esz, tile, ws) : 0;
+}
+__global__ void seg_desc_kernel(const uint32_t *tile_start, const long long *offsets, size_t rows, TileDesc *desc, uint32_t max_tiles)
+{
+    const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= max_tiles) return;
+    desc[t] = seg_tile_desc(tile_start, offsets, rows, t);
+}
+
+// The three preparation steps and the clearing of the status words in ONE launch, for calls with few rows (ragged
+// batches of some hundred sequences: four small launches in front of the scan cost more than they compute).  Every
+// workgroup works out the first tile of every row by itself -- kSegPrepRows / 1024 rows per thread, one scan over the
+// workgroup in LDS -- and then writes the descriptors and clears the status slots of its own 1024 tiles.
+constexpr size_t kSegPrepRows = 4096;                  // rows + 1 entries must fit: calls with fewer rows than this
+__global__ __launch_bounds__(1024) void seg_prepare_kernel(const long long *offsets, size_t rows, size_t total, uintptr_t in_addr, uint32_t esz,
+                                                           uint32_t tile, TileDesc *desc, uint32_t max_tiles, WsHeader *ws)
+{
+    constexpr int kPer = (int)(kSegPrepRows / 1024);
+    __shared__ uint32_t s_start[kSegPrepRows + 1];
+    __shared__ uint32_t s_wave[16];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t c[kPer], mine = 0u;
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        const size_t r = (size_t)kPer * threadIdx.x + j;
+        c[j] = r < rows ? (uint32_t)seg_row_tiles(offsets, r, total, in_addr, esz, tile, ws) : 0u;
+        mine += c[j];
+    }
+    const uint32_t incl = wave_inclusive_scan(mine);
+    if (lane == 63) s_wave[wave] = incl;
+    __syncthreads();
+    uint32_t before = incl - mine;                       // tiles of the rows of the threads before this one
+    for (int w = 0; w < wave; ++w) before += s_wave[w];
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        const size_t r = (size_t)kPer * threadIdx.x + j;
+        if (r <= rows) s_start[r] = before;
+        before += c[j];
+    }
+    __syncthreads();
+    const uint32_t t = blockIdx.x * 1024u + threadIdx.x;
+    if (t >= max_tiles) return;
+    desc[t] = seg_tile_desc(s_start, offsets, rows, t);
+    u32x4 *slot = (u32x4 *)((uint64_t *)(ws + 1) + (size_t)t * kStatusStride);
+#pragma unroll
+    for (int k = 0; k < (int)(8 * kStatusStride / 16); ++k) slot[k] = u32x4{0u, 0u, 0u, 0u};
 }
 
 // One 16-byte store per thread where the address allows it (p is 4-byte aligned; the words in front of the first
@@ -2314,7 +2359,7 @@ hipError_t launch_fill(void *d, size_t bytes, hipStream_t s, void *d2 = nullptr,
 //   * Ticket policy: the header's ticket counter is cleared.
 // `also` / `also_bytes`: another region of the workspace that a clear-first call wants zeroed (same launch).
 tcuscan_status_t begin_chain(Params &P, void *d_ws, size_t tiles, bool clear_first, hipStream_t s, void *also = nullptr,
-                             size_t also_bytes = 0)
+                             size_t also_bytes = 0, bool cleared_by_caller = false)
 {
     P.ticket = 0u;
     P.spin_limit = g_spin_limit.load(std::memory_order_relaxed);
@@ -2327,7 +2372,7 @@ tcuscan_status_t begin_chain(Params &P, void *d_ws, size_t tiles, bool clear_fir
     if (hipStreamIsCapturing(s, &cs) != hipSuccess) { (void)hipGetLastError(); cs = hipStreamCaptureStatusNone; }
     if (clear_first || cs == hipStreamCaptureStatusActive) {
         P.tag = chain_tags::kClearFirstTag;
-        if (launch_fill(status, status_bytes, s, also, also_bytes) != hipSuccess) return TCUSCAN_ERR_HIP;
+        if (!cleared_by_caller && launch_fill(status, status_bytes, s, also, also_bytes) != hipSuccess) return TCUSCAN_ERR_HIP;
     } else {
         if (also && launch_fill(also, also_bytes, s) != hipSuccess) return TCUSCAN_ERR_HIP;
         const chain_tags::CallId id = chain_tags::call_id(g_calls.fetch_add(1u, std::memory_order_relaxed));
@@ -2587,23 +2632,32 @@ tcuscan_status_t run_segmented(const void *d_in, void *d_out, const long long *d
     int32_t *counts = (int32_t *)((char *)d_ws + L.counts_off);
     uint32_t *starts = (uint32_t *)((char *)d_ws + L.starts_off);
     TileDesc *desc = (TileDesc *)((char *)d_ws + L.rowmap_off);
-    {   // step 1: tiles per row
+    const bool few_rows = rows < kSegPrepRows;
+    if (few_rows) {   // steps 1 - 3 and the clearing of the status words in one launch
         const long long *off = d_offsets; size_t r = rows, t = total; uintptr_t in_addr = (uintptr_t)d_in;
-        uint32_t esz = (uint32_t)in_size(dt), tl = (uint32_t)tile; WsHeader *h = (WsHeader *)d_ws;
-        void *args[] = {&off, &r, &t, &in_addr, &esz, &tl, &counts, &h};
-        if (hipLaunchKernel((const void *)seg_tiles_kernel, dim3((unsigned)((rows + 1 + 255) / 256)), dim3(256), args, 0, s) != hipSuccess)
+        uint32_t esz = (uint32_t)in_size(dt), tl = (uint32_t)tile, mt = (uint32_t)L.max_tiles; WsHeader *h = (WsHeader *)d_ws;
+        void *args[] = {&off, &r, &t, &in_addr, &esz, &tl, &desc, &mt, &h};
+        if (hipLaunchKernel((const void *)seg_prepare_kernel, dim3((unsigned)((L.max_tiles + 1023) / 1024)), dim3(1024), args, 0, s) != hipSuccess)
             return TCUSCAN_ERR_HIP;
-    }
-    // step 2: first tile of every row = exclusive scan of the counts (this library's own int32 scan)
-    // (its workspace is a region of this one whose former contents depend on the shapes of earlier calls: cleared first)
-    tcuscan_status_t st = run(counts, starts, 1, rows + 1, TCUSCAN_I32_I32, 1, 0, L.inner_bytes ? (char *)d_ws + L.inner_off : nullptr,
-                              L.inner_bytes, stream, true);
-    if (st != TCUSCAN_OK) return st;
-    {   // step 3: one descriptor per tile
-        const uint32_t *ts = starts; const long long *off = d_offsets; size_t r = rows; uint32_t mt = (uint32_t)L.max_tiles;
-        void *args[] = {&ts, &off, &r, &desc, &mt};
-        if (hipLaunchKernel((const void *)seg_desc_kernel, dim3((unsigned)((L.max_tiles + 255) / 256)), dim3(256), args, 0, s) != hipSuccess)
-            return TCUSCAN_ERR_HIP;
+    } else {
+        {   // step 1: tiles per row
+            const long long *off = d_offsets; size_t r = rows, t = total; uintptr_t in_addr = (uintptr_t)d_in;
+            uint32_t esz = (uint32_t)in_size(dt), tl = (uint32_t)tile; WsHeader *h = (WsHeader *)d_ws;
+            void *args[] = {&off, &r, &t, &in_addr, &esz, &tl, &counts, &h};
+            if (hipLaunchKernel((const void *)seg_tiles_kernel, dim3((unsigned)((rows + 1 + 255) / 256)), dim3(256), args, 0, s) != hipSuccess)
+                return TCUSCAN_ERR_HIP;
+        }
+        // step 2: first tile of every row = exclusive scan of the counts (this library's own int32 scan)
+        // (its workspace is a region of this one whose former contents depend on the shapes of earlier calls: cleared first)
+        tcuscan_status_t st = run(counts, starts, 1, rows + 1, TCUSCAN_I32_I32, 1, 0, L.inner_bytes ? (char *)d_ws + L.inner_off : nullptr,
+                                  L.inner_bytes, stream, true);
+        if (st != TCUSCAN_OK) return st;
+        {   // step 3: one descriptor per tile
+            const uint32_t *ts = starts; const long long *off = d_offsets; size_t r = rows; uint32_t mt = (uint32_t)L.max_tiles;
+            void *args[] = {&ts, &off, &r, &desc, &mt};
+            if (hipLaunchKernel((const void *)seg_desc_kernel, dim3((unsigned)((L.max_tiles + 255) / 256)), dim3(256), args, 0, s) != hipSuccess)
+                return TCUSCAN_ERR_HIP;
+        }
     }
     // step 4: the scan itself; the grid is the upper bound on the number of tiles, surplus workgroups leave at once
     Params P;
@@ -2612,7 +2666,7 @@ tcuscan_status_t run_segmented(const void *d_in, void *d_out, const long long *d
     P.ws = (WsHeader *)d_ws;
     P.reverse = reverse ? 1u : 0u;
     P.tile_desc = desc;
-    const tcuscan_status_t bst = begin_chain(P, d_ws, L.max_tiles, true, s);
+    const tcuscan_status_t bst = begin_chain(P, d_ws, L.max_tiles, true, s, nullptr, 0, few_rows);
     if (bst != TCUSCAN_OK) return bst;
     hipError_t e;
     switch (dt) {
