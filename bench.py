@@ -55,9 +55,9 @@ DESCR = {
 # 1 GiB device copy; the table and the commands are in TRAFFIC_SOURCE.  The figures belong to the kernels they were
 # measured on: TRAFFIC_KERNEL_SHA is the hash of the kernel source at that time, and a run on any other source
 # reports `traffic: null` instead of a stale number.
-MEASURED_TRAFFIC_BYTES = {"C5": 1626828265, "C3": 1358173692, "C4": 805141876, "C2": 101650644}
+MEASURED_TRAFFIC_BYTES = {"C5": 1626934072, "C3": 1358169199, "C4": 805145920, "C2": 101634722}
 TRAFFIC_SOURCE = "profiles/scan_kernel_bench_default.md"
-TRAFFIC_KERNEL_SHA = "57ef7bd8359372d8"
+TRAFFIC_KERNEL_SHA = "dd73eaf2aacba700"
 KERNEL_SOURCE = os.path.join(ROOT, "paper_2411_17887_amd", "csrc", "tcuscan.hip")
 
 
