@@ -145,9 +145,9 @@ tcuscan_status_t tcuscan_scan(const void *d_in, void *d_out, size_t rows, size_t
  *   d_offsets  rows + 1 signed 64-bit element offsets on the DEVICE, non-decreasing, within [0, total]; 8-byte aligned
  *   total      number of elements d_in and d_out hold (an upper bound for d_offsets[rows]); sizes the launch
  *   d_ws       tcuscan_segmented_workspace_bytes(rows, total, dt) bytes, zero-filled once like every workspace here
- * Four launches are enqueued: tiles per row, their exclusive scan (this library's int32 scan), one descriptor per
- * tile (its row's extent and its place in the row), the scan itself.  The tile size follows the average row length
- * total / rows.  Short rows (average below 2048 / 4096 / 8192 elements for 32- / 16- / 8-bit inputs) take another
+ * Four steps are enqueued: tiles per row, their exclusive scan (this library's int32 scan), one descriptor per
+ * tile (its row's extent and its place in the row), the scan itself; with fewer than 4096 rows the first three are one
+ * launch.  The tile size follows the average row length total / rows.  Short rows (average below 2048 / 4096 / 8192 elements for 32- / 16- / 8-bit inputs) take another
  * form, three launches: the row starts become one bit per element, and the range the rows cover is scanned like one
  * row whose sums restart at every set bit (tcuscan_set_segmented_form(0) switches that form off).
  * Rows may start at any element: a row is tiled from the 16-byte boundary at or below its start, the few elements in
