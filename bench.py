@@ -55,7 +55,7 @@ DESCR = {
 # 1 GiB device copy; the table and the commands are in TRAFFIC_SOURCE.  The figures belong to the kernels they were
 # measured on: TRAFFIC_KERNEL_SHA is the hash of the kernel source at that time, and a run on any other source
 # reports `traffic: null` instead of a stale number.
-MEASURED_TRAFFIC_BYTES = {"C5": 1626934072, "C3": 1358169199, "C4": 805145920, "C2": 101634722}
+MEASURED_TRAFFIC_BYTES = {"C5": 1626713736, "C3": 1358168384, "C4": 805174710, "C2": 101630174}
 TRAFFIC_SOURCE = "profiles/scan_kernel_bench_default.md"
 TRAFFIC_KERNEL_SHA = "dd73eaf2aacba700"
 KERNEL_SOURCE = os.path.join(ROOT, "paper_2411_17887_amd", "csrc", "tcuscan.hip")
@@ -99,6 +99,8 @@ def timed_each(fn, m: int):
 
 
 STREAM_VARIANTS = [u | ntl | runs | res for u in range(6) for ntl in (0, 0x100) for runs in (0, 0x200) for res in (0, 0x400)]
+STREAM_VARIANTS += [u | ntl | runs | res | pause for u in (0, 1) for ntl in (0, 0x100) for runs in (0, 0x200) for res in (0, 0x400)
+                    for pause in (0x800, 0x1000)]          # a pause of 512 / 2048 cycles between loads and stores
 _ceiling_cache = {}
 
 
@@ -114,7 +116,7 @@ def stream_ceiling(d_ins, d_outs, n: int, in_bytes: int):
     reps = int(min(200, max(6, 1.0e-3 / (out_bytes * (1 + in_bytes / 4) / 6.0e12))))
     best = None
     for v in STREAM_VARIANTS:
-        if in_bytes == 0 and (v & 0x100):
+        if in_bytes == 0 and (v & 0x1900):
             continue
         ms = timed_mean(lambda i: tcuscan.measure_stream(d_ins[i % pairs], d_outs[i % pairs], out_bytes, in_bytes, v), reps, 2)
         if best is None or ms < best[0]:

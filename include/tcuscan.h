@@ -244,7 +244,10 @@ int tcuscan_path_for(const void *d_in, size_t rows, size_t cols, tcuscan_dtype_t
  * 32-bit inputs with 32-bit outputs.  Both pointers 16-byte aligned.  variant: bits 0-2 = log2 of the 16-byte loads
  * (write-only: stores) each lane has in flight (1, 2, 4, 8, 16, 32), bit 8 = non-temporal loads, bit 9 = every wavefront reads
  * a run of consecutive KiB (a scan tile's shape) instead of interleaving with its workgroup's other wavefronts, bit 10 =
- * a grid of 2048 workgroups that walk over the data instead of one workgroup per chunk; a caller takes the best of them.
+ * a grid of 2048 workgroups that walk over the data instead of one workgroup per chunk, bits 11-12 = a pause between
+ * the arrival of a chunk's loads and its stores (0: none, 1: 512 cycles, 2: 2048 cycles; with 1 or 2 loads per lane
+ * and an input only) -- a scan computes between its loads and its stores, and a kernel that stores the moment its
+ * loads land is not the fastest streaming kernel; a caller takes the best of them.
  * 128-bit loads, non-temporal 128-bit stores, 1 KiB per wavefront and instruction, no dependencies.  The output is a
  * function of the input that nobody needs.
  */

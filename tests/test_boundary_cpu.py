@@ -200,7 +200,10 @@ def test_chain_knobs_static_entry_and_stream_kernel_reject_bad_arguments():
     assert call("tcuscan_measure_stream", FAKE, FAKE, 64, 3, 0, 0) == tcuscan.ERR_INVALID_ARG
     assert call("tcuscan_measure_stream", FAKE, FAKE, 64, 1, 6, 0) == tcuscan.ERR_INVALID_ARG
     assert call("tcuscan_measure_stream", FAKE, FAKE, 64, 1, 8, 0) == tcuscan.ERR_INVALID_ARG
-    assert call("tcuscan_measure_stream", FAKE, FAKE, 64, 1, 0x800, 0) == tcuscan.ERR_INVALID_ARG
+    assert call("tcuscan_measure_stream", FAKE, FAKE, 64, 1, 0x2000, 0) == tcuscan.ERR_INVALID_ARG
+    assert call("tcuscan_measure_stream", FAKE, FAKE, 64, 1, 0x1800, 0) == tcuscan.ERR_INVALID_ARG      # pause: 0, 1 or 2
+    assert call("tcuscan_measure_stream", FAKE, FAKE, 64, 1, 0x802, 0) == tcuscan.ERR_INVALID_ARG       # ... with 1 or 2 loads per lane
+    assert call("tcuscan_measure_stream", FAKE, FAKE, 64, 0, 0x800, 0) == tcuscan.ERR_INVALID_ARG       # ... and an input
     assert call("tcuscan_measure_stream", FAKE, FAKE + 4, 64, 1, 0, 0) == tcuscan.ERR_INVALID_ARG
     assert call("tcuscan_measure_stream", 0, FAKE, 64, 2, 0, 0) == tcuscan.ERR_INVALID_ARG
     assert call("tcuscan_measure_stream", FAKE, FAKE, 48, 4, 0, 0) == tcuscan.ERR_INVALID_ARG

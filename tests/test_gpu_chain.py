@@ -207,7 +207,8 @@ def test_streaming_yardstick_writes_what_it_says(mix):
     n_out = out_bytes // 16
     x = np.arange(4 * (n_out // max(R, 1)), dtype=np.uint32) * 7 + 1
     d_in = torch.from_numpy(x.view(np.int32)).cuda()
-    for variant in (0, 1, 2, 3, 0x100, 0x103, 0x200, 0x203, 0x302, 0x401, 0x703, 0x204, 0x205, 0x705):
+    pauses = (0x800, 0x1001, 0x900, 0x1300) if mix else ()          # a pause between loads and stores: kernels with input only
+    for variant in (0, 1, 2, 3, 0x100, 0x103, 0x200, 0x203, 0x302, 0x401, 0x703, 0x204, 0x205, 0x705) + pauses:
         d_out = torch.full((n_out * 4 + 64,), -1, dtype=torch.int32, device="cuda")
         tcuscan.measure_stream(d_in, d_out, out_bytes, mix, variant)
         torch.cuda.synchronize()
