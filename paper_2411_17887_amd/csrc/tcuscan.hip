@@ -2069,7 +2069,26 @@ __global__ __launch_bounds__(kThreads) void scan_rows_kernel(Params P)
     if (row >= P.rows) return;
     u32x4 g[NT];
     const typename T::AConst Aop = T::make(lane, EXCL, REV);
-    if constexpr (!LEAD) {
+    if constexpr (!LEAD && NT == 2 && T::kEsz != 2) {
+        // Two MFMA tiles of 8- or 32-bit elements: one after the other, the first one's total as the second one's
+        // carry.  With one KiB per wavefront in flight at a time the memory system does better than with both tiles
+        // loaded at once (131072 x 2048 int8 rows 238 -> 215 us, 174762 x 1536 int8 240 -> 225, 524288 x 512 f32 342 ->
+        // 331); 16-bit rows gain or lose a per cent or two (262144 x 1024 bf16 260 -> 257, 262144 x 1000 f16 287 -> 295)
+        // and keep the plain form, and from three tiles on it is the other way round (174762 x 1536 f16 266 -> 276).
+        A carry = acc_from_bits<A>(0u);
+        const typename T::AConst Atot = T::make(lane, false, false);
+#pragma unroll 1
+        for (int k = 0; k < 2; ++k) {
+            const uint64_t base = (uint64_t)(REV ? 1 - k : k) * Geo<DT>::kTileElems;     // a reverse scan starts with the last tile
+            if (base >= P.cols) continue;
+            const Run R1 = make_run<DT>(P, row, base);
+            u32x4 g1[1];
+            load_run<DT, 1, REV>(R1, lane, g1);
+            const A total = k == 0 ? reduce_run<DT, 1>(lane, Atot, g1) : acc_from_bits<A>(0u);
+            scan_and_store<DT, 1, EXCL, REV>(lane, Aop, R1, g1, carry);
+            carry = total;
+        }
+    } else if constexpr (!LEAD) {
         const Run R = make_run<DT>(P, row, 0);
         load_run<DT, NT, REV>(R, lane, g);
         scan_and_store<DT, NT, EXCL, REV>(lane, Aop, R, g, acc_from_bits<A>(0u));
