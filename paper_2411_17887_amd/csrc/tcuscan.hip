@@ -2218,6 +2218,7 @@ __global__ void fill_zero_kernel(uint32_t *p, size_t words, uint32_t *p2, size_t
 constexpr size_t kSmallTile = 8192;                      // elements per workgroup tile, small variant (all dtypes)
 constexpr size_t kShortRowMax = 2048;                    // rows up to this length can be scanned one per wavefront
 constexpr size_t kShortRowMax32 = 2816;                  // ... 32-bit inputs: up to 11 of their 256-element MFMA tiles
+constexpr size_t kShortRowMax8 = 2560;                   // ... 8-bit inputs: two and a half of their 1024-element MFMA tiles
 constexpr size_t kShortRowMinRows = 8;                   // ... when there are enough of them to fill wavefronts
 
 bool valid_dtype(int dt) { return dt >= 0 && dt <= 4; }
@@ -2341,9 +2342,10 @@ template <int DT> hipError_t launch_dt(Params P, bool excl, int size, hipStream_
 {
     // 32-bit rows a little longer than 2048 still do better one per wavefront (12 MFMA tiles, partly masked) than in a
     // workgroup tile of 8192 that is a quarter full: measured 2100 / 2304 / 2560 columns 70 / 76 / 76 % of peak against
-    // 50 / 61 / 69 %, equal at 2816, and the workgroup tile ahead from there (3000: 73.5 % against 70 %); for 8- and
-    // 16-bit inputs the workgroup tile is ahead everywhere above 2048.
-    const size_t row_max = Tr<DT>::kEsz == 4 ? kShortRowMax32 : kShortRowMax;
+    // 50 / 61 / 69 %, equal at 2816, and the workgroup tile ahead from there (3000: 73.5 % against 70 %); 8-bit rows of
+    // 2304 / 2560 elements likewise (237 us for 2^28 elements against 305 / 253; from 2816 on the workgroup tile is
+    // ahead, 223 against 239); for 16-bit inputs the workgroup tile is ahead everywhere above 2048.
+    const size_t row_max = Tr<DT>::kEsz == 4 ? kShortRowMax32 : Tr<DT>::kEsz == 1 ? kShortRowMax8 : kShortRowMax;
     if (P.rows >= kShortRowMinRows && P.cols <= row_max) return launch_rows<DT>(P, excl, s);
     // hipLaunchKernel reports this launch's own status (hipGetLastError could return a stale,
     // unrelated code left behind by another library's polling calls).
@@ -2587,7 +2589,7 @@ tcuscan_status_t run_segmented_flat(const void *d_in, void *d_out, const long lo
 Plan plan_for(uintptr_t in_addr, size_t rows, size_t cols, int dt, bool ws_usable, size_t ws_bytes)
 {
     Plan plan = {TCUSCAN_PATH_TILES, kSegSmall, 0, 0};
-    const size_t row_max = in_size(dt) == 4 ? kShortRowMax32 : kShortRowMax;
+    const size_t row_max = in_size(dt) == 4 ? kShortRowMax32 : in_size(dt) == 1 ? kShortRowMax8 : kShortRowMax;
     if (rows >= kShortRowMinRows && cols <= row_max) { plan.path = TCUSCAN_PATH_ROWS; return plan; }
     if ((in_addr & 15) == 0 && (rows <= 1 || (cols * in_size(dt)) % 16 == 0)) return plan;       // every row starts at a 16-byte boundary
     // the tile the row-length rule picks, or the other one if the workspace only has the status words for that

@@ -153,7 +153,7 @@ def test_batched_shapes(kind, rows, cols):
 
 @pytest.mark.parametrize("kind", KINDS)
 @pytest.mark.parametrize("rows,cols", [(4096, 256), (1000, 1024), (513, 2048), (77, 2047), (9, 1), (100, 300), (8, 2048),
-                                       (4099, 64), (33, 513), (65537, 16), (50, 2815), (31, 2600), (12, 2816), (9, 2817), (64, 512), (30, 1536)])
+                                       (4099, 64), (33, 513), (65537, 16), (50, 2815), (31, 2600), (12, 2816), (9, 2817), (64, 512), (30, 1536), (21, 2304), (19, 2560), (17, 2561)])
 def test_short_rows_one_per_wavefront(kind, rows, cols):
     """Many short rows (histogram-like shapes): each wavefront scans whole rows; includes row lengths that
     leave rows unaligned, a ragged last workgroup and exclusive scans."""

@@ -62,7 +62,7 @@ def test_edge_sizes(kind, excl):
 
 @pytest.mark.parametrize("kind", KINDS)
 @pytest.mark.parametrize("rows,cols", [(7, 333), (3, 8192), (5, 8193), (64, 20000), (33, 16385), (1000, 16), (2, 70001),
-                                       (4096, 256), (513, 2048), (77, 2047), (100, 300), (50, 2815), (31, 2600), (64, 512), (30, 1536)])
+                                       (4096, 256), (513, 2048), (77, 2047), (100, 300), (50, 2815), (31, 2600), (64, 512), (30, 1536), (19, 2560), (17, 2561)])
 def test_batched_shapes_including_short_rows_and_unaligned_rows(kind, rows, cols):
     run_and_check(kind, rows, cols, False, 900 + rows + cols, random_floats=False)
     run_and_check(kind, rows, cols, True, 901 + rows + cols)
