@@ -156,3 +156,54 @@ def test_sort_random_sizes_bits_and_forms():
             assert payload is None or np.array_equal(gv, payload[order]), f"case {case}: payloads"
     finally:
         tcuscan.set_sort_fusion(1)
+
+
+def test_graph_capture_of_compaction_and_sort(sort_form):
+    """A fused compaction and a sort with payloads recorded into one graph; replays with new data, with eager calls on
+    the same workspaces in between, must match the stable reference every time (recorded calls clear their status
+    words with fill kernels, and the fused kernels' look-back polls words of the same replay only)."""
+    import torch
+    n, m = (1 << 20) + 333, (1 << 19) + 77
+    d_v = torch.zeros(n, dtype=torch.int32, device="cuda")
+    d_m = torch.zeros(n, dtype=torch.int8, device="cuda")
+    d_out = torch.empty(n + 2, dtype=torch.int32, device="cuda")
+    d_cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    d_k, d_p = torch.zeros(m, dtype=torch.int32, device="cuda"), torch.zeros(m, dtype=torch.int32, device="cuda")
+    d_kt, d_pt = torch.empty_like(d_k), torch.empty_like(d_p)
+    d_f, d_pos = torch.empty(m, dtype=torch.int8, device="cuda"), torch.empty(m, dtype=torch.int32, device="cuda")
+    ws_c, ws_s = tcuscan.new_workspace(1, n, "i8"), tcuscan.new_workspace(1, m, "i8")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                                             # warm-up outside capture
+        tcuscan.compact_u32(d_v, d_m, d_out, None, count=d_cnt, ws=ws_c, stream=side)
+        tcuscan.split_radix_sort_u32(d_k, d_kt, d_f, d_pos, vals=d_p, vals_tmp=d_pt, bits=32, ws=ws_s, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        tcuscan.compact_u32(d_v, d_m, d_out, None, count=d_cnt, ws=ws_c, stream=side)
+        tcuscan.split_radix_sort_u32(d_k, d_kt, d_f, d_pos, vals=d_p, vals_tmp=d_pt, bits=32, ws=ws_s, stream=side)
+    for rep in range(3):
+        v, msk = keys_u32(n, 70 + rep), inputs.mask_i8(n, 80 + rep)
+        k = keys_u32(m, 90 + rep) & np.uint32(0xFFFF if rep == 1 else 0xFFFFFFFF)      # once with many equal keys
+        d_v.copy_(torch.from_numpy(v.view(np.int32)).cuda()); d_m.copy_(torch.from_numpy(msk).cuda())
+        d_k.copy_(torch.from_numpy(k.view(np.int32)).cuda()); d_p.copy_(torch.arange(m, dtype=torch.int32, device="cuda"))
+        d_out.fill_(-5)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        ref = v[msk != 0]
+        cnt = int(d_cnt.item())
+        out = d_out.cpu().numpy()
+        assert cnt == ref.size and np.array_equal(out[:cnt].view(np.uint32), ref) and np.all(out[cnt:] == -5), f"replay {rep}: compaction"
+        order = np.argsort(k, kind="stable")
+        assert np.array_equal(d_k.cpu().numpy().view(np.uint32), k[order]), f"replay {rep}: keys"
+        assert np.array_equal(d_p.cpu().numpy().view(np.uint32), order.astype(np.uint32)), f"replay {rep}: payloads"
+        # eager calls on the same workspaces between the replays
+        got, _, c = gpu_compact(v[: 100001], msk[: 100001], fused=True)
+        assert c == int((msk[: 100001] != 0).sum()) and np.array_equal(got, v[: 100001][msk[: 100001] != 0])
+        d_k.copy_(torch.from_numpy(k.view(np.int32)).cuda())
+        tcuscan.split_radix_sort_u32(d_k, d_kt, d_f, d_pos, bits=32, ws=ws_s)
+        torch.cuda.synchronize()
+        assert np.array_equal(d_k.cpu().numpy().view(np.uint32), np.sort(k))
+    assert tcuscan.workspace_fault(ws_c) == 0 and tcuscan.workspace_fault(ws_s) == 0
