@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the MatMulScan hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C5] [--no-others] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C5] [--no-others] [--no-cpu] [--apps-only]
 
 A step is one pass of the whole hot path (tile load, MFMA local scans, in-workgroup up-sweep,
 carry chain between workgroups, down-sweep add, store) over one batch of seeded synthetic
@@ -577,6 +577,8 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--copy-only", action="store_true",
                     help="run only the plain 1 GiB device copy (calibrates the HBM byte counters of rocprofv3 --pmc)")
+    ap.add_argument("--apps-only", action="store_true",
+                    help="run only the compaction and split-radix-sort measurements (for rocprofv3 counter passes over their kernels)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (the scan shards with one 8-byte exchange per GPU, "
@@ -589,6 +591,10 @@ def main() -> int:
     tcuscan.load()
     if args.copy_only:
         print(json.dumps({"copy_GBps": copy_ceiling_gbps(), "bytes_read": 1 << 30, "bytes_written": 1 << 30}))
+        return 0
+
+    if args.apps_only:
+        print(json.dumps(measure_apps(8)))
         return 0
 
     head, x, last = measure(args.workload, args.steps, args.warmup, keep_host=not args.no_cpu)
