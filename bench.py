@@ -55,9 +55,9 @@ DESCR = {
 # 1 GiB device copy; the table and the commands are in TRAFFIC_SOURCE.  The figures belong to the kernels they were
 # measured on: TRAFFIC_KERNEL_SHA is the hash of the kernel source at that time, and a run on any other source
 # reports `traffic: null` instead of a stale number.
-MEASURED_TRAFFIC_BYTES = {"C5": 1627170448, "C3": 1358195824, "C4": 805128378, "C2": 101636413}
+MEASURED_TRAFFIC_BYTES = {"C5": 1626986407, "C3": 1358250200, "C4": 805081780, "C2": 101634492}
 TRAFFIC_SOURCE = "profiles/scan_kernel_bench_default.md"
-TRAFFIC_KERNEL_SHA = "d46fa78b6a0f60bf"
+TRAFFIC_KERNEL_SHA = "07d2bc2ca91d1b91"
 KERNEL_SOURCE = os.path.join(ROOT, "paper_2411_17887_amd", "csrc", "tcuscan.hip")
 
 
